@@ -1,0 +1,186 @@
+/*
+ * infllmv2.h -- C ABI of the MI355X (gfx950) implementation of InfLLM-V2's
+ * dense-sparse switchable attention (arXiv 2509.24663).
+ *
+ * The path has four stages (Sec. 3.2-3.4 of the paper):
+ *   1. infllmv2_compress_k      mean-pool keys into compressed keys K^{C1}            (Eq. 3)
+ *   2. infllmv2_block_scores    softmax(scale * Q K^{C1 T}) summed over the GQA group (Eq. 4, 5, Alg. 1)
+ *   3. infllmv2_topk_blocks     max-pool to selection blocks, keep init + local,
+ *                               top-k of the rest                                     (Eq. 6, Eq. 2)
+ *   4. infllmv2_sparse_attn_fwd causal attention over the selected 64-token blocks of
+ *                               the shared K/V (Appendix Alg. 2), dense below the
+ *                               length threshold (Sec. 3.2, "switch")
+ *      infllmv2_dense_attn_fwd  causal GQA attention                                  (Eq. 1, Appendix Alg. 3)
+ *      infllmv2_sparse_decode   stages 2-4 for the one newest token of each sequence
+ *                               against K/V and K^{C1} caches
+ *
+ * General rules
+ *   - Every pointer named *_d or documented "device" is GPU memory on the current
+ *     HIP device; pointers named *_h are host memory and are only read during the
+ *     call.  The library allocates nothing, keeps no state and never synchronises:
+ *     all work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  The caller owns every buffer and keeps it alive until the
+ *     stream work has finished.  Calls are thread-safe.
+ *   - All indices are 0-based.  Token t of a sequence lies in block t / block_size.
+ *     Sequences are packed along the token axis; cu_seqlens has batch+1 int32
+ *     entries (cu_seqlens[0] = 0, non-decreasing) and is passed twice: as a host
+ *     array (launch geometry, validation) and as a device array (read by kernels).
+ *   - Q and O are token-major [total_tokens, num_q_heads, head_dim], contiguous.
+ *     Query head g belongs to KV head g / (num_q_heads / num_kv_heads).
+ *     K and V are addressed as  base + token * kv_tok_stride + kv_head * kv_head_stride
+ *     (strides in elements, head_dim contiguous), so both token-major
+ *     [T, hkv, d] and head-major [hkv, T, d] work; head-major keeps a 64-token
+ *     block in one contiguous 16 KB run and is the fast layout.
+ *   - dtype selects the element type of Q, K, V, O only.  K^{C1}, scores and lse
+ *     are always float32; block indices are int32.
+ *   - A call with zero total tokens (or batch 0) is a no-op that returns INFLLMV2_OK; data pointers may
+ *     then be NULL.
+ *   - Return value: INFLLMV2_OK (0) or a negative infllmv2_status.  Arguments are
+ *     validated before anything is launched (so validation errors can be tested
+ *     without a GPU); a launch failure is reported as INFLLMV2_ERR_HIP.  No
+ *     exception crosses this boundary and nothing aborts.
+ */
+#ifndef INFLLMV2_H
+#define INFLLMV2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define INFLLMV2_FP32 0
+#define INFLLMV2_BF16 1
+
+typedef enum infllmv2_status {
+    INFLLMV2_OK = 0,
+    INFLLMV2_ERR_INVALID_ARGUMENT = -1,   /* null pointer, inconsistent sizes, bad cu_seqlens ...      */
+    INFLLMV2_ERR_UNSUPPORTED = -2,        /* dtype / head_dim / parameter combination not implemented   */
+    INFLLMV2_ERR_WORKSPACE_TOO_SMALL = -3,
+    INFLLMV2_ERR_HIP = -4                 /* a HIP call or kernel launch failed                          */
+} infllmv2_status;
+
+/* Hyper-parameters in the paper's notation (Sec. 3.2, 3.3; values of Sec. 4.1 in brackets). */
+typedef struct infllmv2_params {
+    int32_t dtype;            /* INFLLMV2_FP32 or INFLLMV2_BF16: element type of Q, K, V, O                */
+    int32_t num_q_heads;      /* h_q  [32]                                                                 */
+    int32_t num_kv_heads;     /* h_kv [2]; h_q % h_kv == 0, G = h_q / h_kv <= 16                           */
+    int32_t head_dim;         /* d_h  [128]; 64 or 128                                                     */
+    int32_t block_size;       /* B    [64]; must be 64                                                     */
+    int32_t cmp_len;          /* l_C1 [32]                                                                 */
+    int32_t cmp_stride;       /* s_C1 [16]; 1 <= s_C1 <= l_C1                                              */
+    int32_t pool_len;         /* l    [5]                                                                  */
+    int32_t pool_stride;      /* s    [4]                                                                  */
+    int32_t pool_pad;         /* 0: block j pools compressed keys [s*j, s*j+l) as printed in Eq. 6;
+                                 p > 0 shifts the window to [s*j-p, s*j-p+l)                               */
+    int32_t n_init;           /* |I_init|  [1]                                                             */
+    int32_t n_local;          /* |I_local| [32]; >= 1 (the query's own block is always kept)               */
+    int32_t topk_total;       /* |I|       [96]; n_init + n_local <= topk_total <= 1024                    */
+    int32_t dense_threshold;  /* sequences with fewer tokens than this run dense attention                 */
+    float   softmax_scale;    /* multiplies the logits in stage 2 and in attention; 1/sqrt(d_h)            */
+    int32_t lse_mode;         /* 0: exact two-pass normalisation of stage 2 (the only mode implemented)    */
+} infllmv2_params;
+
+/* Number of compressed keys of a sequence of n tokens: complete windows only,
+ * nc(n) = n < l_C1 ? 0 : (n - l_C1) / s_C1 + 1.  Host helper, no GPU needed. */
+int32_t infllmv2_num_cmp(const infllmv2_params *p, int32_t n);
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char *infllmv2_status_string(int status);
+
+/* Library version string, e.g. "infllmv2-gfx950 0.1". */
+const char *infllmv2_version(void);
+
+/*
+ * Stage 1 -- Sec. 3.3, Eq. 3:  K^{C1}_i = Mean(K[i*s_C1 : i*s_C1 + l_C1]) per sequence and KV head.
+ *   k              device, dtype elements, addressed with the K/V strides
+ *   cu_seqlens_h/d host / device [batch+1]
+ *   kc_d           device out, float32 [num_kv_heads, total_c, head_dim] where
+ *                  total_c = sum over sequences of nc(len); sequence s starts at row cu_seqlens_c[s]
+ *   cu_seqlens_c_d device out, int32 [batch+1], prefix sums of nc(len)
+ *   total_c        rows allocated per head in kc_d (>= the sum above, else INVALID_ARGUMENT)
+ */
+int infllmv2_compress_k(const infllmv2_params *p, const void *k_d, int64_t kv_tok_stride, int64_t kv_head_stride,
+                        const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
+                        float *kc_d, int32_t *cu_seqlens_c_d, int64_t total_c, void *stream);
+
+/*
+ * Stage 2 -- Sec. 3.3 Eq. 4-5, computed as in Alg. 1 (two passes, head-group sum on chip):
+ *   for token t (position within its sequence) and KV head h, over the v(t) compressed keys whose
+ *   window ends at or before t (v(t) = t < l_C1-1 ? 0 : (t-l_C1+1)/s_C1 + 1):
+ *       S^shared[h, t, i] = sum over the G heads g of group h of softmax_i(scale * <Q[t,g], K^{C1}[h,i]>)
+ *   q_d            device [total_tokens, num_q_heads, head_dim]
+ *   kc_d, cu_seqlens_c_d   as written by infllmv2_compress_k
+ *   s_shared_d     device out float32 [num_kv_heads, total_tokens, row_stride]; entries i < v(t) are
+ *                  written, the rest of each row is left untouched.  row_stride >= max over sequences
+ *                  of nc(len) and a multiple of 4.
+ *   Per-head score matrices never reach HBM; only the group sums are stored.
+ */
+int infllmv2_block_scores(const infllmv2_params *p, const void *q_d, const float *kc_d, int64_t total_c,
+                          const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d,
+                          const int32_t *cu_seqlens_c_d, int32_t batch,
+                          float *s_shared_d, int64_t row_stride, void *stream);
+
+/*
+ * Stage 3 -- Sec. 3.3 Eq. 6 then Sec. 3.2 Eq. 2, per token t (block b_t = t / B) and KV head:
+ *   S^cmp_j = max S^shared[s*j - pad : s*j - pad + l] clipped to the v(t) visible keys (empty -> 0), j <= b_t
+ *   forced  = {0..n_init-1} U {b_t-n_local+1..b_t}, clipped to [0, b_t]
+ *   top-k   = the min(topk_total - n_init - n_local, #others) other blocks with the largest S^cmp,
+ *             equal scores resolved towards the smaller block index
+ *   block_idx_d    device out int32 [num_kv_heads, total_tokens, topk_total]: the union, ascending,
+ *                  padded with -1.
+ */
+int infllmv2_topk_blocks(const infllmv2_params *p, const float *s_shared_d, int64_t row_stride,
+                         const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
+                         int32_t *block_idx_d, void *stream);
+
+/*
+ * Stage 4 -- Appendix Alg. 2: token t attends, with one softmax per query head, to the keys u <= t
+ * whose block u / B is listed in block_idx[h, t, :]; O = softmax(scale * q K^T) V.
+ * Sequences shorter than dense_threshold ignore block_idx and attend to every u <= t (Sec. 3.2).
+ *   block_idx_d    device int32 [num_kv_heads, total_tokens, topk_total] (entries must be valid block
+ *                  numbers <= b_t or -1; as produced by infllmv2_topk_blocks)
+ *   out_d          device out, dtype [total_tokens, num_q_heads, head_dim]
+ *   lse_d          device out float32 [num_q_heads, total_tokens]: ln sum_u exp(scale * <q, k_u>); may be NULL
+ */
+int infllmv2_sparse_attn_fwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
+                             int64_t kv_tok_stride, int64_t kv_head_stride, const int32_t *block_idx_d,
+                             const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
+                             void *out_d, float *lse_d, void *stream);
+
+/* Dense causal GQA attention -- Eq. 1 (tile schedule of Appendix Alg. 3).  Arguments as above. */
+int infllmv2_dense_attn_fwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
+                            int64_t kv_tok_stride, int64_t kv_head_stride,
+                            const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
+                            void *out_d, float *lse_d, void *stream);
+
+/*
+ * Decode step -- stages 2-4 for the single query row t = ctx_len-1 of every sequence (the paper
+ * states decode support, Sec. 2.2 / 4.3, without a separate algorithm; it is that row of the prefill).
+ *   q_d            device [batch, num_q_heads, head_dim]
+ *   k_cache_d, v_cache_d   device, element (b, h, t, c) at
+ *                  base + b*kv_batch_stride + h*kv_head_stride + t*kv_tok_stride + c; the newest
+ *                  token's K/V are already stored at t = ctx_len-1
+ *   kc_cache_d     device float32, row i of (b, h) at base + (b*num_kv_heads + h)*kc_head_stride + i*head_dim;
+ *                  holds at least nc(ctx_len) rows
+ *   ctx_lens_h/d   host / device int32 [batch], each >= 1
+ *   block_idx_out_d device out int32 [batch, num_kv_heads, topk_total] or NULL
+ *   out_d          device out dtype [batch, num_q_heads, head_dim];  lse_d float32 [batch, num_q_heads] or NULL
+ *   workspace_d    device scratch of at least infllmv2_decode_workspace_bytes(...) bytes, 256-byte aligned
+ * Sequences shorter than dense_threshold attend densely.
+ */
+int infllmv2_sparse_decode(const infllmv2_params *p, const void *q_d, const void *k_cache_d, const void *v_cache_d,
+                           int64_t kv_batch_stride, int64_t kv_head_stride, int64_t kv_tok_stride,
+                           const float *kc_cache_d, int64_t kc_head_stride,
+                           const int32_t *ctx_lens_h, const int32_t *ctx_lens_d, int32_t batch,
+                           int32_t *block_idx_out_d, void *out_d, float *lse_d,
+                           void *workspace_d, size_t workspace_bytes, void *stream);
+
+/* Bytes of scratch infllmv2_sparse_decode needs for `batch` sequences of at most max_ctx_len tokens. */
+size_t infllmv2_decode_workspace_bytes(const infllmv2_params *p, int32_t batch, int32_t max_ctx_len);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INFLLMV2_H */

@@ -1,0 +1,237 @@
+"""ctypes binding of libinfllmv2.so: argument marshalling only, one function per C entry point."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libinfllmv2.so")
+
+FP32, BF16 = 0, 1
+
+
+class InfllmV2Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class Params(ctypes.Structure):
+    """Mirror of `infllmv2_params` (paper notation: Sec. 3.2, 3.3, 4.1)."""
+
+    _fields_ = [
+        ("dtype", ctypes.c_int32), ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32), ("cmp_len", ctypes.c_int32),
+        ("cmp_stride", ctypes.c_int32), ("pool_len", ctypes.c_int32), ("pool_stride", ctypes.c_int32),
+        ("pool_pad", ctypes.c_int32), ("n_init", ctypes.c_int32), ("n_local", ctypes.c_int32),
+        ("topk_total", ctypes.c_int32), ("dense_threshold", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+        ("lse_mode", ctypes.c_int32),
+    ]
+
+    @staticmethod
+    def make(dtype: str, num_q_heads: int, num_kv_heads: int, head_dim: int, *, block_size=64, cmp_len=32,
+             cmp_stride=16, pool_len=5, pool_stride=4, pool_pad=0, n_init=1, n_local=8, topk_total=64,
+             dense_threshold=0, softmax_scale: Optional[float] = None, lse_mode=0) -> "Params":
+        scale = float(head_dim) ** -0.5 if softmax_scale is None else float(softmax_scale)
+        return Params({"fp32": FP32, "bf16": BF16}[dtype], num_q_heads, num_kv_heads, head_dim, block_size, cmp_len,
+                      cmp_stride, pool_len, pool_stride, pool_pad, n_init, n_local, topk_total, dense_threshold,
+                      scale, lse_mode)
+
+    @staticmethod
+    def from_config(cfg, **over) -> "Params":
+        kw = dict(block_size=cfg.block_size, cmp_len=cfg.cmp_len, cmp_stride=cfg.cmp_stride,
+                  pool_len=cfg.pool_len, pool_stride=cfg.pool_stride, pool_pad=cfg.pool_pad, n_init=cfg.n_init,
+                  n_local=cfg.n_local, topk_total=cfg.topk_total, dense_threshold=cfg.dense_threshold,
+                  softmax_scale=cfg.softmax_scale)
+        kw.update(over)
+        return Params.make(cfg.dtype, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, **kw)
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == BF16 else torch.float32
+
+
+_lib = None
+_P = ctypes.c_void_p
+_I32, _I64, _SZ = ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+_PP = ctypes.POINTER(Params)
+
+_SIGNATURES = {
+    "infllmv2_num_cmp": (_I32, [_PP, _I32]),
+    "infllmv2_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "infllmv2_version": (ctypes.c_char_p, []),
+    "infllmv2_compress_k": (ctypes.c_int, [_PP, _P, _I64, _I64, _P, _P, _I32, _P, _P, _I64, _P]),
+    "infllmv2_block_scores": (ctypes.c_int, [_PP, _P, _P, _I64, _P, _P, _P, _I32, _P, _I64, _P]),
+    "infllmv2_topk_blocks": (ctypes.c_int, [_PP, _P, _I64, _P, _P, _I32, _P, _P]),
+    "infllmv2_sparse_attn_fwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _P, _I32, _P, _P, _P]),
+    "infllmv2_dense_attn_fwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _I32, _P, _P, _P]),
+    "infllmv2_sparse_decode": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _I64, _P, _I64, _P, _P, _I32, _P, _P, _P,
+                                              _P, _SZ, _P]),
+    "infllmv2_decode_workspace_bytes": (_SZ, [_PP, _I32, _I32]),
+}
+
+
+def lib() -> ctypes.CDLL:
+    """Load libinfllmv2.so (no fallback: a missing library is an error)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(or python paper_2509_24663_amd/build.py) first; there is no CPU fallback")
+        L = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def exported_symbols() -> Sequence[str]:
+    return tuple(_SIGNATURES)
+
+
+def status_string(status: int) -> str:
+    return lib().infllmv2_status_string(int(status)).decode()
+
+
+def version() -> str:
+    return lib().infllmv2_version().decode()
+
+
+def num_cmp(p: Params, n: int) -> int:
+    return int(lib().infllmv2_num_cmp(ctypes.byref(p), int(n)))
+
+
+def _check(st: int, where: str):
+    if st != 0:
+        raise InfllmV2Error(st, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _cu_pair(cu_seqlens):
+    """host int32 numpy-backed tensor + device copy"""
+    cu_h = torch.as_tensor(cu_seqlens, dtype=torch.int32, device="cpu").contiguous()
+    return cu_h, cu_h.cuda()
+
+
+def _kv_strides(k: torch.Tensor):
+    """k is [hkv, T, d] (head-major) or any view with d contiguous: returns (tok_stride, head_stride)."""
+    assert k.dim() == 3 and k.stride(2) == 1
+    return k.stride(1), k.stride(0)
+
+
+# ---------------------------------------------------------------------------------- stage wrappers
+def compress_k(p: Params, k: torch.Tensor, cu_seqlens):
+    """Stage 1.  k [hkv, T, d] (device).  Returns kc [hkv, total_c, d] fp32, cu_seqlens_c (device int32)."""
+    cu_h, cu_d = _cu_pair(cu_seqlens)
+    batch = cu_h.numel() - 1
+    lens = (cu_h[1:] - cu_h[:-1]).tolist()
+    total_c = sum(num_cmp(p, n) for n in lens)
+    kc = torch.empty((p.num_kv_heads, max(total_c, 1), p.head_dim), dtype=torch.float32, device=k.device)
+    cu_c = torch.empty(batch + 1, dtype=torch.int32, device=k.device)
+    ts, hs = _kv_strides(k)
+    st = lib().infllmv2_compress_k(ctypes.byref(p), _ptr(k), ts, hs, _ptr(cu_h), _ptr(cu_d), batch, _ptr(kc),
+                                   _ptr(cu_c), kc.shape[1], _stream())
+    _check(st, "infllmv2_compress_k")
+    return kc, cu_c
+
+
+def block_scores(p: Params, q: torch.Tensor, kc: torch.Tensor, cu_seqlens, cu_seqlens_c: torch.Tensor,
+                 out: Optional[torch.Tensor] = None):
+    """Stage 2.  q [T, hq, d]; returns S^shared [hkv, T, row_stride] fp32 (entries beyond v(t) unspecified)."""
+    cu_h, cu_d = _cu_pair(cu_seqlens)
+    batch = cu_h.numel() - 1
+    max_len = int((cu_h[1:] - cu_h[:-1]).max()) if batch else 0
+    rs = max(4, (num_cmp(p, max_len) + 3) // 4 * 4)
+    if out is None:
+        out = torch.zeros((p.num_kv_heads, q.shape[0], rs), dtype=torch.float32, device=q.device)
+    st = lib().infllmv2_block_scores(ctypes.byref(p), _ptr(q), _ptr(kc), kc.shape[1], _ptr(cu_h), _ptr(cu_d),
+                                     _ptr(cu_seqlens_c), batch, _ptr(out), out.shape[2], _stream())
+    _check(st, "infllmv2_block_scores")
+    return out
+
+
+def topk_blocks(p: Params, s_shared: torch.Tensor, cu_seqlens, out: Optional[torch.Tensor] = None):
+    """Stage 3.  s_shared [hkv, T, row_stride] -> block_idx [hkv, T, topk_total] int32."""
+    cu_h, cu_d = _cu_pair(cu_seqlens)
+    batch = cu_h.numel() - 1
+    if out is None:
+        out = torch.empty((p.num_kv_heads, s_shared.shape[1], p.topk_total), dtype=torch.int32, device=s_shared.device)
+    st = lib().infllmv2_topk_blocks(ctypes.byref(p), _ptr(s_shared), s_shared.shape[2], _ptr(cu_h), _ptr(cu_d), batch,
+                                    _ptr(out), _stream())
+    _check(st, "infllmv2_topk_blocks")
+    return out
+
+
+def sparse_attn_fwd(p: Params, q, k, v, block_idx, cu_seqlens, out=None, lse=None):
+    """Stage 4.  Returns (out [T, hq, d], lse [hq, T])."""
+    cu_h, cu_d = _cu_pair(cu_seqlens)
+    batch = cu_h.numel() - 1
+    out = torch.empty_like(q) if out is None else out
+    lse = torch.empty((p.num_q_heads, q.shape[0]), dtype=torch.float32, device=q.device) if lse is None else lse
+    ts, hs = _kv_strides(k)
+    assert _kv_strides(v) == (ts, hs)
+    st = lib().infllmv2_sparse_attn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), ts, hs, _ptr(block_idx),
+                                        _ptr(cu_h), _ptr(cu_d), batch, _ptr(out), _ptr(lse), _stream())
+    _check(st, "infllmv2_sparse_attn_fwd")
+    return out, lse
+
+
+def dense_attn_fwd(p: Params, q, k, v, cu_seqlens, out=None, lse=None):
+    """Dense causal GQA attention.  Returns (out [T, hq, d], lse [hq, T])."""
+    cu_h, cu_d = _cu_pair(cu_seqlens)
+    batch = cu_h.numel() - 1
+    out = torch.empty_like(q) if out is None else out
+    lse = torch.empty((p.num_q_heads, q.shape[0]), dtype=torch.float32, device=q.device) if lse is None else lse
+    ts, hs = _kv_strides(k)
+    assert _kv_strides(v) == (ts, hs)
+    st = lib().infllmv2_dense_attn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), ts, hs, _ptr(cu_h), _ptr(cu_d),
+                                       batch, _ptr(out), _ptr(lse), _stream())
+    _check(st, "infllmv2_dense_attn_fwd")
+    return out, lse
+
+
+def decode_workspace_bytes(p: Params, batch: int, max_ctx_len: int) -> int:
+    return int(lib().infllmv2_decode_workspace_bytes(ctypes.byref(p), int(batch), int(max_ctx_len)))
+
+
+def sparse_decode(p: Params, q, k_cache, v_cache, kc_cache, ctx_lens, workspace=None, return_idx=True):
+    """Decode step.  q [B, hq, d]; k_cache/v_cache [B, hkv, Lmax, d]; kc_cache [B, hkv, max_nc, d] fp32.
+    Returns (out [B, hq, d], lse [B, hq], block_idx [B, hkv, topk_total] or None)."""
+    ctx_h = torch.as_tensor(ctx_lens, dtype=torch.int32, device="cpu").contiguous()
+    ctx_d = ctx_h.cuda()
+    B = q.shape[0]
+    need = decode_workspace_bytes(p, B, int(ctx_h.max()) if B else 0)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    out = torch.empty_like(q)
+    lse = torch.empty((B, p.num_q_heads), dtype=torch.float32, device=q.device)
+    idx = torch.empty((B, p.num_kv_heads, p.topk_total), dtype=torch.int32, device=q.device) if return_idx else None
+    assert k_cache.dim() == 4 and k_cache.stride(3) == 1 and k_cache.stride() == v_cache.stride()
+    assert kc_cache.dim() == 4 and kc_cache.is_contiguous()
+    st = lib().infllmv2_sparse_decode(ctypes.byref(p), _ptr(q), _ptr(k_cache), _ptr(v_cache), k_cache.stride(0),
+                                      k_cache.stride(1), k_cache.stride(2), _ptr(kc_cache), kc_cache.stride(1),
+                                      _ptr(ctx_h), _ptr(ctx_d), B, _ptr(idx), _ptr(out), _ptr(lse),
+                                      _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "infllmv2_sparse_decode")
+    return out, lse, idx
+
+
+def sparse_prefill(p: Params, q, k, v, cu_seqlens):
+    """The four stages back to back (a convenience for tests and the benchmark; no arithmetic here).
+    Returns dict(out, lse, block_idx, s_shared, kc)."""
+    kc, cu_c = compress_k(p, k, cu_seqlens)
+    sh = block_scores(p, q, kc, cu_seqlens, cu_c)
+    idx = topk_blocks(p, sh, cu_seqlens)
+    out, lse = sparse_attn_fwd(p, q, k, v, idx, cu_seqlens)
+    return dict(out=out, lse=lse, block_idx=idx, s_shared=sh, kc=kc, cu_seqlens_c=cu_c)

@@ -1,0 +1,133 @@
+// Shared device/host helpers of the gfx950 InfLLM-V2 attention library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "infllmv2.h"
+
+namespace ifv2 {
+
+constexpr int kBlock = 64;      // selection block B (Sec. 3.2); the kernels are written for 64
+constexpr int kMaxGroup = 16;   // largest GQA group size G handled
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------- element types
+struct bf16_t { uint16_t bits; };
+
+__host__ __device__ inline float bf16_to_float(uint16_t b) {
+    union { uint32_t u; float f; } x;
+    x.u = (uint32_t)b << 16;
+    return x.f;
+}
+__host__ __device__ inline uint16_t float_to_bf16(float f) {   // round to nearest even
+    union { uint32_t u; float f; } x;
+    x.f = f;
+    if ((x.u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((x.u >> 16) | 0x40u);   // quiet NaN
+    uint32_t r = x.u + 0x7fffu + ((x.u >> 16) & 1u);
+    return (uint16_t)(r >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    __device__ static inline float load(const float *p) { return *p; }
+    __device__ static inline void store(float *p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+    __device__ static inline float load(const bf16_t *p) { return bf16_to_float(p->bits); }
+    __device__ static inline void store(bf16_t *p, float v) { p->bits = float_to_bf16(v); }
+};
+
+// ---------------------------------------------------------------- where a query row lives
+// Prefill: rows are packed tokens, sequences delimited by cu_seqlens.  Decode: row b is the
+// newest token of sequence b, whose caches start at b * kv_batch_stride.
+struct RowMap {
+    const int32_t *cu;        // prefill: [batch+1] token offsets;          decode: nullptr
+    const int32_t *cu_c;      // prefill: [batch+1] compressed-row offsets; decode: nullptr
+    const int32_t *ctx;       // decode: [batch] context lengths;           prefill: nullptr
+    int32_t batch;
+    int32_t total_rows;       // prefill: total tokens; decode: batch
+    int32_t num_kv_heads;
+    int64_t kv_tok_stride, kv_head_stride, kv_batch_stride;
+    int64_t kc_total_c;       // prefill: rows per head plane of kc
+    int64_t kc_head_stride;   // decode: elements between (b,h) planes of the kc cache
+};
+
+struct RowLoc {
+    int32_t seq, pos, len;    // sequence, position of the query inside it, sequence length
+    int64_t kv_base;          // element offset of (token 0, head 0) of that sequence in K / V
+};
+
+__device__ inline int find_seq(const int32_t *cu, int batch, int row) {
+    int lo = 0, hi = batch - 1;     // largest s with cu[s] <= row
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (cu[mid] <= row) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+__device__ inline RowLoc locate(const RowMap &m, int row) {
+    RowLoc r;
+    if (m.ctx) {
+        r.seq = row;
+        r.len = m.ctx[row];
+        r.pos = r.len - 1;
+        r.kv_base = (int64_t)row * m.kv_batch_stride;
+    } else {
+        r.seq = find_seq(m.cu, m.batch, row);
+        int a = m.cu[r.seq];
+        r.len = m.cu[r.seq + 1] - a;
+        r.pos = row - a;
+        r.kv_base = (int64_t)a * m.kv_tok_stride;
+    }
+    return r;
+}
+
+// first compressed key of (sequence, kv head) in the kc array, head_dim d
+__device__ inline const float *kc_base(const RowMap &m, const float *kc, int seq, int h, int d) {
+    if (m.ctx) return kc + ((int64_t)seq * m.num_kv_heads + h) * m.kc_head_stride;
+    return kc + ((int64_t)h * m.kc_total_c + m.cu_c[seq]) * d;
+}
+// flat index of (kv head h, row) in per-(head,row) outputs: [hkv, T, *] for prefill, [batch, hkv, *] for decode
+__device__ inline int64_t head_row(const RowMap &m, int h, int row) {
+    return m.ctx ? (int64_t)row * m.num_kv_heads + h : (int64_t)h * m.total_rows + row;
+}
+// flat index of (query head qh, row) in lse: [hq, T] for prefill, [batch, hq] for decode
+__device__ inline int64_t qhead_row(const RowMap &m, int qh, int hq, int row) {
+    return m.ctx ? (int64_t)row * hq + qh : (int64_t)qh * m.total_rows + row;
+}
+
+__host__ __device__ inline int num_cmp(int n, int lc, int sc) { return n < lc ? 0 : (n - lc) / sc + 1; }
+__host__ __device__ inline int visible_cmp(int t, int lc, int sc) { return t < lc - 1 ? 0 : (t - lc + 1) / sc + 1; }
+
+// ---------------------------------------------------------------- wave helpers
+__device__ inline float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// ---------------------------------------------------------------- launchers implemented per stage
+struct Launch {
+    const infllmv2_params *p;
+    RowMap map;
+    hipStream_t stream;
+    int32_t max_len;          // longest sequence (host knowledge, for grid sizing)
+};
+
+int launch_cu_c(const infllmv2_params *p, const int32_t *cu_d, int batch, int32_t *cu_c_d, hipStream_t s);
+int launch_compress_k(const Launch &L, const void *k, float *kc, int64_t total_c_rows);
+int launch_block_scores(const Launch &L, const void *q, const float *kc, float *s_shared, int64_t row_stride);
+int launch_topk(const Launch &L, const float *s_shared, int64_t row_stride, int32_t *idx);
+// idx == nullptr: dense for every sequence; dense_below: sequences shorter than this are dense anyway
+int launch_attn(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
+                int dense_below, void *out, float *lse, const int32_t *cu_h);
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? INFLLMV2_OK : INFLLMV2_ERR_HIP; }
+
+}  // namespace ifv2

@@ -11,7 +11,9 @@ from .generator import (  # noqa: F401
     CONFIGS,
     WorkloadConfig,
     bf16_bits,
+    draw_ctx_lens,
     from_bf16_bits,
+    make_config,
     make_decode,
     make_prefill,
     make_varlen,

@@ -1,0 +1,95 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments before touching a GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def m():
+    import paper_2509_24663_amd as m
+    if not os.path.exists(os.path.join(ROOT, "paper_2509_24663_amd", "libinfllmv2.so")):
+        from paper_2509_24663_amd import build
+        build.build(force=False)
+    return m
+
+
+def test_header_symbols_are_exported(m):
+    hdr = open(os.path.join(ROOT, "include", "infllmv2.h")).read()
+    declared = set(re.findall(r"\b(infllmv2_[a-z_0-9]+)\s*\(", hdr))
+    assert {"infllmv2_compress_k", "infllmv2_block_scores", "infllmv2_topk_blocks", "infllmv2_sparse_attn_fwd",
+            "infllmv2_sparse_decode", "infllmv2_dense_attn_fwd"} <= declared
+    L = m.lib()
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in the header but not exported"
+    from paper_2509_24663_amd import binding
+    assert set(binding.exported_symbols()) == declared
+
+
+def test_struct_layout_matches_header(m):
+    hdr = open(os.path.join(ROOT, "include", "infllmv2.h")).read()
+    body = re.search(r"typedef struct infllmv2_params \{(.*?)\} infllmv2_params;", hdr, re.S).group(1)
+    fields = re.findall(r"^\s*(?:int32_t|float)\s+([a-z_]+);", body, re.M)
+    assert fields == [f[0] for f in m.Params._fields_]
+    assert ctypes.sizeof(m.Params) == 4 * len(fields)
+
+
+def test_num_cmp_and_strings(m):
+    p = m.Params.make("bf16", 32, 2, 128)
+    assert [m.num_cmp(p, n) for n in (0, 31, 32, 47, 48, 2048, 32768, 131072)] == [0, 0, 1, 1, 2, 127, 2047, 8191]
+    assert m.status_string(0) == "ok"
+    assert "workspace" in m.status_string(-3)
+    assert m.version().startswith("infllmv2")
+
+
+def _call_compress(m, p, cu, total_c=100, k=1, kc=1, cuc=1, tok=256, head=128):
+    cu = np.asarray(cu, dtype=np.int32)
+    return m.lib().infllmv2_compress_k(ctypes.byref(p), ctypes.c_void_p(k), tok, head,
+                                       cu.ctypes.data_as(ctypes.c_void_p), ctypes.c_void_p(1), len(cu) - 1,
+                                       ctypes.c_void_p(kc), ctypes.c_void_p(cuc), total_c, None)
+
+
+def test_validation_errors_before_launch(m):
+    good = dict(dtype="bf16", num_q_heads=32, num_kv_heads=2, head_dim=128)
+    INVALID, UNSUPPORTED = -1, -2
+    cases = [
+        (dict(good, num_q_heads=31), INVALID),            # hq % hkv != 0
+        (dict(good, head_dim=96), UNSUPPORTED),
+        (dict(good, num_q_heads=64), UNSUPPORTED),        # G = 32 > 16
+    ]
+    for kw, want in cases:
+        p = m.Params.make(kw.pop("dtype"), kw.pop("num_q_heads"), kw.pop("num_kv_heads"), kw.pop("head_dim"))
+        assert _call_compress(m, p, [0, 64]) == want
+    for over, want in [(dict(n_local=0), INVALID), (dict(n_init=60, n_local=8, topk_total=64), INVALID),
+                       (dict(block_size=128), UNSUPPORTED), (dict(cmp_stride=0), INVALID),
+                       (dict(cmp_len=8, cmp_stride=16), INVALID), (dict(lse_mode=1), UNSUPPORTED),
+                       (dict(softmax_scale=0.0), INVALID), (dict(topk_total=2048), UNSUPPORTED)]:
+        p = m.Params.make("bf16", 32, 2, 128, **over)
+        assert _call_compress(m, p, [0, 64]) == want, over
+    p = m.Params.make("bf16", 32, 2, 128)
+    assert _call_compress(m, p, [1, 64]) == INVALID                 # cu[0] != 0
+    assert _call_compress(m, p, [0, 64, 32]) == INVALID             # decreasing
+    assert _call_compress(m, p, [0, 64], k=0) == INVALID            # null K
+    assert _call_compress(m, p, [0, 64], total_c=2) == INVALID      # kc too small: nc(64) = 3
+    assert _call_compress(m, p, [0, 64], tok=64) == INVALID         # token stride < head_dim
+    assert m.lib().infllmv2_compress_k(None, None, 0, 0, None, None, 0, None, None, 0, None) == INVALID
+    # decode: workspace size query and too-small workspace
+    need = m.decode_workspace_bytes(p, 16, 65536)
+    assert need > 16 * 2 * 4095 * 4
+    ctx = np.array([100, 200], dtype=np.int32)
+    st = m.lib().infllmv2_sparse_decode(ctypes.byref(p), ctypes.c_void_p(256), ctypes.c_void_p(256),
+                                        ctypes.c_void_p(256), 1 << 20, 1 << 16, 128, ctypes.c_void_p(256), 1 << 16,
+                                        ctx.ctypes.data_as(ctypes.c_void_p), ctypes.c_void_p(256), 2, None,
+                                        ctypes.c_void_p(256), None, ctypes.c_void_p(256), 16, None)
+    assert st == -3
+    ctx[1] = 0
+    st = m.lib().infllmv2_sparse_decode(ctypes.byref(p), ctypes.c_void_p(256), ctypes.c_void_p(256),
+                                        ctypes.c_void_p(256), 1 << 20, 1 << 16, 128, ctypes.c_void_p(256), 1 << 16,
+                                        ctx.ctypes.data_as(ctypes.c_void_p), ctypes.c_void_p(256), 2, None,
+                                        ctypes.c_void_p(256), None, ctypes.c_void_p(256), 1 << 30, None)
+    assert st == INVALID

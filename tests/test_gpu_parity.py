@@ -1,0 +1,258 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integer results (block lists given identical scores) must match bit for bit; end-to-end
+selections may differ only at near-ties (1e-3 relative); attention outputs must be within max-abs 1e-4
+(fp32) or max-abs 2e-2 / mean-abs 2e-3 (bf16) -- also when the oracle is fed the GPU's own selection,
+which separates attention error from selection error."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from helpers import assert_out_close, check_selection, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def m():
+    import paper_2509_24663_amd as m
+    m.lib()
+    assert torch.cuda.is_available()
+    return m
+
+
+def _params(m, oracle, dtype, hq, hkv, d, **kw):
+    gp = m.Params.make(dtype, hq, hkv, d, **kw)
+    op = oracle.Params(block_size=gp.block_size, cmp_len=gp.cmp_len, cmp_stride=gp.cmp_stride, pool_len=gp.pool_len,
+                       pool_stride=gp.pool_stride, pool_pad=gp.pool_pad, n_init=gp.n_init, n_local=gp.n_local,
+                       topk_total=gp.topk_total, dense_threshold=gp.dense_threshold,
+                       softmax_scale=float(gp.softmax_scale))
+    return gp, op
+
+
+def _run_prefill_case(m, oracle, w, gp, op, dtype, rows=None, check_stages=True):
+    """Full sparse path on one packed workload; returns stats."""
+    cu = w["cu_seqlens"]
+    T, hq, d = w["q"].shape
+    hkv = w["k"].shape[0]
+    G = hq // hkv
+    q, k, v = (to_dev(w[x], dtype) for x in ("q", "k", "v"))
+    res = m.sparse_prefill(gp, q, k, v, cu)
+    torch.cuda.synchronize()
+    out_g, lse_g, idx_g = to_np(res["out"]), to_np(res["lse"]), to_np(res["block_idx"])
+    sh_g, kc_g = to_np(res["s_shared"]), to_np(res["kc"])
+    rows = np.arange(T) if rows is None else np.asarray(rows)
+    stats = dict(rows_diff=0, blocks_diff=0)
+    cu_c = to_np(res["cu_seqlens_c"].int())
+    for s in range(len(cu) - 1):
+        a, b = int(cu[s]), int(cu[s + 1])
+        n = b - a
+        sel = rows[(rows >= a) & (rows < b)]
+        if len(sel) == 0:
+            continue
+        pos = (sel - a).astype(np.int32)
+        dense = n < op.dense_threshold
+        for h in range(hkv):
+            Qh = w["q"][sel, h * G:(h + 1) * G]
+            Kh, Vh = w["k"][h, a:b], w["v"][h, a:b]
+            if dense:
+                O, L = oracle.dense_attn(Qh, pos, Kh, Vh, op)
+                assert np.all(idx_g[h, sel] == -1)
+            else:
+                kc_o = oracle.compress_k(Kh, op)
+                nc = kc_o.shape[0]
+                assert cu_c[s + 1] - cu_c[s] == nc
+                if check_stages:
+                    np.testing.assert_allclose(kc_g[h, cu_c[s]:cu_c[s] + nc], kc_o, rtol=0, atol=2e-6)
+                sh_o = oracle.block_scores(Qh, pos, kc_o, op)
+                idx_o, cmp_o = oracle.topk_blocks(sh_o, pos, op, return_cmp=True)
+                if check_stages:
+                    for r, t in enumerate(pos):
+                        vis = oracle.visible_cmp(int(t), op)
+                        np.testing.assert_allclose(sh_g[h, sel[r], :vis], sh_o[r, :vis], rtol=2e-4, atol=1e-7)
+                    # stage 3 alone: oracle top-k of the GPU's scores must equal the GPU's list bit for bit
+                    shg_rows = np.zeros_like(sh_o)
+                    for r, t in enumerate(pos):
+                        vis = oracle.visible_cmp(int(t), op)
+                        shg_rows[r, :vis] = sh_g[h, sel[r], :vis]
+                    np.testing.assert_array_equal(idx_g[h, sel], oracle.topk_blocks(shg_rows, pos, op))
+                rd, bd = check_selection(idx_g[h, sel], idx_o, cmp_o, pos, op.n_init, op.n_local)
+                stats["rows_diff"] += rd
+                stats["blocks_diff"] += bd
+                # attention error alone: oracle attention over the GPU's selection
+                O_iso, L_iso = oracle.sparse_attn(Qh, pos, Kh, Vh, idx_g[h, sel], op)
+                assert_out_close(out_g[sel, h * G:(h + 1) * G], O_iso, dtype, "out | GPU selection")
+                np.testing.assert_allclose(lse_g[h * G:(h + 1) * G, sel].T, L_iso, atol=2e-3 if dtype == "bf16" else 1e-4)
+                O, L = oracle.sparse_attn(Qh, pos, Kh, Vh, idx_o, op)
+            if rd_ok(stats):
+                assert_out_close(out_g[sel, h * G:(h + 1) * G], O, dtype, "out end-to-end")
+    return stats
+
+
+def rd_ok(stats):
+    # with identical selections the end-to-end output must match too; with tie flips it may legitimately differ
+    return stats["rows_diff"] == 0
+
+
+# ----------------------------------------------------------------------------------------------- configs
+def test_c1_tiny_fp32_full(m, oracle):
+    """BASELINE config 1 in full: fp32, n 2048, 4 q heads / 1 kv head, d 64, top-k 8 (1 init + 2 local)."""
+    cfg = synth.CONFIGS["C1"]
+    w = synth.make_config(cfg)
+    gp, op = m.Params.from_config(cfg), oracle.Params.from_config(cfg)
+    st = _run_prefill_case(m, oracle, w, gp, op, "fp32")
+    assert st["rows_diff"] == 0, st
+
+
+@pytest.mark.parametrize("n", [1, 31, 32, 63, 64, 65, 200, 1000, 1537])
+def test_ragged_lengths_fp32(m, oracle, n):
+    w = synth.make_prefill(n, 4, 2, 64, seed=100 + n, dtype="fp32")
+    gp, op = _params(m, oracle, "fp32", 4, 2, 64, n_init=1, n_local=2, topk_total=6)
+    _run_prefill_case(m, oracle, w, gp, op, "fp32")
+
+
+@pytest.mark.parametrize("shape", [(8, 2, 128), (3, 3, 64), (16, 1, 64), (6, 2, 128)])
+def test_head_shapes_bf16_generic(m, oracle, shape):
+    hq, hkv, d = shape
+    w = synth.make_prefill(700, hq, hkv, d, seed=7, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", hq, hkv, d, n_init=1, n_local=2, topk_total=5)
+    _run_prefill_case(m, oracle, w, gp, op, "bf16")
+
+
+@pytest.mark.parametrize("n", [257, 2048, 4500])
+def test_paper_head_shape_bf16(m, oracle, n):
+    """h_q 32 / h_kv 2 / d 128 (the paper's model shape): the MFMA kernels' home."""
+    w = synth.make_prefill(n, 32, 2, 128, seed=300 + n, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=8, topk_total=16)
+    _run_prefill_case(m, oracle, w, gp, op, "bf16")
+
+
+@pytest.mark.parametrize("cfg", [(1, 1, 4), (2, 3, 9), (0, 1, 3), (1, 8, 64)])
+@pytest.mark.parametrize("pad", [0, 1])
+def test_topk_stage_bit_exact_on_tied_scores(m, oracle, cfg, pad):
+    """Stage 3 alone on scores with many exact ties: the block lists must equal the oracle's bit for bit."""
+    n_init, n_local, total = cfg
+    n = 6000
+    gp, op = _params(m, oracle, "fp32", 4, 2, 64, n_init=n_init, n_local=n_local, topk_total=total, pool_pad=pad)
+    nc = oracle.num_cmp(n, op)
+    rs = (nc + 3) // 4 * 4
+    rng = np.random.default_rng(5)
+    sh = np.zeros((2, n, rs), np.float32)
+    for t in range(n):
+        v = oracle.visible_cmp(t, op)
+        sh[:, t, :v] = rng.integers(0, 40, (2, v)).astype(np.float32) / 16
+        sh[:, t, v:] = 77.0          # garbage beyond the visible prefix must be ignored
+    idx = to_np(m.topk_blocks(gp, torch.from_numpy(sh).cuda(), [0, n]))
+    pos = np.arange(n, dtype=np.int32)
+    for h in range(2):
+        clean = sh[h].copy()
+        for t in range(n):
+            clean[t, oracle.visible_cmp(t, op):] = 0
+        np.testing.assert_array_equal(idx[h], oracle.topk_blocks(clean[:, :nc], pos, op))
+
+
+def test_dense_attention(m, oracle):
+    for dtype, hq, hkv, d, n in [("fp32", 4, 1, 64, 777), ("bf16", 32, 2, 128, 1100), ("bf16", 8, 2, 64, 300)]:
+        w = synth.make_prefill(n, hq, hkv, d, seed=9, dtype=dtype)
+        gp, op = _params(m, oracle, dtype, hq, hkv, d)
+        q, k, v = (to_dev(w[x], dtype) for x in ("q", "k", "v"))
+        out, lse = m.dense_attn_fwd(gp, q, k, v, [0, n])
+        torch.cuda.synchronize()
+        ref = oracle.prefill(w["q"], w["k"], w["v"], [0, n], op, force="dense")
+        assert_out_close(to_np(out), ref["out"], dtype, "dense out")
+        np.testing.assert_allclose(to_np(lse).T, ref["lse"], atol=2e-3 if dtype == "bf16" else 1e-4)
+
+
+def test_sparse_equals_dense_when_all_blocks_kept(m, oracle):
+    """Invariant: with top-k covering every block the sparse path is dense causal attention."""
+    n = 1000
+    w = synth.make_prefill(n, 32, 2, 128, seed=12, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=8, topk_total=16)
+    q, k, v = (to_dev(w[x], "bf16") for x in ("q", "k", "v"))
+    res = m.sparse_prefill(gp, q, k, v, [0, n])
+    dn, dl = m.dense_attn_fwd(gp, q, k, v, [0, n])
+    torch.cuda.synchronize()
+    assert_out_close(to_np(res["out"]), to_np(dn), "bf16")
+    np.testing.assert_allclose(to_np(res["lse"]), to_np(dl), atol=2e-3)
+
+
+def test_varlen_switch(m, oracle):
+    """Packed sequences on both sides of the dense/sparse threshold (the shape of BASELINE config 5, smaller)."""
+    lens = [100, 1024, 64, 2500, 1023, 1]
+    w = synth.make_varlen(lens, 32, 2, 128, seed=77, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=4, topk_total=10, dense_threshold=1024)
+    st = _run_prefill_case(m, oracle, w, gp, op, "bf16")
+    # fp32 / small heads too
+    w = synth.make_varlen([70, 500, 33], 4, 2, 64, seed=78, dtype="fp32")
+    gp, op = _params(m, oracle, "fp32", 4, 2, 64, n_init=1, n_local=2, topk_total=4, dense_threshold=100)
+    _run_prefill_case(m, oracle, w, gp, op, "fp32")
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d", [("bf16", 32, 2, 128), ("fp32", 4, 1, 64)])
+def test_decode_matches_oracle_and_prefill_row(m, oracle, dtype, hq, hkv, d):
+    ctx = [3000, 641, 64, 33, 5, 2049, 1]
+    w = synth.make_decode(ctx, hq, hkv, d, seed=31, dtype=dtype, max_len=3008)
+    gp, op = _params(m, oracle, dtype, hq, hkv, d, n_init=1, n_local=2, topk_total=8)
+    q, kc_, vc_ = to_dev(w["q"], dtype), to_dev(w["k_cache"], dtype), to_dev(w["v_cache"], dtype)
+    B = len(ctx)
+    max_nc = oracle.num_cmp(3008, op)
+    kcc = torch.zeros((B, hkv, max_nc, d), dtype=torch.float32, device="cuda")
+    for b, L in enumerate(ctx):      # compressed-key cache built by the library's own stage 1
+        kcb, _ = m.compress_k(gp, kc_[b, :, :L], [0, L])
+        nc = oracle.num_cmp(L, op)
+        kcc[b, :, :nc] = kcb[:, :nc]
+    out, lse, idx = m.sparse_decode(gp, q, kc_, vc_, kcc, ctx)
+    torch.cuda.synchronize()
+    ref = oracle.decode(w["q"], w["k_cache"], w["v_cache"], ctx, op)
+    idx = to_np(idx)
+    G = hq // hkv
+    for b, L in enumerate(ctx):
+        pos = np.array([L - 1], np.int32)
+        for h in range(hkv):
+            Kh = w["k_cache"][b, h, :L]
+            sh = oracle.block_scores(w["q"][b:b + 1, h * G:(h + 1) * G], pos, oracle.compress_k(Kh, op), op)
+            io, co = oracle.topk_blocks(sh, pos, op, return_cmp=True)
+            check_selection(idx[b, h][None], io, co, pos, op.n_init, op.n_local)
+            O, Ls = oracle.sparse_attn(w["q"][b:b + 1, h * G:(h + 1) * G], pos, Kh, w["v_cache"][b, h, :L],
+                                       idx[b, h][None], op)
+            assert_out_close(to_np(out)[b, h * G:(h + 1) * G], O[0], dtype, "decode out | GPU selection")
+            np.testing.assert_allclose(to_np(lse)[b, h * G:(h + 1) * G], Ls[0], atol=2e-3 if dtype == "bf16" else 1e-4)
+    if np.array_equal(idx, ref["idx"]):
+        assert_out_close(to_np(out), ref["out"], dtype, "decode out")
+    # decode == last row of the library's own prefill on the same sequence
+    L = ctx[0]
+    q_full = torch.zeros((L, hq, d), dtype=q.dtype, device="cuda")
+    q_full[L - 1] = q[0]
+    pre = m.sparse_prefill(gp, q_full, kc_[0, :, :L], vc_[0, :, :L], [0, L])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_np(pre["block_idx"])[:, L - 1], idx[0])
+    assert_out_close(to_np(pre["out"])[L - 1], to_np(out)[0], dtype, "decode vs prefill row")
+
+
+def test_empty_batch_and_empty_sequences(m, oracle):
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128)
+    q = torch.zeros((0, 32, 128), dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros((2, 0, 128), dtype=torch.bfloat16, device="cuda")
+    res = m.sparse_prefill(gp, q, k, k, [0])
+    assert res["out"].shape[0] == 0
+    # a zero-length sequence in the middle of a batch
+    w = synth.make_varlen([130, 200], 4, 2, 64, seed=3, dtype="fp32")
+    cu3 = np.array([0, 130, 130, 330], np.int32)
+    gp, op = _params(m, oracle, "fp32", 4, 2, 64, n_init=1, n_local=2, topk_total=4)
+    q, k, v = (to_dev(w[x], "fp32") for x in ("q", "k", "v"))
+    a = m.sparse_prefill(gp, q, k, v, w["cu_seqlens"])
+    b = m.sparse_prefill(gp, q, k, v, cu3)
+    torch.cuda.synchronize()
+    assert torch.equal(a["out"], b["out"]) and torch.equal(a["block_idx"], b["block_idx"])
+
+
+def test_determinism(m, oracle):
+    """No atomics on floats anywhere: two runs give bitwise identical results."""
+    w = synth.make_prefill(3000, 32, 2, 128, seed=55, dtype="bf16")
+    gp, _ = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=8, topk_total=16)
+    q, k, v = (to_dev(w[x], "bf16") for x in ("q", "k", "v"))
+    a = m.sparse_prefill(gp, q, k, v, [0, 3000])
+    b = m.sparse_prefill(gp, q, k, v, [0, 3000])
+    torch.cuda.synchronize()
+    for key in ("out", "lse", "block_idx", "kc"):
+        assert torch.equal(a[key], b[key]), key
