@@ -1,0 +1,261 @@
+#!/usr/bin/env python3
+"""Benchmark of the InfLLM-V2 attention hot path on one MI355X.
+
+A "step" is one pass of the whole sparse prefill path -- compress_k, block_scores, topk_blocks,
+sparse_attn_fwd -- over one synthetic batch that is already resident in HBM.  The default workload is
+BASELINE config 3 (bf16, 131072 tokens, 32 query heads / 2 KV heads, d 128, 64 selected blocks), the one
+the headline metric is quoted on.  One JSON line is printed with the whole-step throughput, the per-stage
+times, the roofline of the dominant kernel (HIP-event timed on the launch stream), the library's own dense
+path at the same shape, the decode workload (config 4) and the CPU oracle timed on a bounded sample of rows.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
+
+
+def _events(torch, n):
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C3", choices=["C2", "C3"])
+    ap.add_argument("--dense-steps", type=int, default=1, help="timed runs of the dense path at the same shape (0 = skip)")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-rows", type=int, default=512, help="query rows per KV head the oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2509_24663_amd as m
+    import synth
+
+    m.lib()     # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    gp = m.Params.from_config(cfg)
+    n, hq, hkv, d = cfg.seq_len, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim
+    G = hq // hkv
+
+    t0 = time.time()
+    w = synth.make_config(cfg)
+    q = torch.from_numpy(w["q"]).to(torch.bfloat16).cuda()
+    k = torch.from_numpy(w["k"]).to(torch.bfloat16).cuda()
+    v = torch.from_numpy(w["v"]).to(torch.bfloat16).cuda()
+    gen_s = time.time() - t0
+    si = m.SeqInfo([0, n])
+
+    # ------------------------------------------------------------------ whole path, K timed steps
+    bufs = m.sparse_prefill(gp, q, k, v, si)          # first call allocates every buffer once
+    torch.cuda.synchronize()
+    for _ in range(max(args.warmup - 1, 0)):
+        m.sparse_prefill(gp, q, k, v, si, buffers=bufs)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        m.sparse_prefill(gp, q, k, v, si, buffers=bufs)
+    torch.cuda.synchronize()
+    step_ms = (time.perf_counter() - t_start) * 1e3 / args.steps
+
+    # ------------------------------------------------------------------ per-stage HIP-event timing
+    stage_names = ["compress_k", "block_scores", "topk_blocks", "sparse_attn_fwd"]
+    acc = {s: 0.0 for s in stage_names}
+    for _ in range(args.steps):
+        ev = _events(torch, 5)
+        ev[0].record()
+        m.compress_k(gp, k, si, out=(bufs["kc"], bufs["cu_seqlens_c"]))
+        ev[1].record()
+        m.block_scores(gp, q, bufs["kc"], si, bufs["cu_seqlens_c"], out=bufs["s_shared"])
+        ev[2].record()
+        m.topk_blocks(gp, bufs["s_shared"], si, out=bufs["block_idx"])
+        ev[3].record()
+        m.sparse_attn_fwd(gp, q, k, v, bufs["block_idx"], si, out=bufs["out"], lse=bufs["lse"])
+        ev[4].record()
+        torch.cuda.synchronize()
+        for i, s in enumerate(stage_names):
+            acc[s] += ev[i].elapsed_time(ev[i + 1])
+    stage_ms = {s: acc[s] / args.steps for s in stage_names}
+
+    # executed attention flops from the actual selection: every selected block is full except the query's own
+    idx = bufs["block_idx"]
+    nsel = (idx >= 0).sum(-1).to(torch.int64)                               # [hkv, n]
+    tpos = torch.arange(n, device=idx.device, dtype=torch.int64)[None, :]
+    keys = (nsel - 1) * cfg.block_size + (tpos % cfg.block_size) + 1
+    attn_keys = int(keys.sum())
+    attn_flops = 4.0 * d * G * attn_keys
+    vis = torch.clamp((tpos - cfg.cmp_len + 1) // cfg.cmp_stride + 1, min=0)
+    vis = torch.where(tpos < cfg.cmp_len - 1, torch.zeros_like(vis), vis)
+    score_flops = 2 * 2.0 * d * hq * int(vis.sum())                          # two passes, 1x MFMA each
+    score_bytes = 4.0 * hkv * int(vis.sum())
+
+    tflops = attn_flops / (step_ms * 1e-3) / 1e12
+    stages = {s: {"ms": round(stage_ms[s], 4)} for s in stage_names}
+    stages["sparse_attn_fwd"].update(tflops=round(attn_flops / (stage_ms["sparse_attn_fwd"] * 1e-3) / 1e12, 2),
+                                     frac_mfma_peak=round(attn_flops / (stage_ms["sparse_attn_fwd"] * 1e-3) / 1e12 /
+                                                          PEAK_BF16_MFMA_TFLOPS, 4))
+    stages["block_scores"].update(tflops=round(score_flops / (stage_ms["block_scores"] * 1e-3) / 1e12, 2),
+                                  frac_mfma_peak=round(score_flops / (stage_ms["block_scores"] * 1e-3) / 1e12 /
+                                                       PEAK_BF16_MFMA_TFLOPS, 4))
+    kbytes = 2.0 * n * hkv * d + 4.0 * hkv * bufs["kc"].shape[1] * d
+    stages["compress_k"].update(gbs=round(kbytes / (stage_ms["compress_k"] * 1e-3) / 1e9, 1))
+    tk_bytes = score_bytes + 4.0 * hkv * n * cfg.topk_total
+    stages["topk_blocks"].update(gbs=round(tk_bytes / (stage_ms["topk_blocks"] * 1e-3) / 1e9, 1),
+                                 frac_hbm_peak=round(tk_bytes / (stage_ms["topk_blocks"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4))
+
+    # roofline of the dominant kernel (largest share of the step)
+    dom = max(stage_names, key=lambda s: stage_ms[s])
+    if dom in ("sparse_attn_fwd", "block_scores"):
+        fl = attn_flops if dom == "sparse_attn_fwd" else score_flops
+        ach = fl / (stage_ms[dom] * 1e-3) / 1e12
+        roof = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": None}
+    else:
+        by = tk_bytes if dom == "topk_blocks" else kbytes
+        ach = by / (stage_ms[dom] * 1e-3) / 1e9
+        roof = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
+
+    # ------------------------------------------------------------------ the library's own dense path
+    dense = None
+    if args.dense_steps > 0:
+        od, ld = m.dense_attn_fwd(gp, q, k, v, si, out=torch.empty_like(q), lse=torch.empty_like(bufs["lse"]))
+        torch.cuda.synchronize()
+        e0, e1 = _events(torch, 2)
+        e0.record()
+        for _ in range(args.dense_steps):
+            m.dense_attn_fwd(gp, q, k, v, si, out=od, lse=ld)
+        e1.record()
+        torch.cuda.synchronize()
+        dms = e0.elapsed_time(e1) / args.dense_steps
+        dfl = 4.0 * d * hq * n * (n + 1) / 2
+        dense = {"ms": round(dms, 3), "tflops": round(dfl / (dms * 1e-3) / 1e12, 2),
+                 "frac_mfma_peak": round(dfl / (dms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),
+                 "speedup_sparse_path": round(dms / step_ms, 2),
+                 "speedup_sparse_attn_only": round(dms / stage_ms["sparse_attn_fwd"], 2)}
+        del od, ld
+
+    # ------------------------------------------------------------------ decode workload (config 4)
+    decode = None
+    if not args.no_decode:
+        decode = bench_decode(torch, m, synth)
+
+    # ------------------------------------------------------------------ CPU oracle on a bounded sample of rows
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        op = oracle.Params.from_config(cfg)
+        rng = np.random.default_rng(0)
+        rows = np.sort(rng.choice(n, size=min(args.cpu_rows, n), replace=False)).astype(np.int32)
+        t1 = time.perf_counter()
+        okeys = 0
+        for h in range(hkv):
+            Qh = w["q"][rows, h * G:(h + 1) * G]
+            ih = oracle.select_blocks(Qh, rows, w["k"][h], op)
+            oracle.sparse_attn(Qh, rows, w["k"][h], w["v"][h], ih, op)
+            okeys += int((((ih >= 0).sum(-1) - 1) * cfg.block_size + rows % cfg.block_size + 1).sum())
+        cpu_s = time.perf_counter() - t1
+        cpu = {"value": round(4.0 * d * G * okeys / cpu_s / 1e12, 6), "unit": "TFLOP/s",
+               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "kind": "oracle",
+               "sample": f"stages 1-4 of the oracle on {len(rows)} random query rows per KV head of the same "
+                         f"{args.workload} inputs (compress_k over the whole sequence), {cpu_s:.1f} s; rate in the "
+                         "same unit: executed attention flops of those rows / oracle time"}
+
+    line = {
+        "metric": "sparse attn prefill TFLOP/s at 128K (stages 1-4; executed attention flops / step time)"
+        if args.workload == "C3" else "sparse attn prefill TFLOP/s at 32K (stages 1-4)",
+        "value": round(tflops, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(step_ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: sparse causal prefill, batch 1, seq {n}, {hq} q heads / {hkv} kv heads, "
+                               f"d {d}, block 64, compress 32/16, top-k {cfg.topk_total} (1 init + {cfg.n_local} local)",
+                   "seed": cfg.seed, "topic_std": cfg.topic_std, "density": round(attn_keys / (hkv * n * (n + 1) / 2), 5)},
+        "ms_per_layer": {**{s: round(stage_ms[s], 4) for s in stage_names}, "total": round(step_ms, 4)},
+        "stages": stages,
+        "roofline": roof,
+        "dense_same_shape": dense,
+        "decode": decode,
+        "cpu_baseline": cpu,
+        "frac_mfma_peak_whole_step": round(tflops / PEAK_BF16_MFMA_TFLOPS, 4),
+        "input_gen_s": round(gen_s, 1),
+    }
+    print(json.dumps(line))
+    return 0
+
+
+def bench_decode(torch, m, synth, iters: int = 20, nsets: int = 4):
+    """Config 4: batch 16, context lengths uniform in [16384, 65536]; K/V and K^{C1} caches precomputed.
+    Rotates over `nsets` distinct cache sets so repeated steps do not just hit the Infinity Cache."""
+    cfg = synth.CONFIGS["C4"]
+    gp = m.Params.from_config(cfg)
+    hq, hkv, d = cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim
+    ctx = synth.draw_ctx_lens(cfg.batch, cfg.ctx_lo, cfg.ctx_hi, cfg.seed)
+    lmax = int(ctx.max())
+    B = cfg.batch
+    gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    sets = []
+    max_nc = m.num_cmp(gp, lmax)
+    for s in range(nsets):
+        # device-side random caches with the generator's block-topic structure (timing only: parity is in tests/)
+        nb = (lmax + 63) // 64
+        topic = 0.5 * torch.randn((B, hkv, nb, 1, d), generator=gen, device="cuda")
+        kc_ = (torch.randn((B, hkv, nb, 64, d), generator=gen, device="cuda") + topic).reshape(B, hkv, nb * 64, d)
+        kc_ = kc_[:, :, :lmax].to(torch.bfloat16).contiguous()
+        vc_ = torch.randn((B, hkv, lmax, d), generator=gen, device="cuda").to(torch.bfloat16)
+        src = torch.randint(0, nb // 4, (B, hkv), generator=gen, device="cuda")
+        tq = topic[torch.arange(B)[:, None], torch.arange(hkv)[None, :], src, 0]          # [B, hkv, d]
+        qd = (torch.randn((B, hkv, hq // hkv, d), generator=gen, device="cuda") + tq[:, :, None]).reshape(B, hq, d)
+        qd = qd.to(torch.bfloat16)
+        kcc = torch.zeros((B, hkv, max_nc, d), dtype=torch.float32, device="cuda")
+        for b in range(B):
+            L = int(ctx[b])
+            kcb, _ = m.compress_k(gp, kc_[b, :, :L], [0, L])
+            kcc[b, :, :kcb.shape[1]] = kcb
+        sets.append((qd, kc_, vc_, kcc))
+        del topic
+    ws = torch.empty(m.decode_workspace_bytes(gp, B, lmax), dtype=torch.uint8, device="cuda")
+    for s in range(nsets):
+        m.sparse_decode(gp, *sets[s], ctx, workspace=ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(iters):
+        m.sparse_decode(gp, *sets[i % nsets], ctx, workspace=ws, return_idx=False)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    out, lse, idx = m.sparse_decode(gp, *sets[0], ctx, workspace=ws)
+    nsel = (idx >= 0).sum(-1)                                                     # [B, hkv]
+    last = torch.as_tensor(ctx, device="cuda")[:, None]
+    keys = (nsel - 1) * 64 + ((last - 1) % 64) + 1
+    kv_bytes = float(keys.sum()) * d * 2 * 2
+    kc_bytes = float(sum(m.num_cmp(gp, int(L)) for L in ctx)) * hkv * d * 4
+    byts = kv_bytes + kc_bytes + 2.0 * B * hq * d * 2
+    return {"workload": "C4: batch 16, ctx uniform [16384, 65536], 32 q heads / 2 kv heads, d 128, top-k 64",
+            "ms_per_step": round(ms, 4), "tokens_per_s": round(B / (ms * 1e-3), 1),
+            "algorithmic_bytes": int(byts), "gbs": round(byts / (ms * 1e-3) / 1e9, 1),
+            "frac_hbm_peak": round(byts / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "note": f"attention layer only; rotates over {nsets} distinct cache sets ({nsets * 2 * B * hkv * lmax * d * 2 / 1e9:.1f} GB of K/V)"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     FP32,
     InfllmV2Error,
     Params,
+    SeqInfo,
     block_scores,
     compress_k,
     decode_workspace_bytes,

@@ -118,10 +118,23 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+class SeqInfo:
+    """cu_seqlens as the ABI wants it: a host int32 array plus a device copy, made once and reused."""
+
+    def __init__(self, cu_seqlens):
+        self.cu_h = torch.as_tensor(cu_seqlens, dtype=torch.int32, device="cpu").contiguous()
+        self.cu_d = self.cu_h.cuda()
+        self.batch = self.cu_h.numel() - 1
+        lens = (self.cu_h[1:] - self.cu_h[:-1])
+        self.lens = lens.tolist()
+        self.max_len = int(lens.max()) if self.batch else 0
+        self.total = int(self.cu_h[-1])
+
+
 def _cu_pair(cu_seqlens):
-    """host int32 numpy-backed tensor + device copy"""
-    cu_h = torch.as_tensor(cu_seqlens, dtype=torch.int32, device="cpu").contiguous()
-    return cu_h, cu_h.cuda()
+    """host int32 tensor + device copy (pass a SeqInfo to avoid the copy on every call)"""
+    si = cu_seqlens if isinstance(cu_seqlens, SeqInfo) else SeqInfo(cu_seqlens)
+    return si.cu_h, si.cu_d
 
 
 def _kv_strides(k: torch.Tensor):
@@ -131,14 +144,18 @@ def _kv_strides(k: torch.Tensor):
 
 
 # ---------------------------------------------------------------------------------- stage wrappers
-def compress_k(p: Params, k: torch.Tensor, cu_seqlens):
-    """Stage 1.  k [hkv, T, d] (device).  Returns kc [hkv, total_c, d] fp32, cu_seqlens_c (device int32)."""
+def compress_k(p: Params, k: torch.Tensor, cu_seqlens, out=None):
+    """Stage 1.  k [hkv, T, d] (device).  Returns kc [hkv, total_c, d] fp32, cu_seqlens_c (device int32).
+    out: optional (kc, cu_seqlens_c) buffers to reuse."""
     cu_h, cu_d = _cu_pair(cu_seqlens)
     batch = cu_h.numel() - 1
-    lens = (cu_h[1:] - cu_h[:-1]).tolist()
-    total_c = sum(num_cmp(p, n) for n in lens)
-    kc = torch.empty((p.num_kv_heads, max(total_c, 1), p.head_dim), dtype=torch.float32, device=k.device)
-    cu_c = torch.empty(batch + 1, dtype=torch.int32, device=k.device)
+    if out is None:
+        lens = (cu_h[1:] - cu_h[:-1]).tolist()
+        total_c = sum(num_cmp(p, n) for n in lens)
+        kc = torch.empty((p.num_kv_heads, max(total_c, 1), p.head_dim), dtype=torch.float32, device=k.device)
+        cu_c = torch.empty(batch + 1, dtype=torch.int32, device=k.device)
+    else:
+        kc, cu_c = out
     ts, hs = _kv_strides(k)
     st = lib().infllmv2_compress_k(ctypes.byref(p), _ptr(k), ts, hs, _ptr(cu_h), _ptr(cu_d), batch, _ptr(kc),
                                    _ptr(cu_c), kc.shape[1], _stream())
@@ -154,7 +171,7 @@ def block_scores(p: Params, q: torch.Tensor, kc: torch.Tensor, cu_seqlens, cu_se
     max_len = int((cu_h[1:] - cu_h[:-1]).max()) if batch else 0
     rs = max(4, (num_cmp(p, max_len) + 3) // 4 * 4)
     if out is None:
-        out = torch.zeros((p.num_kv_heads, q.shape[0], rs), dtype=torch.float32, device=q.device)
+        out = torch.empty((p.num_kv_heads, q.shape[0], rs), dtype=torch.float32, device=q.device)
     st = lib().infllmv2_block_scores(ctypes.byref(p), _ptr(q), _ptr(kc), kc.shape[1], _ptr(cu_h), _ptr(cu_d),
                                      _ptr(cu_seqlens_c), batch, _ptr(out), out.shape[2], _stream())
     _check(st, "infllmv2_block_scores")
@@ -227,11 +244,14 @@ def sparse_decode(p: Params, q, k_cache, v_cache, kc_cache, ctx_lens, workspace=
     return out, lse, idx
 
 
-def sparse_prefill(p: Params, q, k, v, cu_seqlens):
+def sparse_prefill(p: Params, q, k, v, cu_seqlens, buffers: Optional[dict] = None):
     """The four stages back to back (a convenience for tests and the benchmark; no arithmetic here).
-    Returns dict(out, lse, block_idx, s_shared, kc)."""
-    kc, cu_c = compress_k(p, k, cu_seqlens)
-    sh = block_scores(p, q, kc, cu_seqlens, cu_c)
-    idx = topk_blocks(p, sh, cu_seqlens)
-    out, lse = sparse_attn_fwd(p, q, k, v, idx, cu_seqlens)
+    buffers: a dict returned by an earlier call, whose tensors are then reused (nothing is allocated).
+    Returns dict(out, lse, block_idx, s_shared, kc, cu_seqlens_c)."""
+    b = buffers or {}
+    si = cu_seqlens if isinstance(cu_seqlens, SeqInfo) else SeqInfo(cu_seqlens)
+    kc, cu_c = compress_k(p, k, si, out=(b["kc"], b["cu_seqlens_c"]) if b else None)
+    sh = block_scores(p, q, kc, si, cu_c, out=b.get("s_shared"))
+    idx = topk_blocks(p, sh, si, out=b.get("block_idx"))
+    out, lse = sparse_attn_fwd(p, q, k, v, idx, si, out=b.get("out"), lse=b.get("lse"))
     return dict(out=out, lse=lse, block_idx=idx, s_shared=sh, kc=kc, cu_seqlens_c=cu_c)

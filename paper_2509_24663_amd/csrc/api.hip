@@ -245,7 +245,9 @@ int infllmv2_sparse_decode(const infllmv2_params *p, const void *q_d, const void
 namespace ifv2 {
 int launch_attn(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
                 int dense_below, void *out, float *lse, const int32_t *cu_h) {
-    if (attn_mfma_supported(L.p)) return launch_attn_mfma(L, q, k, v, idx, dense_below, out, lse, cu_h);
+    const bool aligned = (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) == 0 &&
+                         L.map.kv_tok_stride % 8 == 0 && L.map.kv_head_stride % 8 == 0;
+    if (attn_mfma_supported(L.p) && aligned) return launch_attn_mfma(L, q, k, v, idx, dense_below, out, lse, cu_h);
     return launch_attn_generic(L, q, k, v, idx, dense_below, out, lse);
 }
 }  // namespace ifv2
