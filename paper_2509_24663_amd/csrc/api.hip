@@ -125,7 +125,7 @@ int infllmv2_block_scores(const infllmv2_params *p, const void *q_d, const float
         return INFLLMV2_ERR_INVALID_ARGUMENT;
     Launch L{p, prefill_map(p, cu_seqlens_d, cu_seqlens_c_d, batch, total, 0, 0, total_c), (hipStream_t)stream,
              max_len};
-    return launch_block_scores(L, q_d, kc_d, s_shared_d, row_stride);
+    return launch_block_scores(L, q_d, kc_d, s_shared_d, row_stride, cu_seqlens_h);
 }
 
 int infllmv2_topk_blocks(const infllmv2_params *p, const float *s_shared_d, int64_t row_stride,
@@ -233,7 +233,7 @@ int infllmv2_sparse_decode(const infllmv2_params *p, const void *q_d, const void
     m.kc_total_c = 0;
     m.kc_head_stride = kc_head_stride;
     Launch L{p, m, (hipStream_t)stream, max_ctx};
-    st = launch_block_scores(L, q_d, kc_cache_d, scores, (int64_t)rs);
+    st = launch_block_scores(L, q_d, kc_cache_d, scores, (int64_t)rs, nullptr);
     if (st) return st;
     st = launch_topk(L, scores, (int64_t)rs, idx);
     if (st) return st;

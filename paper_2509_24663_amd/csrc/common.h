@@ -122,7 +122,9 @@ struct Launch {
 
 int launch_cu_c(const infllmv2_params *p, const int32_t *cu_d, int batch, int32_t *cu_c_d, hipStream_t s);
 int launch_compress_k(const Launch &L, const void *k, float *kc, int64_t total_c_rows);
-int launch_block_scores(const Launch &L, const void *q, const float *kc, float *s_shared, int64_t row_stride);
+// cu_h: host cu_seqlens for the tiled kernels' grid (nullptr: single-row / decode form)
+int launch_block_scores(const Launch &L, const void *q, const float *kc, float *s_shared, int64_t row_stride,
+                        const int32_t *cu_h);
 int launch_topk(const Launch &L, const float *s_shared, int64_t row_stride, int32_t *idx);
 // idx == nullptr: dense for every sequence; dense_below: sequences shorter than this are dense anyway
 int launch_attn(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
