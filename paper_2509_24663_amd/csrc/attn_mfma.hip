@@ -8,30 +8,37 @@
 // gather traffic from L2 / HBM drops by the sharing factor while the arithmetic stays exactly the
 // per-token softmax attention of Alg. 2.
 //
-// Per (token, block) the 16 heads of the group are one MFMA tile side: S^T = K_blk Q_t^T is computed as
-// 4 key tiles x 4 k-steps of v_mfma_f32_16x16x32_bf16 (A = K rows from LDS, B = Q_t held in registers), so
-// a lane owns one head and 16 keys: the running max / sum of the online softmax need two cross-lane steps,
-// and P^T is already laid out as the B operand of O^T += V_blk^T P^T (A = V^T from LDS, 8 dim tiles x 2
-// k-steps).  Keys are assigned to MFMA rows so that a lane's 8 probabilities of a k-step are 8 consecutive
-// keys, which makes the V^T operand a single 16-byte LDS read.  V is transposed once per block while it
-// is written to LDS.  Dense attention is the same kernel with "every block, every token".
+// Data movement: K and V blocks go from global memory straight into LDS (global_load_lds, 16 bytes per
+// lane, no register staging), row-major, with the 16-byte chunks of a row XOR-swizzled by the row number
+// so that both operand reads below are spread over all banks.
+//
+// Per (token, block) the 16 heads of the group are one MFMA tile side.  S^T = K_blk Q_t^T is 4 key tiles x
+// 4 k-steps of v_mfma_f32_16x16x32_bf16 (A = K rows from LDS, B = Q_t held in registers), so a lane owns
+// one head and 16 keys: the online softmax needs two cross-lane steps for the row max and none for the row
+// sum (kept as per-lane partial sums until the end).  P^T is then already laid out as the B operand of
+// O^T += V_blk^T P^T (8 dim tiles x 2 k-steps); its A operand V^T is read from the row-major V block with
+// the transposing LDS read (ds_read_b64_tr_b16), two reads per operand.  Dense attention is the same
+// kernel with "every block, every token".
+#include <stdlib.h>
+#include <string.h>
+
 #include "common.h"
 
 namespace ifv2 {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short short8v __attribute__((ext_vector_type(8)));
 
 namespace {
 
 constexpr int D = 128;            // head dim
 constexpr int G = 16;             // heads per KV head
-constexpr int KS = D + 8;         // LDS row stride of a K block, in bf16 (pad: conflict-free 16 B row reads)
-constexpr int VS = kBlock + 8;    // LDS row stride of a transposed V block
-constexpr int K_ELEMS = kBlock * KS;
-constexpr int V_ELEMS = D * VS;
-constexpr int STAGE_ELEMS = K_ELEMS + V_ELEMS;          // 17920 bf16 = 35840 B per stage
+constexpr int TILE_ELEMS = kBlock * D;            // one K or V block in LDS: 64 rows x 256 B, unpadded
+constexpr int STAGE_ELEMS = 2 * TILE_ELEMS;       // K then V: 32 KB per stage
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr int WAIT_VMCNT0 = 0x0F70;               // s_waitcnt vmcnt(0), other counters untouched
 
 struct AttnArgs {
     const uint16_t *q, *k, *v;
@@ -47,62 +54,29 @@ struct AttnArgs {
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void glb_void;
+
 template <int NW, int TPW>
 struct TileKernel {
     static constexpr int T = NW * TPW;
     static constexpr int NTHR = NW * 64;
-    static constexpr int KCH = 1024 / NTHR;      // 16-byte K chunks per thread per block
-    static constexpr int VIT = 1024 / NTHR;      // (key quad, dim pair) V items per thread per block
+    static_assert(32 % NW == 0 || NW == 32, "32 one-KB load instructions are dealt round-robin to the waves");
 
-    struct Prefetch {
-        uint4 k[KCH];
-        uint32_t v[VIT][4];
-    };
-
-    // ---- global -> registers for block j of the sequence (rows past the sequence end read as zero)
-    __device__ static inline void load_block(const AttnArgs &a, const uint16_t *kb, const uint16_t *vb, int j, int len,
-                                             int tid, Prefetch &pf) {
+    // ---- block j of the sequence: global -> LDS stage, asynchronously.  One instruction moves 1 KB = 4 rows;
+    // lane l fills LDS slot (row 4q + l/16, physical chunk l%16), which holds logical chunk (l%16) ^ (row%16).
+    // Rows past the end of the sequence re-read the last valid row (finite data, always masked by causality).
+    __device__ static inline void issue_block_load(const AttnArgs &a, const uint16_t *kb, const uint16_t *vb, int j,
+                                                   int len, uint16_t *stage, int w, int lane) {
 #pragma unroll
-        for (int r = 0; r < KCH; ++r) {
-            const int c = tid + r * NTHR;
-            const int row = c >> 4, col = (c & 15) * 8;
-            const int tok = j * kBlock + row;
-            pf.k[r] = tok < len ? *reinterpret_cast<const uint4 *>(kb + (int64_t)tok * a.map.kv_tok_stride + col)
-                                : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int r = 0; r < VIT; ++r) {
-            const int it = tid + r * NTHR;
-            const int kq = it >> 6, dp = it & 63;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int tok = j * kBlock + kq * 4 + kk;
-                pf.v[r][kk] = tok < len ? *reinterpret_cast<const uint32_t *>(vb + (int64_t)tok * a.map.kv_tok_stride + dp * 2)
-                                        : 0u;
-            }
-        }
-    }
-
-    // ---- registers -> LDS stage: K row-major, V transposed ([dim][key])
-    __device__ static inline void store_block(uint16_t *stage, int tid, const Prefetch &pf) {
-        uint16_t *ks = stage, *vt = stage + K_ELEMS;
-#pragma unroll
-        for (int r = 0; r < KCH; ++r) {
-            const int c = tid + r * NTHR;
-            const int row = c >> 4, col = (c & 15) * 8;
-            *reinterpret_cast<uint4 *>(ks + row * KS + col) = pf.k[r];
-        }
-#pragma unroll
-        for (int r = 0; r < VIT; ++r) {
-            const int it = tid + r * NTHR;
-            const int kq = it >> 6, dp = it & 63;
-            uint2 lo, hi;   // dim 2dp: low halves of the four keys; dim 2dp+1: high halves
-            lo.x = (pf.v[r][0] & 0xffffu) | (pf.v[r][1] << 16);
-            lo.y = (pf.v[r][2] & 0xffffu) | (pf.v[r][3] << 16);
-            hi.x = (pf.v[r][0] >> 16) | (pf.v[r][1] & 0xffff0000u);
-            hi.y = (pf.v[r][2] >> 16) | (pf.v[r][3] & 0xffff0000u);
-            *reinterpret_cast<uint2 *>(vt + (2 * dp) * VS + kq * 4) = lo;
-            *reinterpret_cast<uint2 *>(vt + (2 * dp + 1) * VS + kq * 4) = hi;
+        for (int qi = w; qi < 32; qi += NW) {
+            const int q16 = qi & 15;                       // 16 instructions per tile
+            const int row = 4 * q16 + (lane >> 4);
+            const int chunk = (lane & 15) ^ (row & 15);
+            const int tok = min(j * kBlock + row, len - 1);
+            const uint16_t *src = (qi < 16 ? kb : vb) + (int64_t)tok * a.map.kv_tok_stride + chunk * 8;
+            uint16_t *dst = stage + (qi < 16 ? 0 : TILE_ELEMS) + q16 * 512;
+            __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)dst, 16, 0, 0);
         }
     }
 
@@ -112,29 +86,46 @@ struct TileKernel {
         float m, l;        // running max (raw logits) and this lane's share of the running sum
     };
 
-    // ---- one (token, block) unit: S^T = K Q^T, online softmax, O^T += V^T P^T
-    __device__ static inline void unit(TokState &st, const uint16_t *stage, int lane, bool diag, int key_limit, float c) {
+    struct LaneOffs {
+        int kx[4];         // K operand: element offset of (row m16, logical chunk 4s+g) in a swizzled tile
+        int vx[8];         // V operand source address of this lane for dim tile dt (transposing read)
+    };
+
+    __device__ static inline LaneOffs lane_offsets(int lane) {
+        LaneOffs o;
         const int m16 = lane & 15, g = lane >> 4;
-        const uint16_t *ks = stage + ((8 * (m16 >> 2) + (m16 & 3)) * KS + g * 8);
-        const uint16_t *vt = stage + K_ELEMS + (m16 * VS + g * 8);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) o.kx[s] = m16 * D + (((4 * s + g) ^ m16) << 3);
+        // transposing read: within a group of 16 lanes, lane L supplies 4 consecutive dims of key row L/4 and
+        // receives, for its dim (= L), the values of 4 consecutive key rows.
+        const int rowlow = 4 * g + (m16 >> 2);
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+            o.vx[dt] = rowlow * D + (((2 * dt + ((m16 >> 1) & 1)) ^ rowlow) << 3) + 4 * (m16 & 1);
+        return o;
+    }
+
+    // ---- one (token, block) unit: S^T = K Q^T, online softmax, O^T += V^T P^T
+    __device__ static inline void unit(TokState &st, const uint16_t *stage, const LaneOffs &lo, int lane, bool diag,
+                                       int key_limit, float c) {
+        const int g = lane >> 4;
         f32x4 acc[4];
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt) {
             acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ks + (32 * (kt >> 1) + 4 * (kt & 1)) * KS + s * 32);
+                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(stage + kt * 16 * D + lo.kx[s]);
                 acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, st.qf[s], acc[kt], 0, 0, 0);
             }
         }
-        if (diag) {   // keys after the query token are masked
+        // acc[kt][r] is key 16*kt + 4*g + r of the block, for head lane%16
+        if (diag) {
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int key = 32 * (kt >> 1) + 8 * g + 4 * (kt & 1) + r;
-                    if (key > key_limit) acc[kt][r] = -INFINITY;
-                }
+                for (int r = 0; r < 4; ++r)
+                    if (16 * kt + 4 * g + r > key_limit) acc[kt][r] = -INFINITY;
         }
         float mx = acc[0][0];
 #pragma unroll
@@ -143,10 +134,15 @@ struct TileKernel {
             for (int r = 0; r < 4; ++r) mx = fmaxf(mx, acc[kt][r]);
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(st.m, mx);
-        const float alpha = fast_exp2((st.m - m_new) * c);
-        const float mc = m_new * c;
-        st.m = m_new;
+        if (__any(mx > st.m)) {          // some head's running max moved: rescale (rare after the first blocks)
+            const float m_new = fmaxf(st.m, mx);
+            const float alpha = fast_exp2((st.m - m_new) * c);
+            st.m = m_new;
+            st.l *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) st.o[dt] *= alpha;
+        }
+        const float mc = st.m * c;
         float ls = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
@@ -155,28 +151,32 @@ struct TileKernel {
                 acc[kt][r] = fast_exp2(acc[kt][r] * c - mc);
                 ls += acc[kt][r];
             }
-        st.l = st.l * alpha + ls;
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) st.o[dt] *= alpha;
+        st.l += ls;
+        // P^T as B operand of k-step s2 (keys 32*s2 ..): slots 0-3 = keys 32*s2 + 4g + r, slots 4-7 = +16
         bf16x8 pb[2];
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
+        for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                pb[s][r] = (__bf16)acc[2 * s][r];
-                pb[s][4 + r] = (__bf16)acc[2 * s + 1][r];
+                pb[s2][r] = (__bf16)acc[2 * s2][r];
+                pb[s2][4 + r] = (__bf16)acc[2 * s2 + 1][r];
             }
+        const uint16_t *vt = stage + TILE_ELEMS;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vt + dt * 16 * VS + s * 32);
-                st.o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[s], st.o[dt], 0, 0, 0);
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const short4v v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) short4v *)(vt + (32 * s2) * D + lo.vx[dt]));
+                const short4v v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) short4v *)(vt + (32 * s2 + 16) * D + lo.vx[dt]));
+                const short8v v8 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+                st.o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v8), pb[s2], st.o[dt], 0, 0, 0);
             }
     }
 
     __device__ static void run(const AttnArgs &a, int num_tiles) {
-        extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+        extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
         uint16_t *stages = smem;
         uint32_t *masks = reinterpret_cast<uint32_t *>(smem + 2 * STAGE_ELEMS);
         int32_t *list_j = reinterpret_cast<int32_t *>(masks + a.nb_cap);
@@ -235,6 +235,7 @@ struct TileKernel {
         } else {
             ne = nblk;
         }
+        if (ne > 0) issue_block_load(a, kb, vb, dense ? 0 : list_j[0], len, stages, w, lane);
 
         // ---- this wave's tokens: ti = i * NW + w (interleaved so the waves' loads stay similar)
         TokState st[TPW];
@@ -255,25 +256,23 @@ struct TileKernel {
         }
         const float c = a.scale * LOG2E;
         const uint32_t full = ntok >= 32 ? 0xffffffffu : ((1u << ntok) - 1u);
+        const LaneOffs lo = lane_offsets(lane);
 
-        Prefetch pf;
-        if (ne > 0) {
-            load_block(a, kb, vb, dense ? 0 : list_j[0], len, tid, pf);
-            store_block(stages, tid, pf);
-        }
+        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
         __syncthreads();
         for (int e = 0; e < ne; ++e) {
             const int j = dense ? e : list_j[e];
             const uint32_t mk = dense ? full : masks[j];
-            if (e + 1 < ne) load_block(a, kb, vb, dense ? e + 1 : list_j[e + 1], len, tid, pf);
+            if (e + 1 < ne)
+                issue_block_load(a, kb, vb, dense ? e + 1 : list_j[e + 1], len, stages + ((e + 1) & 1) * STAGE_ELEMS, w, lane);
             const uint16_t *stage = stages + (e & 1) * STAGE_ELEMS;
             const bool diag = j == bt;
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
                 const int ti = i * NW + w;
-                if (mk & (1u << ti)) unit(st[i], stage, lane, diag, t0 + ti - j * kBlock, c);
+                if (mk & (1u << ti)) unit(st[i], stage, lo, lane, diag, t0 + ti - j * kBlock, c);
             }
-            if (e + 1 < ne) store_block(stages + ((e + 1) & 1) * STAGE_ELEMS, tid, pf);
+            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);     // the next block has landed in LDS
             __syncthreads();
         }
 
@@ -316,7 +315,7 @@ int launch_tile(const Launch &L, const AttnArgs &a0, const int32_t *cu_h) {
     a.nb_cap = a.idx ? (nb_max + 3) / 4 * 4 : 0;
     a.list_cap = a.idx ? min(nb_max, T * L.p->topk_total) : 0;
     const size_t lds = (size_t)2 * STAGE_ELEMS * sizeof(uint16_t) + (size_t)(a.nb_cap + a.list_cap) * 4;
-    if (lds > 160 * 1024) return INFLLMV2_ERR_UNSUPPORTED;      // > ~2.8M tokens per sequence
+    if (lds > 160 * 1024 - 64) return INFLLMV2_ERR_UNSUPPORTED;      // sequences beyond ~3M tokens
     auto kern = attn_tile_kernel<NW, TPW>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -351,7 +350,12 @@ int launch_attn_mfma(const Launch &L, const void *q, const void *k, const void *
     a.dense_below = dense_below;
     a.scale = L.p->softmax_scale;
     a.nb_cap = a.list_cap = 0;
-    return launch_tile<4, 4>(L, a, cu_h);
+    static const char *cfg = getenv("INFLLMV2_ATTN_CFG");      // experiment switch
+    if (cfg && !strcmp(cfg, "8x2")) return launch_tile<8, 2>(L, a, cu_h);
+    if (cfg && !strcmp(cfg, "8x4")) return launch_tile<8, 4>(L, a, cu_h);
+    if (cfg && !strcmp(cfg, "16x2")) return launch_tile<16, 2>(L, a, cu_h);
+    if (cfg && !strcmp(cfg, "4x4")) return launch_tile<4, 4>(L, a, cu_h);
+    return launch_tile<16, 1>(L, a, cu_h);
 }
 
 }  // namespace ifv2
