@@ -202,7 +202,7 @@ def main() -> int:
     return 0
 
 
-def bench_decode(torch, m, synth, iters: int = 20, nsets: int = 4):
+def bench_decode(torch, m, synth, iters: int = 40, nsets: int = 4):
     """Config 4: batch 16, context lengths uniform in [16384, 65536]; K/V and K^{C1} caches precomputed.
     Rotates over `nsets` distinct cache sets so repeated steps do not just hit the Infinity Cache."""
     cfg = synth.CONFIGS["C4"]
@@ -233,13 +233,14 @@ def bench_decode(torch, m, synth, iters: int = 20, nsets: int = 4):
         sets.append((qd, kc_, vc_, kcc))
         del topic
     ws = torch.empty(m.decode_workspace_bytes(gp, B, lmax), dtype=torch.uint8, device="cuda")
+    di = m.DecodeInfo(ctx)
     for s in range(nsets):
-        m.sparse_decode(gp, *sets[s], ctx, workspace=ws)
+        o_, l_, i_ = m.sparse_decode(gp, *sets[s], di, workspace=ws)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for i in range(iters):
-        m.sparse_decode(gp, *sets[i % nsets], ctx, workspace=ws, return_idx=False)
+        m.sparse_decode(gp, *sets[i % nsets], di, workspace=ws, out=o_, lse=l_, idx=i_)
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / iters

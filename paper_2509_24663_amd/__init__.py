@@ -8,6 +8,7 @@ library has not been built, importing the binding raises.
 """
 from .binding import (  # noqa: F401
     BF16,
+    DecodeInfo,
     FP32,
     InfllmV2Error,
     Params,

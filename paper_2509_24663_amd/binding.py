@@ -222,23 +222,34 @@ def decode_workspace_bytes(p: Params, batch: int, max_ctx_len: int) -> int:
     return int(lib().infllmv2_decode_workspace_bytes(ctypes.byref(p), int(batch), int(max_ctx_len)))
 
 
-def sparse_decode(p: Params, q, k_cache, v_cache, kc_cache, ctx_lens, workspace=None, return_idx=True):
+class DecodeInfo:
+    """ctx_lens as the ABI wants them (host + device copy), made once per step and reusable."""
+
+    def __init__(self, ctx_lens):
+        self.ctx_h = torch.as_tensor(ctx_lens, dtype=torch.int32, device="cpu").contiguous()
+        self.ctx_d = self.ctx_h.cuda()
+        self.batch = self.ctx_h.numel()
+        self.max_ctx = int(self.ctx_h.max()) if self.batch else 0
+
+
+def sparse_decode(p: Params, q, k_cache, v_cache, kc_cache, ctx_lens, workspace=None, return_idx=True, out=None,
+                  lse=None, idx=None):
     """Decode step.  q [B, hq, d]; k_cache/v_cache [B, hkv, Lmax, d]; kc_cache [B, hkv, max_nc, d] fp32.
+    ctx_lens: a sequence of ints or a DecodeInfo.  out / lse / idx / workspace: optional buffers to reuse.
     Returns (out [B, hq, d], lse [B, hq], block_idx [B, hkv, topk_total] or None)."""
-    ctx_h = torch.as_tensor(ctx_lens, dtype=torch.int32, device="cpu").contiguous()
-    ctx_d = ctx_h.cuda()
+    di = ctx_lens if isinstance(ctx_lens, DecodeInfo) else DecodeInfo(ctx_lens)
     B = q.shape[0]
-    need = decode_workspace_bytes(p, B, int(ctx_h.max()) if B else 0)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
-    out = torch.empty_like(q)
-    lse = torch.empty((B, p.num_q_heads), dtype=torch.float32, device=q.device)
-    idx = torch.empty((B, p.num_kv_heads, p.topk_total), dtype=torch.int32, device=q.device) if return_idx else None
+        workspace = torch.empty(max(decode_workspace_bytes(p, B, di.max_ctx), 256), dtype=torch.uint8, device=q.device)
+    out = torch.empty_like(q) if out is None else out
+    lse = torch.empty((B, p.num_q_heads), dtype=torch.float32, device=q.device) if lse is None else lse
+    if idx is None and return_idx:
+        idx = torch.empty((B, p.num_kv_heads, p.topk_total), dtype=torch.int32, device=q.device)
     assert k_cache.dim() == 4 and k_cache.stride(3) == 1 and k_cache.stride() == v_cache.stride()
     assert kc_cache.dim() == 4 and kc_cache.is_contiguous()
     st = lib().infllmv2_sparse_decode(ctypes.byref(p), _ptr(q), _ptr(k_cache), _ptr(v_cache), k_cache.stride(0),
                                       k_cache.stride(1), k_cache.stride(2), _ptr(kc_cache), kc_cache.stride(1),
-                                      _ptr(ctx_h), _ptr(ctx_d), B, _ptr(idx), _ptr(out), _ptr(lse),
+                                      _ptr(di.ctx_h), _ptr(di.ctx_d), B, _ptr(idx), _ptr(out), _ptr(lse),
                                       _ptr(workspace), workspace.numel(), _stream())
     _check(st, "infllmv2_sparse_decode")
     return out, lse, idx

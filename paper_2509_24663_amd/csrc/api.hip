@@ -11,6 +11,12 @@ int launch_attn_generic(const Launch &L, const void *q, const void *k, const voi
 int launch_attn_mfma(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
                      int dense_below, void *out, float *lse, const int32_t *cu_h);
 bool attn_mfma_supported(const infllmv2_params *p);
+bool decode_mfma_supported(const infllmv2_params *p);
+size_t decode_mfma_workspace(const infllmv2_params *p, int batch, int max_ctx);
+int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, const void *v, int64_t kv_batch_stride,
+                       int64_t kv_head_stride, int64_t kv_tok_stride, const float *kc, int64_t kc_head_stride,
+                       const int32_t *ctx_h, const int32_t *ctx_d, int batch, int32_t *idx_out, void *out, float *lse,
+                       void *ws, hipStream_t stream);
 }  // namespace ifv2
 
 static int check_params(const infllmv2_params *p) {
@@ -186,7 +192,9 @@ size_t infllmv2_decode_workspace_bytes(const infllmv2_params *p, int32_t batch, 
     if (check_params(p) != INFLLMV2_OK || batch < 0 || max_ctx_len < 0) return 0;
     const size_t rs = align_up((size_t)num_cmp(max_ctx_len, p->cmp_len, p->cmp_stride) + 4, 4);
     const size_t rows = (size_t)batch * p->num_kv_heads;
-    return align_up(rows * rs * sizeof(float), 256) + align_up(rows * p->topk_total * sizeof(int32_t), 256) + 256;
+    const size_t generic = align_up(rows * rs * sizeof(float), 256) + align_up(rows * p->topk_total * sizeof(int32_t), 256) + 256;
+    const size_t fast = decode_mfma_supported(p) ? decode_mfma_workspace(p, batch, max_ctx_len) : 0;
+    return generic > fast ? generic : fast;
 }
 
 int infllmv2_sparse_decode(const infllmv2_params *p, const void *q_d, const void *k_cache_d, const void *v_cache_d,
@@ -213,6 +221,15 @@ int infllmv2_sparse_decode(const infllmv2_params *p, const void *q_d, const void
     const size_t need = infllmv2_decode_workspace_bytes(p, batch, max_ctx);
     if (workspace_d == nullptr || ((uintptr_t)workspace_d & 255) != 0) return INFLLMV2_ERR_INVALID_ARGUMENT;
     if (workspace_bytes < need) return INFLLMV2_ERR_WORKSPACE_TOO_SMALL;
+
+    const bool aligned = (((uintptr_t)q_d | (uintptr_t)k_cache_d | (uintptr_t)v_cache_d | (uintptr_t)kc_cache_d |
+                           (uintptr_t)out_d) & 15) == 0 &&
+                         kv_tok_stride % 8 == 0 && kv_head_stride % 8 == 0 && kv_batch_stride % 8 == 0 &&
+                         kc_head_stride % 4 == 0;
+    if (decode_mfma_supported(p) && aligned)
+        return launch_decode_mfma(p, q_d, k_cache_d, v_cache_d, kv_batch_stride, kv_head_stride, kv_tok_stride,
+                                  kc_cache_d, kc_head_stride, ctx_lens_h, ctx_lens_d, batch, block_idx_out_d, out_d,
+                                  lse_d, workspace_d, (hipStream_t)stream);
 
     const size_t rs = align_up((size_t)num_cmp(max_ctx, p->cmp_len, p->cmp_stride) + 4, 4);
     const size_t rows = (size_t)batch * p->num_kv_heads;

@@ -1,0 +1,134 @@
+// Building blocks shared by the prefill tile kernel and the decode kernel: LDS tile layout, asynchronous
+// block loads and the (token, block) MFMA unit.  bf16 data, G = 16 heads per KV head, d_h = 128.
+#pragma once
+#include "common.h"
+
+namespace ifv2 {
+namespace attn_unit {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short short8v __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void glb_void;
+
+constexpr int D = 128;            // head dim
+constexpr int G = 16;             // heads per KV head
+constexpr int TILE_ELEMS = kBlock * D;            // one K or V block in LDS: 64 rows x 256 B, unpadded
+constexpr int STAGE_ELEMS = 2 * TILE_ELEMS;       // K then V: 32 KB per stage
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr int WAIT_VMCNT0 = 0x0F70;               // s_waitcnt vmcnt(0), other counters untouched
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// One 1 KB piece (4 rows) of a K or V block: global -> LDS, asynchronously.  Lane l fills LDS slot
+// (row 4*q16 + l/16, physical chunk l%16), which holds logical 16-byte chunk (l%16) ^ (row%16) of that row.
+// Rows past the end of the sequence re-read the last valid row (finite data, always masked by causality).
+__device__ inline void load_piece(const uint16_t *base, int64_t tok_stride, int j, int len, uint16_t *tile, int q16,
+                                  int lane) {
+    const int row = 4 * q16 + (lane >> 4);
+    const int chunk = (lane & 15) ^ (row & 15);
+    const int tok = min(j * kBlock + row, len - 1);
+    const uint16_t *src = base + (int64_t)tok * tok_stride + chunk * 8;
+    __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)(tile + q16 * 512), 16, 0, 0);
+}
+
+struct TokState {
+    bf16x8 qf[4];      // Q_t as MFMA B operand: head = lane % 16, dims ks*32 + (lane/16)*8 .. +8
+    f32x4 o[8];        // O_t^T: dim tile dt, dims dt*16 + 4*(lane/16) + r, head = lane % 16
+    float m, l;        // running max (raw logits) and this lane's share of the running sum
+};
+
+struct LaneOffs {
+    int kx[4];         // K operand: element offset of (row m16, logical chunk 4s+g) in a swizzled tile
+    int vx[8];         // V operand source address of this lane for dim tile dt (transposing read)
+};
+
+__device__ inline LaneOffs lane_offsets(int lane) {
+    LaneOffs o;
+    const int m16 = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) o.kx[s] = m16 * D + (((4 * s + g) ^ m16) << 3);
+    // transposing read: within a group of 16 lanes, lane L supplies 4 consecutive dims of key row L/4 and
+    // receives, for its dim (= L), the values of 4 consecutive key rows.
+    const int rowlow = 4 * g + (m16 >> 2);
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+        o.vx[dt] = rowlow * D + (((2 * dt + ((m16 >> 1) & 1)) ^ rowlow) << 3) + 4 * (m16 & 1);
+    return o;
+}
+
+// ---- one (token, block) unit: S^T = K Q^T, online softmax, O^T += V^T P^T
+__device__ inline void unit(TokState &st, const uint16_t *stage, const LaneOffs &lo, int lane, bool diag,
+                                   int key_limit, float c) {
+    const int g = lane >> 4;
+    f32x4 acc[4];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+        acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(stage + kt * 16 * D + lo.kx[s]);
+            acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, st.qf[s], acc[kt], 0, 0, 0);
+        }
+    }
+    // acc[kt][r] is key 16*kt + 4*g + r of the block, for head lane%16
+    if (diag) {
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (16 * kt + 4 * g + r > key_limit) acc[kt][r] = -INFINITY;
+    }
+    float mx = acc[0][0];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mx = fmaxf(mx, acc[kt][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    if (__any(mx > st.m)) {          // some head's running max moved: rescale (rare after the first blocks)
+        const float m_new = fmaxf(st.m, mx);
+        const float alpha = fast_exp2((st.m - m_new) * c);
+        st.m = m_new;
+        st.l *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) st.o[dt] *= alpha;
+    }
+    const float mc = st.m * c;
+    float ls = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            acc[kt][r] = fast_exp2(acc[kt][r] * c - mc);
+            ls += acc[kt][r];
+        }
+    st.l += ls;
+    // P^T as B operand of k-step s2 (keys 32*s2 ..): slots 0-3 = keys 32*s2 + 4g + r, slots 4-7 = +16
+    bf16x8 pb[2];
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            pb[s2][r] = (__bf16)acc[2 * s2][r];
+            pb[s2][4 + r] = (__bf16)acc[2 * s2 + 1][r];
+        }
+    const uint16_t *vt = stage + TILE_ELEMS;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const short4v v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) short4v *)(vt + (32 * s2) * D + lo.vx[dt]));
+            const short4v v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) short4v *)(vt + (32 * s2 + 16) * D + lo.vx[dt]));
+            const short8v v8 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+            st.o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v8), pb[s2], st.o[dt], 0, 0, 0);
+        }
+}
+
+
+}  // namespace attn_unit
+}  // namespace ifv2

@@ -229,6 +229,61 @@ def test_decode_matches_oracle_and_prefill_row(m, oracle, dtype, hq, hkv, d):
     assert_out_close(to_np(pre["out"])[L - 1], to_np(out)[0], dtype, "decode vs prefill row")
 
 
+def _check_decode(m, oracle, w, ctx, gp, op, dtype):
+    hq, hkv, d = gp.num_q_heads, gp.num_kv_heads, gp.head_dim
+    G = hq // hkv
+    q, kc_, vc_ = to_dev(w["q"], dtype), to_dev(w["k_cache"], dtype), to_dev(w["v_cache"], dtype)
+    B = len(ctx)
+    lmax = w["k_cache"].shape[2]
+    max_nc = max(oracle.num_cmp(lmax, op), 1)
+    kcc = torch.zeros((B, hkv, max_nc, d), dtype=torch.float32, device="cuda")
+    for b, L in enumerate(ctx):
+        nc = oracle.num_cmp(int(L), op)
+        if nc:
+            kcb, _ = m.compress_k(gp, kc_[b, :, :int(L)], [0, int(L)])
+            kcc[b, :, :nc] = kcb[:, :nc]
+    out, lse, idx = m.sparse_decode(gp, q, kc_, vc_, kcc, ctx)
+    torch.cuda.synchronize()
+    out, lse, idx = to_np(out), to_np(lse), to_np(idx)
+    n_sparse = 0
+    for b, L in enumerate(ctx):
+        L = int(L)
+        pos = np.array([L - 1], np.int32)
+        for h in range(hkv):
+            Qh = w["q"][b:b + 1, h * G:(h + 1) * G]
+            Kh, Vh = w["k_cache"][b, h, :L], w["v_cache"][b, h, :L]
+            if L < op.dense_threshold:
+                assert np.all(idx[b, h] == -1)
+                O, Ls = oracle.dense_attn(Qh, pos, Kh, Vh, op)
+            else:
+                n_sparse += 1
+                sh = oracle.block_scores(Qh, pos, oracle.compress_k(Kh, op), op)
+                io, co = oracle.topk_blocks(sh, pos, op, return_cmp=True)
+                check_selection(idx[b, h][None], io, co, pos, op.n_init, op.n_local)
+                O, Ls = oracle.sparse_attn(Qh, pos, Kh, Vh, idx[b, h][None], op)
+            assert_out_close(out[b, h * G:(h + 1) * G], O[0], dtype, "decode out | GPU selection")
+            np.testing.assert_allclose(lse[b, h * G:(h + 1) * G], Ls[0], atol=2e-3 if dtype == "bf16" else 1e-4)
+    return n_sparse
+
+
+def test_decode_dense_switch_and_ragged(m, oracle):
+    """Decode with sequences on both sides of the dense threshold, partial last blocks, tiny contexts."""
+    ctx = [1, 2, 31, 32, 63, 64, 65, 127, 700, 1024, 1023, 2500, 4097]
+    for dtype, hq, hkv, d in [("bf16", 32, 2, 128), ("fp32", 4, 2, 64)]:
+        w = synth.make_decode(ctx, hq, hkv, d, seed=91, dtype=dtype, max_len=4160)
+        gp, op = _params(m, oracle, dtype, hq, hkv, d, n_init=1, n_local=2, topk_total=9, dense_threshold=1024)
+        assert _check_decode(m, oracle, w, ctx, gp, op, dtype) == 3 * hkv
+
+
+def test_decode_c4_full_shape(m, oracle):
+    """BASELINE config 4 at full size: batch 16, context lengths uniform in [16384, 65536], top-k 64."""
+    cfg = synth.CONFIGS["C4"]
+    ctx = synth.draw_ctx_lens(cfg.batch, cfg.ctx_lo, cfg.ctx_hi, cfg.seed)
+    w = synth.make_config(cfg, ctx_lens=ctx)
+    gp, op = m.Params.from_config(cfg), oracle.Params.from_config(cfg)
+    assert _check_decode(m, oracle, w, ctx, gp, op, "bf16") == 32
+
+
 def test_empty_batch_and_empty_sequences(m, oracle):
     gp, op = _params(m, oracle, "bf16", 32, 2, 128)
     q = torch.zeros((0, 32, 128), dtype=torch.bfloat16, device="cuda")
