@@ -59,20 +59,23 @@ __device__ inline LaneOffs lane_offsets(int lane) {
     return o;
 }
 
-// ---- one (token, block) unit: S^T = K Q^T, online softmax, O^T += V^T P^T
-__device__ inline void unit(TokState &st, const uint16_t *stage, const LaneOffs &lo, int lane, bool diag,
-                                   int key_limit, float c) {
-    const int g = lane >> 4;
-    f32x4 acc[4];
+// ---- S^T = K_blk Q_t^T with the K block in a swizzled LDS tile: acc[kt][r] = key 16*kt + 4*(lane/16) + r
+__device__ inline void qk_from_lds(f32x4 (&acc)[4], const bf16x8 (&qf)[4], const uint16_t *ktile, const LaneOffs &lo) {
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) {
         acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(stage + kt * 16 * D + lo.kx[s]);
-            acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, st.qf[s], acc[kt], 0, 0, 0);
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ktile + kt * 16 * D + lo.kx[s]);
+            acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[s], acc[kt], 0, 0, 0);
         }
     }
+}
+
+// ---- online softmax over the 64 logits of a block and O^T += V_blk^T P^T (V block in a swizzled LDS tile)
+__device__ inline void softmax_pv(TokState &st, f32x4 (&acc)[4], const uint16_t *vt, const LaneOffs &lo, int lane,
+                                  bool diag, int key_limit, float c) {
+    const int g = lane >> 4;
     // acc[kt][r] is key 16*kt + 4*g + r of the block, for head lane%16
     if (diag) {
 #pragma unroll
@@ -115,7 +118,6 @@ __device__ inline void unit(TokState &st, const uint16_t *stage, const LaneOffs 
             pb[s2][r] = (__bf16)acc[2 * s2][r];
             pb[s2][4 + r] = (__bf16)acc[2 * s2 + 1][r];
         }
-    const uint16_t *vt = stage + TILE_ELEMS;
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
@@ -129,6 +131,13 @@ __device__ inline void unit(TokState &st, const uint16_t *stage, const LaneOffs 
         }
 }
 
+// ---- one (token, block) unit with both blocks in one LDS stage (K tile, then V tile)
+__device__ inline void unit(TokState &st, const uint16_t *stage, const LaneOffs &lo, int lane, bool diag,
+                            int key_limit, float c) {
+    f32x4 acc[4];
+    qk_from_lds(acc, st.qf, stage, lo);
+    softmax_pv(st, acc, stage + TILE_ELEMS, lo, lane, diag, key_limit, c);
+}
 
 }  // namespace attn_unit
 }  // namespace ifv2

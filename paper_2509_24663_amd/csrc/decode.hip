@@ -1,14 +1,18 @@
 // Decode step for bf16 caches, G = 16, d_h = 128: stages 2-4 of the method for the single query row
 // t = L-1 of every sequence (the row of Alg. 1 / Eq. 2 / Alg. 2 that a prefill would compute last).
 // The step moves ~100 MB (compressed-key cache once, 64 selected K/V blocks per KV head) and does almost no
-// arithmetic, so the work of one (sequence, KV head) pair is split over many workgroups to fill the chip:
+// arithmetic, so the work of one (sequence, KV head) pair is split over many workgroups to fill the chip;
+// the two reductions that need a whole pair are separate small kernels (a kernel boundary is the cheap
+// way to make one workgroup's results visible to another on a multi-die GPU):
 //   scores  : grid (key chunks, pairs)  logits of 128 compressed keys x 16 heads per workgroup, written once
-//             as log2-domain logits, plus per-chunk (max, sum) partials for the softmax normaliser
-//   select  : grid (pairs)              merge the partials, group-sum the normalised scores into LDS,
-//                                        max-pool + top-k by one wavefront (same routine as prefill)
-//   attend  : grid (splits, pairs)      one wavefront per selected block (MFMA unit shared with prefill),
-//                                        the four partial results of a workgroup are merged in LDS
-//   merge   : grid (pairs)              log-sum-exp merge of the per-split partial outputs
+//             as log2-domain logits, plus per-chunk (max, sum) partials of the softmax normaliser
+//   group sum: grid (key chunks, pairs) merge the partials into the normaliser, sum the normalised scores of
+//             the 16 heads for 128 keys
+//   top-k   : the prefill stage-3 kernel on the one row per pair
+//   attend  : grid (splits, pairs)      one wavefront per selected block: K fragments straight from global
+//             memory into MFMA operands, V through a 16 KB LDS tile (MFMA unit shared with prefill); the
+//             eight partial results of a workgroup are merged in LDS
+//   merge   : grid (pairs)              log-sum-exp merge of the per-split partial outputs, writes O and lse
 // K^{C1} is float32; it is split into a bf16 high part and a bf16 residual in registers and both products
 // are accumulated, so the logits carry ~16 mantissa bits of K^{C1} (as in the prefill score kernel).
 #include "attn_unit.h"
@@ -33,6 +37,7 @@ struct DecArgs {
     TopkArgs tk;
     float *z;          // [pairs][16][zs] log2-domain logits c * <q, kc>
     float *part;       // [pairs][nchunk][16][2] (max, sum 2^(z - max)) per chunk
+    float *sh;         // [pairs][zs] group scores S^shared of the query row
     int32_t *idx;      // [pairs][topk_total]
     float *opart;      // [pairs][nsplit][OPART]  partial O^T ([dim][head]) relative to the split's own max
     float *mlpart;     // [pairs][nsplit][16][2]
@@ -50,119 +55,138 @@ __global__ void __launch_bounds__(256) dec_scores_kernel(DecArgs a) {
     const int n16 = lane & 15, g = lane >> 4;
     __shared__ float red[4][16][2];
     float *part = a.part + ((int64_t)pair * a.nchunk + chunk) * 32;
-    const int v = L < a.tk.dense_below ? 0 : visible_cmp(L - 1, a.tk.lc, a.tk.sc);
+    const bool dense = L < a.tk.dense_below;
+    const int v = dense ? 0 : visible_cmp(L - 1, a.tk.lc, a.tk.sc);
+    const float c = a.scale * LOG2E;
     if (chunk * CK >= v) {                       // nothing visible here (or a dense sequence)
         if (tid < 16) { part[tid * 2] = -INFINITY; part[tid * 2 + 1] = 0.f; }
-        return;
-    }
-    const float c = a.scale * LOG2E;
-    const uint16_t *qp = a.q + ((int64_t)b * a.hq + h * G + n16) * D + g * 8;
-    bf16x8 qf[4];
+    } else {
+        const uint16_t *qp = a.q + ((int64_t)b * a.hq + h * G + n16) * D + g * 8;
+        bf16x8 qf[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(qp + s * 32));
-    const float *kcb = a.kc + (int64_t)pair * a.kc_head_stride;
-    float m[4], l[4];
+        for (int s = 0; s < 4; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(qp + s * 32));
+        const float *kcb = a.kc + (int64_t)pair * a.kc_head_stride;
+        float m[4], l[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) { m[r] = -INFINITY; l[r] = 0.f; }
+        for (int r = 0; r < 4; ++r) { m[r] = -INFINITY; l[r] = 0.f; }
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int key = chunk * CK + w * 32 + nt * 16 + n16;
-        const bool valid = key < v;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        const float *kr = kcb + (int64_t)(valid ? key : 0) * D + g * 8;
+        for (int nt = 0; nt < 2; ++nt) {
+            const int key = chunk * CK + w * 32 + nt * 16 + n16;
+            const bool valid = key < v;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            const float *kr = kcb + (int64_t)(valid ? key : 0) * D + g * 8;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const float4 x0 = *reinterpret_cast<const float4 *>(kr + s * 32);
-            const float4 x1 = *reinterpret_cast<const float4 *>(kr + s * 32 + 4);
-            const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-            bf16x8 bh, bl;
+            for (int s = 0; s < 4; ++s) {
+                const float4 x0 = *reinterpret_cast<const float4 *>(kr + s * 32);
+                const float4 x1 = *reinterpret_cast<const float4 *>(kr + s * 32 + 4);
+                const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+                bf16x8 bh, bl;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const __bf16 hi = (__bf16)x[e];
-                bh[e] = hi;
-                bl[e] = (__bf16)(x[e] - (float)hi);
+                for (int e = 0; e < 8; ++e) {
+                    const __bf16 hi = (__bf16)x[e];
+                    bh[e] = hi;
+                    bl[e] = (__bf16)(x[e] - (float)hi);
+                }
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[s], bh, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[s], bl, acc, 0, 0, 0);
             }
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[s], bh, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[s], bl, acc, 0, 0, 0);
+            // acc[r] = <q_head(4g+r), kc_key>
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float zc = acc[r] * c;
+                if (valid) {
+                    a.z[((int64_t)pair * G + 4 * g + r) * a.zs + key] = zc;
+                    const float mn = fmaxf(m[r], zc);
+                    l[r] = l[r] * fast_exp2(m[r] - mn) + fast_exp2(zc - mn);
+                    m[r] = mn;
+                }
+            }
         }
-        // acc[r] = <q_head(4g+r), kc_key>
+        // merge over the 16 key lanes, then over the 4 waves
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float zc = acc[r] * c;
-            if (valid) {
-                a.z[((int64_t)pair * G + 4 * g + r) * a.zs + key] = zc;
-                const float mn = fmaxf(m[r], zc);
-                l[r] = l[r] * fast_exp2(m[r] - mn) + fast_exp2(zc - mn);
-                m[r] = mn;
+            float mm = m[r], ll = l[r];
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) {
+                const float mo = __shfl_xor(mm, o), lo = __shfl_xor(ll, o);
+                const float mn = fmaxf(mm, mo);
+                const float ms = mn == -INFINITY ? 0.f : mn;
+                ll = ll * fast_exp2(mm - ms) + lo * fast_exp2(mo - ms);
+                mm = mn;
             }
+            if (n16 == 0) { red[w][4 * g + r][0] = mm; red[w][4 * g + r][1] = ll; }
+        }
+        __syncthreads();
+        if (tid < 16) {
+            float mm = -INFINITY;
+            for (int k = 0; k < 4; ++k) mm = fmaxf(mm, red[k][tid][0]);
+            float ll = 0.f;
+            for (int k = 0; k < 4; ++k)
+                if (red[k][tid][0] != -INFINITY) ll += red[k][tid][1] * fast_exp2(red[k][tid][0] - mm);
+            part[tid * 2] = mm;
+            part[tid * 2 + 1] = ll;
         }
     }
-    // merge over the 16 key lanes, then over the 4 waves
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        float mm = m[r], ll = l[r];
-#pragma unroll
-        for (int o = 1; o < 16; o <<= 1) {
-            const float mo = __shfl_xor(mm, o), lo = __shfl_xor(ll, o);
+}
+
+// ------------------------------------------------------------------------------------------ group sum
+// S^shared[i] = sum over the 16 heads of 2^(z[g][i] - lse2[g]) for the 128 keys of one chunk.
+__global__ void __launch_bounds__(256) dec_gsum_kernel(DecArgs a) {
+    __shared__ float red[16][16][2];
+    __shared__ float lse2[16];
+    __shared__ float half_sum[128];
+    const int chunk = blockIdx.x, pair = blockIdx.y;
+    const int b = pair / a.hkv;
+    const int L = a.ctx[b];
+    const int tid = threadIdx.x;
+    if (L < a.tk.dense_below) return;
+    const int v = visible_cmp(L - 1, a.tk.lc, a.tk.sc);
+    if (chunk * CK >= v) return;
+    {   // log2 of sum_i 2^z per head: 16 threads per head over the chunk partials, then 16 -> 1
+        const int head = tid & 15, pg = tid >> 4;
+        const float *pp = a.part + (int64_t)pair * a.nchunk * 32 + head * 2;
+        float mm = -INFINITY, ll = 0.f;
+        for (int ch = pg; ch < a.nchunk; ch += 16) {
+            const float mo = pp[ch * 32], lo = pp[ch * 32 + 1];
             const float mn = fmaxf(mm, mo);
             const float ms = mn == -INFINITY ? 0.f : mn;
             ll = ll * fast_exp2(mm - ms) + lo * fast_exp2(mo - ms);
             mm = mn;
         }
-        if (n16 == 0) { red[w][4 * g + r][0] = mm; red[w][4 * g + r][1] = ll; }
+        red[pg][head][0] = mm;
+        red[pg][head][1] = ll;
+        __syncthreads();
+        if (tid < 16) {
+            float m2 = -INFINITY;
+            for (int k = 0; k < 16; ++k) m2 = fmaxf(m2, red[k][tid][0]);
+            float l2 = 0.f;
+            for (int k = 0; k < 16; ++k)
+                if (red[k][tid][0] != -INFINITY) l2 += red[k][tid][1] * fast_exp2(red[k][tid][0] - m2);
+            lse2[tid] = m2 + __log2f(l2);
+        }
+        __syncthreads();
     }
-    __syncthreads();
-    if (tid < 16) {
-        float mm = -INFINITY;
-        for (int k = 0; k < 4; ++k) mm = fmaxf(mm, red[k][tid][0]);
-        float ll = 0.f;
-        for (int k = 0; k < 4; ++k)
-            if (red[k][tid][0] != -INFINITY) ll += red[k][tid][1] * fast_exp2(red[k][tid][0] - mm);
-        part[tid * 2] = mm;
-        part[tid * 2 + 1] = ll;
-    }
-}
-
-// ------------------------------------------------------------------------------------------ select
-template <int NCH>
-__global__ void __launch_bounds__(256) dec_select_kernel(DecArgs a) {
-    extern __shared__ float sh[];                 // [zs] group scores, then (NCH == 0) the top-k key area
-    __shared__ float lse2[16];
-    const int pair = blockIdx.x;
-    const int b = pair / a.hkv;
-    const int L = a.ctx[b];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    int32_t *out = a.idx + (int64_t)pair * a.tk.topk_total;
-    if (L < a.tk.dense_below) {
-        for (int j = tid; j < a.tk.topk_total; j += 256) out[j] = -1;
-        return;
-    }
-    const int v = visible_cmp(L - 1, a.tk.lc, a.tk.sc);
-    if (tid < 16) {
-        const float *part = a.part + (int64_t)pair * a.nchunk * 32 + tid * 2;
-        float mm = -INFINITY;
-        for (int ch = 0; ch < a.nchunk; ++ch) mm = fmaxf(mm, part[ch * 32]);
-        float ll = 0.f;
-        for (int ch = 0; ch < a.nchunk; ++ch)
-            if (part[ch * 32] != -INFINITY) ll += part[ch * 32 + 1] * fast_exp2(part[ch * 32] - mm);
-        lse2[tid] = mm + __log2f(ll);
-    }
-    __syncthreads();
-    const float *zb = a.z + (int64_t)pair * G * a.zs;
-    for (int i = tid; i < v; i += 256) {
-        float s = 0.f;
+    const int key = chunk * CK + (tid & 127), hh = tid >> 7;      // two threads per key, 8 heads each
+    float sum = 0.f;
+    if (key < v) {
+        const float *zb = a.z + ((int64_t)pair * G + hh * 8) * a.zs + key;
 #pragma unroll
-        for (int gq = 0; gq < G; ++gq) s += fast_exp2(zb[(int64_t)gq * a.zs + i] - lse2[gq]);
-        sh[i] = s;
+        for (int gq = 0; gq < 8; ++gq) sum += fast_exp2(zb[(int64_t)gq * a.zs] - lse2[hh * 8 + gq]);
     }
+    if (hh == 1) half_sum[tid & 127] = sum;
     __syncthreads();
-    if (w == 0) topk_row<NCH>(sh, L - 1, a.tk, out, reinterpret_cast<uint32_t *>(sh + a.zs), lane);
+    if (hh == 0 && key < v) a.sh[(int64_t)pair * a.zs + key] = sum + half_sum[tid];
 }
 
-// ------------------------------------------------------------------------------------------ attend
-__global__ void __launch_bounds__(256) dec_attn_kernel(DecArgs a) {
-    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];     // 4 stages of 32 KB, one per wave
-    __shared__ float wm[4][16], wl[4][16];
+// ------------------------------------------------------------------------------------------ attend + merge
+#ifndef IFV2_DEC_AW
+#define IFV2_DEC_AW 8
+#endif
+constexpr int AW = IFV2_DEC_AW;   // waves (= selected blocks) per attend workgroup
+
+__global__ void __launch_bounds__(AW * 64) dec_attn_kernel(DecArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];     // AW V tiles of 16 KB, one per wave
+    __shared__ float wm[AW][16], wl[AW][16];
     const int split = blockIdx.x, pair = blockIdx.y;
     const int b = pair / a.hkv, h = pair - b * a.hkv;
     const int L = a.ctx[b];
@@ -170,14 +194,15 @@ __global__ void __launch_bounds__(256) dec_attn_kernel(DecArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m16 = lane & 15, g = lane >> 4;
     const bool dense = L < a.tk.dense_below;
-    const int e = split * 4 + w;                                          // entry of the block list
+    const int e = split * AW + w;                                         // entry of the block list
     int j = -1;
     if (dense) j = e <= bt ? e : -1;
     else if (e < a.tk.topk_total) j = a.idx[(int64_t)pair * a.tk.topk_total + e];
     if (j > bt) j = -1;
-    uint16_t *stage = smem + w * STAGE_ELEMS;
+    uint16_t *vtile = smem + w * TILE_ELEMS;
     const uint16_t *kb = a.k + (int64_t)b * a.kv_batch_stride + (int64_t)h * a.kv_head_stride;
     const uint16_t *vb = a.v + (int64_t)b * a.kv_batch_stride + (int64_t)h * a.kv_head_stride;
+    const float c = a.scale * LOG2E;
     TokState st;
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) st.o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -185,69 +210,105 @@ __global__ void __launch_bounds__(256) dec_attn_kernel(DecArgs a) {
     st.l = 0.f;
     if (j >= 0) {
 #pragma unroll
-        for (int qi = 0; qi < 32; ++qi)
-            load_piece(qi < 16 ? kb : vb, a.kv_tok_stride, j, L, stage + (qi < 16 ? 0 : TILE_ELEMS), qi & 15, lane);
+        for (int qi = 0; qi < 16; ++qi) load_piece(vb, a.kv_tok_stride, j, L, vtile, qi, lane);
+        // K fragments as MFMA A operands, straight from global memory: row 16*kt + m16, dims 32*s + 8*g ..
+        bf16x8 kf[4][4];
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+            const int tok = min(j * kBlock + 16 * kt + m16, L - 1);
+            const uint16_t *kr = kb + (int64_t)tok * a.kv_tok_stride + g * 8;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) kf[kt][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(kr + s * 32));
+        }
         const uint16_t *qp = a.q + ((int64_t)b * a.hq + h * G + m16) * D + g * 8;
 #pragma unroll
         for (int s = 0; s < 4; ++s) st.qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(qp + s * 32));
         const LaneOffs lo = lane_offsets(lane);
+        f32x4 acc[4];
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+            acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][s], st.qf[s], acc[kt], 0, 0, 0);
+        }
         __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-        unit(st, stage, lo, lane, j == bt, t - j * kBlock, a.scale * LOG2E);
+        softmax_pv(st, acc, vtile, lo, lane, j == bt, t - j * kBlock, c);
         st.l += __shfl_xor(st.l, 16);
         st.l += __shfl_xor(st.l, 32);
     }
     if (g == 0) { wm[w][m16] = st.m; wl[w][m16] = st.l; }
-    __syncthreads();                                  // every wave is done with its K/V stage: reuse as scratch
-    float *scr = reinterpret_cast<float *>(smem);      // [4 waves][dim][head]
+    __syncthreads();                                  // every wave is done with its V tile: reuse as scratch
+    float *scr = reinterpret_cast<float *>(smem);      // [AW waves][dim][head]
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) scr[w * OPART + (dt * 16 + 4 * g + r) * G + m16] = st.o[dt][r];
     __syncthreads();
-    const float c = a.scale * LOG2E;
     float *op = a.opart + ((int64_t)pair * a.nsplit + split) * OPART;
-    for (int o = tid; o < OPART; o += 256) {
+    for (int o = tid; o < OPART; o += AW * 64) {
         const int head = o & 15;
-        const float mm = fmaxf(fmaxf(wm[0][head], wm[1][head]), fmaxf(wm[2][head], wm[3][head]));
+        float mm = -INFINITY;
+#pragma unroll
+        for (int k = 0; k < AW; ++k) mm = fmaxf(mm, wm[k][head]);
         float acc = 0.f;
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
+        for (int k = 0; k < AW; ++k)
             if (wm[k][head] != -INFINITY) acc += scr[k * OPART + o] * fast_exp2((wm[k][head] - mm) * c);
         op[o] = acc;
     }
     if (tid < 16) {
-        const float mm = fmaxf(fmaxf(wm[0][tid], wm[1][tid]), fmaxf(wm[2][tid], wm[3][tid]));
+        float mm = -INFINITY;
+        for (int k = 0; k < AW; ++k) mm = fmaxf(mm, wm[k][tid]);
         float ll = 0.f;
-        for (int k = 0; k < 4; ++k)
+        for (int k = 0; k < AW; ++k)
             if (wm[k][tid] != -INFINITY) ll += wl[k][tid] * fast_exp2((wm[k][tid] - mm) * c);
         float *ml = a.mlpart + ((int64_t)pair * a.nsplit + split) * 32;
         ml[tid * 2] = mm;
         ml[tid * 2 + 1] = ll;
     }
+
 }
 
 // ------------------------------------------------------------------------------------------ merge
 __global__ void __launch_bounds__(256) dec_merge_kernel(DecArgs a) {
+    extern __shared__ float wgt[];                     // [nsplit][16] weights of the splits
+    __shared__ float mtot[16], ltot[16];
     const int pair = blockIdx.x;
     const int b = pair / a.hkv, h = pair - b * a.hkv;
     const int tid = threadIdx.x;
-    const int head = tid & 15, dg = tid >> 4;          // 16 heads x 16 groups of 8 dims
     const float c = a.scale * LOG2E;
-    const float *ml = a.mlpart + (int64_t)pair * a.nsplit * 32 + head * 2;
-    float mm = -INFINITY;
-    for (int s = 0; s < a.nsplit; ++s) mm = fmaxf(mm, ml[s * 32]);
-    float ll = 0.f, o[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = 0.f;
-    for (int s = 0; s < a.nsplit; ++s) {
-        const float ms = ml[s * 32];
-        if (ms == -INFINITY) continue;
-        const float wgt = fast_exp2((ms - mm) * c);
-        ll += ml[s * 32 + 1] * wgt;
-        const float *op = a.opart + ((int64_t)pair * a.nsplit + s) * OPART + (dg * 8) * G + head;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] += op[e * G] * wgt;
+    const float *ml = a.mlpart + (int64_t)pair * a.nsplit * 32;
+    if (tid < 16) {
+        float mm = -INFINITY;
+        for (int s = 0; s < a.nsplit; ++s) mm = fmaxf(mm, ml[s * 32 + tid * 2]);
+        mtot[tid] = mm;
     }
+    __syncthreads();
+    for (int i = tid; i < a.nsplit * 16; i += 256) {
+        const int s = i >> 4, head = i & 15;
+        const float ms = ml[s * 32 + head * 2];
+        wgt[i] = ms == -INFINITY ? 0.f : fast_exp2((ms - mtot[head]) * c);
+    }
+    __syncthreads();
+    if (tid < 16) {
+        float ll = 0.f;
+        for (int s = 0; s < a.nsplit; ++s) ll += ml[s * 32 + tid * 2 + 1] * wgt[s * 16 + tid];
+        ltot[tid] = ll;
+    }
+    __syncthreads();
+    const int head = tid & 15, dg = tid >> 4;          // 16 heads x 16 groups of 8 dims
+    float o[8];
+#pragma unroll
+    for (int e2 = 0; e2 < 8; ++e2) o[e2] = 0.f;
+    const float *opb = a.opart + (int64_t)pair * a.nsplit * OPART + (dg * 8) * G + head;
+#pragma unroll 4
+    for (int s = 0; s < a.nsplit; ++s) {
+        const float wg = wgt[s * 16 + head];
+#pragma unroll
+        for (int e2 = 0; e2 < 8; ++e2) o[e2] += opb[(int64_t)s * OPART + e2 * G] * wg;
+    }
+    const float ll = ltot[head];
     const float inv = ll > 0.f ? 1.f / ll : 0.f;
     uint4 pk;
     pk.x = (uint32_t)float_to_bf16(o[0] * inv) | ((uint32_t)float_to_bf16(o[1] * inv) << 16);
@@ -255,14 +316,14 @@ __global__ void __launch_bounds__(256) dec_merge_kernel(DecArgs a) {
     pk.z = (uint32_t)float_to_bf16(o[4] * inv) | ((uint32_t)float_to_bf16(o[5] * inv) << 16);
     pk.w = (uint32_t)float_to_bf16(o[6] * inv) | ((uint32_t)float_to_bf16(o[7] * inv) << 16);
     *reinterpret_cast<uint4 *>(a.out + ((int64_t)b * a.hq + h * G + head) * D + dg * 8) = pk;
-    if (a.lse != nullptr && dg == 0) a.lse[(int64_t)b * a.hq + h * G + head] = mm * a.scale + __logf(ll);
+    if (a.lse != nullptr && dg == 0) a.lse[(int64_t)b * a.hq + h * G + head] = mtot[head] * a.scale + __logf(ll);
 }
 
 inline size_t align_up(size_t x, size_t al) { return (x + al - 1) / al * al; }
 
 struct DecLayout {
     int zs, nchunk, nsplit;
-    size_t off_part, off_idx, off_opart, off_ml, total;
+    size_t off_part, off_sh, off_idx, off_opart, off_ml, total;
 };
 
 DecLayout dec_layout(const infllmv2_params *p, int batch, int max_ctx, int dense_blocks) {
@@ -273,10 +334,12 @@ DecLayout dec_layout(const infllmv2_params *p, int batch, int max_ctx, int dense
     d.nchunk = (max_nc + CK - 1) / CK;
     if (d.nchunk < 1) d.nchunk = 1;
     const int entries = p->topk_total > dense_blocks ? p->topk_total : dense_blocks;
-    d.nsplit = (entries + 3) / 4;
+    d.nsplit = (entries + AW - 1) / AW;
     size_t off = align_up(pairs * G * d.zs * sizeof(float), 256);
     d.off_part = off;
     off += align_up(pairs * d.nchunk * 32 * sizeof(float), 256);
+    d.off_sh = off;
+    off += align_up(pairs * d.zs * sizeof(float), 256);
     d.off_idx = off;
     off += align_up(pairs * p->topk_total * sizeof(int32_t), 256);
     d.off_opart = off;
@@ -332,6 +395,7 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     char *base = (char *)ws;
     a.z = (float *)base;
     a.part = (float *)(base + d.off_part);
+    a.sh = (float *)(base + d.off_sh);
     a.idx = idx_out ? idx_out : (int32_t *)(base + d.off_idx);
     a.opart = (float *)(base + d.off_opart);
     a.mlpart = (float *)(base + d.off_ml);
@@ -342,20 +406,22 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     a.nsplit = d.nsplit;
 
     hipLaunchKernelGGL(dec_scores_kernel, dim3(d.nchunk, pairs), dim3(256), 0, stream, a);
-    const int nch = ((max_ctx + kBlock - 1) / kBlock + 63) / 64;
-    size_t sel_lds = (size_t)d.zs * sizeof(float);
-    if (nch <= 4) hipLaunchKernelGGL(dec_select_kernel<4>, dim3(pairs), dim3(256), sel_lds, stream, a);
-    else if (nch <= 16) hipLaunchKernelGGL(dec_select_kernel<16>, dim3(pairs), dim3(256), sel_lds, stream, a);
-    else if (nch <= 32) hipLaunchKernelGGL(dec_select_kernel<32>, dim3(pairs), dim3(256), sel_lds, stream, a);
-    else {
-        sel_lds += (size_t)nch * 64 * sizeof(uint32_t);
-        if (sel_lds > 160 * 1024 - 256) return INFLLMV2_ERR_UNSUPPORTED;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(dec_select_kernel<0>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_lds);
-        if (e != hipSuccess) return INFLLMV2_ERR_HIP;
-        hipLaunchKernelGGL(dec_select_kernel<0>, dim3(pairs), dim3(256), sel_lds, stream, a);
+    hipLaunchKernelGGL(dec_gsum_kernel, dim3(d.nchunk, pairs), dim3(256), 0, stream, a);
+    {   // max-pool + top-k: the prefill kernel on the one row per pair
+        RowMap m;
+        m.cu = nullptr;
+        m.cu_c = nullptr;
+        m.ctx = ctx_d;
+        m.batch = batch;
+        m.total_rows = batch;
+        m.num_kv_heads = p->num_kv_heads;
+        m.kv_tok_stride = m.kv_head_stride = m.kv_batch_stride = 0;
+        m.kc_total_c = m.kc_head_stride = 0;
+        Launch L{p, m, stream, max_ctx};
+        const int st = launch_topk(L, a.sh, d.zs, a.idx);
+        if (st) return st;
     }
-    const size_t attn_lds = (size_t)4 * STAGE_ELEMS * sizeof(uint16_t);
+    const size_t attn_lds = (size_t)AW * TILE_ELEMS * sizeof(uint16_t);
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(dec_attn_kernel),
@@ -363,8 +429,8 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
         if (e != hipSuccess) return INFLLMV2_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL(dec_attn_kernel, dim3(d.nsplit, pairs), dim3(256), attn_lds, stream, a);
-    hipLaunchKernelGGL(dec_merge_kernel, dim3(pairs), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(dec_attn_kernel, dim3(d.nsplit, pairs), dim3(AW * 64), attn_lds, stream, a);
+    hipLaunchKernelGGL(dec_merge_kernel, dim3(pairs), dim3(256), (size_t)d.nsplit * 16 * sizeof(float), stream, a);
     return hip_status(hipGetLastError());
 }
 

@@ -4,7 +4,7 @@
 namespace ifv2 {
 
 // NCH > 0: pooled keys live in NCH registers per lane; NCH == 0: in LDS.
-template <int NCH>
+template <int NCH, bool FAST>
 __global__ void __launch_bounds__(256)
 topk_blocks_kernel(const float *__restrict__ s_shared, int64_t row_stride, RowMap map, TopkArgs a,
                    int32_t *__restrict__ idx, int lds_keys_per_wave) {
@@ -18,7 +18,7 @@ topk_blocks_kernel(const float *__restrict__ s_shared, int64_t row_stride, RowMa
         for (int j = lane; j < a.topk_total; j += 64) out[j] = -1;
         return;
     }
-    topk_row<NCH>(s_shared + head_row(map, h, row) * row_stride, loc.pos, a, out,
+    topk_row<NCH, FAST>(s_shared + head_row(map, h, row) * row_stride, loc.pos, a, out,
                   lds_keys + (size_t)w * lds_keys_per_wave, lane);
 }
 
@@ -26,7 +26,12 @@ template <int NCH>
 static int launch_n(const Launch &L, const float *s, int64_t rs, int32_t *idx, const TopkArgs &a, size_t lds, int per_wave) {
     dim3 grid((L.map.total_rows + 3) / 4, L.p->num_kv_heads);
     if (grid.x == 0) return INFLLMV2_OK;
-    hipLaunchKernelGGL((topk_blocks_kernel<NCH>), grid, dim3(256), lds, L.stream, s, rs, L.map, a, idx, per_wave);
+    const bool fast = NCH > 0 && a.pool_len == 5 && a.pool_stride == 4 && a.pool_pad == 0 && rs % 4 == 0 &&
+                      ((uintptr_t)s & 15) == 0;
+    if (fast)
+        hipLaunchKernelGGL((topk_blocks_kernel<NCH, true>), grid, dim3(256), lds, L.stream, s, rs, L.map, a, idx, per_wave);
+    else
+        hipLaunchKernelGGL((topk_blocks_kernel<NCH, false>), grid, dim3(256), lds, L.stream, s, rs, L.map, a, idx, per_wave);
     return hip_status(hipGetLastError());
 }
 

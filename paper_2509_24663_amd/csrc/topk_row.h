@@ -17,10 +17,30 @@ struct TopkArgs {
     int dense_below;   // rows of sequences shorter than this get an all -1 list (they attend densely)
 };
 
+// Bit descent over the first N register chunks: on return p is either (exact) a value with exactly kr keys
+// >= p, or the kr-th largest key, with gt = number of keys > p.
+template <int N, int NK>
+__device__ inline void descend(const uint32_t (&keys)[NK], int kr, uint32_t &p, bool &exact, int &gt) {
+    static_assert(N <= NK, "chunk count");
+    for (int b = 31; b >= 0; --b) {
+        const uint32_t cand = p | (1u << b);
+        int cnt = 0;
+#pragma unroll
+        for (int c = 0; c < N; ++c) cnt += __popcll(__ballot(keys[c] >= cand));
+        if (cnt >= kr) {
+            p = cand;
+            if (cnt == kr) { exact = true; return; }
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < N; ++c) gt += __popcll(__ballot(keys[c] > p));
+}
+
 // srow: the row's group scores (global or LDS), t: query position, out: topk_total entries.
 // NCH > 0: pooled keys live in NCH registers per lane (blocks j = c*64 + lane, needs nblk <= 64*NCH);
 // NCH == 0: they live in lk[] (LDS, at least 64*ceil(nblk/64) words owned by this wave).
-template <int NCH>
+// FAST: the pooling is the paper's (l = 5, s = 4, no shift) and srow is 16-byte aligned: vector loads.
+template <int NCH, bool FAST = false>
 __device__ inline void topk_row(const float *srow, int t, const TopkArgs &a, int32_t *out, uint32_t *lk, int lane) {
     const int bt = t / kBlock, nblk = bt + 1;
     const int v = visible_cmp(t, a.lc, a.sc);
@@ -58,7 +78,35 @@ __device__ inline void topk_row(const float *srow, int t, const TopkArgs &a, int
         }
         return __float_as_uint(m);
     };
-    if (NCH > 0) {
+    if (NCH > 0 && FAST) {
+        // pool window = [4j, 4j+5): one aligned 16-byte load plus one scalar per block, all issued up front
+        // with addresses clamped into the visible prefix (so nothing branches and nothing is read out of
+        // bounds); invisible or forced entries are masked afterwards.
+        const int vlast = max(v - 1, 0);
+#pragma unroll
+        for (int c0 = 0; c0 < NCH; c0 += 8) {
+            float4 q4[8];
+            float f5[8];
+#pragma unroll
+            for (int c = c0; c < c0 + 8 && c < NCH; ++c) {
+                const int i0 = 4 * (c * 64 + lane);
+                q4[c - c0] = *reinterpret_cast<const float4 *>(srow + min(i0, vlast & ~3));
+                f5[c - c0] = srow[min(i0 + 4, vlast)];
+            }
+#pragma unroll
+            for (int c = c0; c < c0 + 8 && c < NCH; ++c) {
+                const int j = c * 64 + lane, i0 = 4 * j;
+                float m = 0.f;
+                m = i0 < v ? fmaxf(m, q4[c - c0].x) : m;
+                m = i0 + 1 < v ? fmaxf(m, q4[c - c0].y) : m;
+                m = i0 + 2 < v ? fmaxf(m, q4[c - c0].z) : m;
+                m = i0 + 3 < v ? fmaxf(m, q4[c - c0].w) : m;
+                m = i0 + 4 < v ? fmaxf(m, f5[c - c0]) : m;
+                const bool dead = j >= nblk || j < f_init || j >= f_lo;
+                keys[c] = dead ? 0u : __float_as_uint(m);
+            }
+        }
+    } else if (NCH > 0) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
             if (c < nch) keys[c] = pooled(c * 64 + lane);
@@ -69,38 +117,35 @@ __device__ inline void topk_row(const float *srow, int t, const TopkArgs &a, int
     auto live = [&](int j) -> bool { return j < nblk && !(j < f_init || j >= f_lo); };
     auto key_at = [&](int c) -> uint32_t { return NCH > 0 ? keys[c] : lk[c * 64 + lane]; };
 
-    // ---- k-th largest by bit descent (kr >= 0; kr == 0 keeps only the forced blocks)
+    // ---- k-th largest by bit descent (kr >= 0; kr == 0 keeps only the forced blocks).
+    // Dead slots (forced blocks, blocks past the query) hold key 0 and every candidate is >= 1, so they are
+    // never counted; the register variant therefore runs straight-line over a compile-time chunk count.
     if (kr > 0) {
         uint32_t p = 0;
         bool exact = false;
-        for (int b = 31; b >= 0; --b) {
-            const uint32_t cand = p | (1u << b);
-            int cnt = 0;
-            if (NCH > 0) {
-#pragma unroll
-                for (int c = 0; c < NCH; ++c)
-                    if (c < nch) cnt += __popcll(__ballot(live(c * 64 + lane) && keys[c] >= cand));
-            } else {
-                for (int c = 0; c < nch; ++c) cnt += __popcll(__ballot(live(c * 64 + lane) && key_at(c) >= cand));
+        int gt = 0;
+        if (NCH > 0) {
+            if (nch * 4 <= NCH) descend<(NCH + 3) / 4>(keys, kr, p, exact, gt);
+            else if (nch * 2 <= NCH) descend<(NCH + 1) / 2>(keys, kr, p, exact, gt);
+            else descend<(NCH > 0 ? NCH : 1)>(keys, kr, p, exact, gt);
+        } else {
+            for (int b = 31; b >= 0; --b) {
+                const uint32_t cand = p | (1u << b);
+                int cnt = 0;
+                for (int c = 0; c < nch; ++c) cnt += __popcll(__ballot(key_at(c) >= cand));
+                if (cnt >= kr) {
+                    p = cand;
+                    if (cnt == kr) { exact = true; break; }
+                }
             }
-            if (cnt >= kr) {
-                p = cand;
-                if (cnt == kr) { exact = true; break; }
-            }
+            if (!exact)
+                for (int c = 0; c < nch; ++c) gt += __popcll(__ballot(key_at(c) > p));
         }
         if (exact) {
             thr_gt = p - 1;            // exactly kr keys are >= p
             need = 0;
         } else {
             // p is the kr-th largest value; more than kr keys are >= p, so some equal ones are dropped
-            int gt = 0;
-            if (NCH > 0) {
-#pragma unroll
-                for (int c = 0; c < NCH; ++c)
-                    if (c < nch) gt += __popcll(__ballot(live(c * 64 + lane) && keys[c] > p));
-            } else {
-                for (int c = 0; c < nch; ++c) gt += __popcll(__ballot(live(c * 64 + lane) && key_at(c) > p));
-            }
             thr_gt = p;
             thr_eq = p;
             need = kr - gt;
