@@ -19,6 +19,7 @@ constexpr int TILE_ELEMS = kBlock * D;            // one K or V block in LDS: 64
 constexpr int STAGE_ELEMS = 2 * TILE_ELEMS;       // K then V: 32 KB per stage
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr int WAIT_VMCNT0 = 0x0F70;               // s_waitcnt vmcnt(0), other counters untouched
+constexpr int WAIT_LGKMCNT0 = 0xC07F;             // s_waitcnt lgkmcnt(0), other counters untouched
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -59,53 +60,68 @@ __device__ inline LaneOffs lane_offsets(int lane) {
     return o;
 }
 
-// ---- S^T = K_blk Q_t^T with the K block in a swizzled LDS tile: acc[kt][r] = key 16*kt + 4*(lane/16) + r
+// ---- S^T = K_blk Q_t^T with the K block in a swizzled LDS tile: acc[kt][r] = key 16*kt + 4*(lane/16) + r.
+// The 16 operand reads go through a rolling window of 8 registers sets, and consecutive MFMAs write
+// different accumulators, so LDS latency and MFMA latency overlap instead of adding up.
 __device__ inline void qk_from_lds(f32x4 (&acc)[4], const bf16x8 (&qf)[4], const uint16_t *ktile, const LaneOffs &lo) {
+    bf16x8 f[8];
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt) {
-        acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < 8; ++i)      // i -> (s = i / 4, kt = i % 4)
+        f[i] = *reinterpret_cast<const bf16x8 *>(ktile + (i & 3) * 16 * D + lo.kx[i >> 2]);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(ktile + kt * 16 * D + lo.kx[s]);
-            acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[s], acc[kt], 0, 0, 0);
-        }
+    for (int kt = 0; kt < 4; ++kt) acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int kt = i & 3, s = i >> 2;
+        acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[i & 7], qf[s], acc[kt], 0, 0, 0);
+        if (i + 8 < 16) f[i & 7] = *reinterpret_cast<const bf16x8 *>(ktile + kt * 16 * D + lo.kx[s + 2]);
     }
 }
+
+// max over the four 16-lane rows of a wave (lanes with equal lane % 16), without going through LDS
+__device__ inline float rows_max(float x) {
+    const unsigned u = __float_as_uint(x);
+    const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const float m1 = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const unsigned v = __float_as_uint(m1);
+    const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
+// The running reference st.m of the online softmax need not be the exact row maximum: any value shared by the
+// lanes of a head works as long as 2^(c (z - m)) stays far from overflow.  It is therefore only refreshed
+// (cross-lane max, rescale of O and l) when some logit exceeds it by more than this many powers of two.
+constexpr float kMaxSlack = 8.0f;
 
 // ---- online softmax over the 64 logits of a block and O^T += V_blk^T P^T (V block in a swizzled LDS tile)
 __device__ inline void softmax_pv(TokState &st, f32x4 (&acc)[4], const uint16_t *vt, const LaneOffs &lo, int lane,
                                   bool diag, int key_limit, float c) {
     const int g = lane >> 4;
-    // acc[kt][r] is key 16*kt + 4*g + r of the block, for head lane%16
-    if (diag) {
+    if (__builtin_amdgcn_readfirstlane(diag)) {       // only the query's own block needs the causal mask
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 if (16 * kt + 4 * g + r > key_limit) acc[kt][r] = -INFINITY;
     }
-    float mx = acc[0][0];
+    float mx = fmaxf(fmaxf(acc[0][0], acc[0][1]), fmaxf(acc[0][2], acc[0][3]));
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) mx = fmaxf(mx, acc[kt][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    if (__any(mx > st.m)) {          // some head's running max moved: rescale (rare after the first blocks)
-        const float m_new = fmaxf(st.m, mx);
+    for (int kt = 1; kt < 4; ++kt) mx = fmaxf(mx, fmaxf(fmaxf(acc[kt][0], acc[kt][1]), fmaxf(acc[kt][2], acc[kt][3])));
+    if (__any(mx * c > st.m * c + kMaxSlack)) {
+        const float m_new = fmaxf(st.m, rows_max(mx));
         const float alpha = fast_exp2((st.m - m_new) * c);
         st.m = m_new;
         st.l *= alpha;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) st.o[dt] *= alpha;
     }
-    const float mc = st.m * c;
+    const float nmc = -st.m * c;
     float ls = 0.f;
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            acc[kt][r] = fast_exp2(acc[kt][r] * c - mc);
+            acc[kt][r] = fast_exp2(__builtin_fmaf(acc[kt][r], c, nmc));
             ls += acc[kt][r];
         }
     st.l += ls;
@@ -118,17 +134,25 @@ __device__ inline void softmax_pv(TokState &st, f32x4 (&acc)[4], const uint16_t 
             pb[s2][r] = (__bf16)acc[2 * s2][r];
             pb[s2][4 + r] = (__bf16)acc[2 * s2 + 1][r];
         }
+    // 16 MFMAs, i -> (s2 = i / 8, dt = i % 8): consecutive ones write different accumulators; the V^T
+    // operands (two transposing reads each) go through a rolling window of 8
+    typedef __attribute__((address_space(3))) short4v lds_s4;
+    short4v v0[8], v1[8];
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt)
+    for (int i = 0; i < 8; ++i) {
+        v0[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)(vt + lo.vx[i]));
+        v1[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)(vt + 16 * D + lo.vx[i]));
+    }
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            const short4v v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) short4v *)(vt + (32 * s2) * D + lo.vx[dt]));
-            const short4v v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) short4v *)(vt + (32 * s2 + 16) * D + lo.vx[dt]));
-            const short8v v8 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-            st.o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v8), pb[s2], st.o[dt], 0, 0, 0);
+    for (int i = 0; i < 16; ++i) {
+        const int dt = i & 7, s2 = i >> 3;
+        const short8v v8 = __builtin_shufflevector(v0[dt], v1[dt], 0, 1, 2, 3, 4, 5, 6, 7);
+        st.o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v8), pb[s2], st.o[dt], 0, 0, 0);
+        if (i < 8) {
+            v0[dt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)(vt + 32 * D + lo.vx[dt]));
+            v1[dt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)(vt + 48 * D + lo.vx[dt]));
         }
+    }
 }
 
 // ---- one (token, block) unit with both blocks in one LDS stage (K tile, then V tile)
