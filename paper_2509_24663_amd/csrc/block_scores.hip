@@ -109,23 +109,30 @@ static int launch_generic(const Launch &L, const void *q, const float *kc, float
 // registers as MFMA A operands (M = the 16 heads of the group).  Compressed keys stream through LDS in
 // tiles of 64 and each B fragment read from LDS is reused by all TPW tokens of the wave.  A lane then owns
 // one key column and four heads, so
-//   pass 1 keeps a private running (max, sum exp) per head with no cross-lane traffic in the loop, and
+//   pass 1 keeps a private running (reference, sum 2^(y - reference)) per head with no cross-lane traffic
+//          in the loop; the reference is only moved when a logit exceeds it by 2^16, and
 //   pass 2 sums its four heads in registers and finishes the head-group sum with a 3-step butterfly
 //          across the four lane groups, after which the 64 lanes hold 64 consecutive keys' group sums.
-// K^{C1} is float32 in HBM.  It is split on the way into LDS into a bf16 high part and a bf16 residual.
-// Pass 1 (the normaliser, an average over many keys) uses the high part only; pass 2 adds the residual
-// product so the stored scores carry ~16 mantissa bits of K^{C1} and selections do not flip on rounding.
+//
+// Precision.  The ranking of blocks is sensitive to ~1e-3 relative changes of the scores, so the operands
+// are not rounded to bf16.  Q (bf16) converts to fp16 exactly and K^{C1} (float32 means of 32 keys) is
+// rounded to fp16, whose 11-bit significand keeps the logit error near 1e-4 -- one fp16 MFMA instead of a
+// bf16 high/low pair.  fp16's narrow exponent range is handled by exact power-of-two scalings: the Q rows of
+// a token are scaled so that their largest magnitude is below 2^15, and a key tile that holds a magnitude
+// above 2^15 (never the case for real activations) is re-staged with its own scale; both exponents are
+// folded back into the factor that multiplies the accumulator.  Both passes see the same logits.
 // ------------------------------------------------------------------------------------------
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 namespace {
 
 constexpr int SD = 128, SG = 16;
-constexpr int SKS = SD + 8;                    // LDS row stride (bf16) of a compressed-key tile
-constexpr int S_TILE = kBlock * SKS;           // one 64-key tile (hi or lo)
-constexpr int S_STAGE = 2 * S_TILE;            // hi + lo
+constexpr int SKS = SD + 8;                    // LDS row stride (fp16) of a compressed-key tile
+constexpr int S_TILE = kBlock * SKS;           // one 64-key tile
 constexpr float S_LOG2E = 1.4426950408889634f;
+constexpr float S_SLACK = 16.0f;               // pass 1 moves its reference when a logit exceeds it by 2^16
+constexpr float S_FP16_SAFE = 32768.0f;
 
 struct ScoreArgs {
     const uint16_t *q;
@@ -137,7 +144,16 @@ struct ScoreArgs {
     int64_t row_stride;
 };
 
-template <int NW, int TPW, bool P1_LO>
+__device__ inline float s_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// exponent e >= 0 such that amax * 2^-e < 2^15
+__device__ inline int fp16_shift(float amax) {
+    int ex;
+    (void)frexpf(amax, &ex);                   // amax = f * 2^ex, 0.5 <= f < 1
+    return amax > 0.f && ex > 15 ? ex - 15 : 0;
+}
+
+template <int NW, int TPW>
 struct ScoreKernel {
     static constexpr int T = NW * TPW;
     static constexpr int NTHR = NW * 64;
@@ -152,58 +168,72 @@ struct ScoreKernel {
                              : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     }
-    __device__ static inline void store_tile(uint16_t *stage, int tid, const float4 (&pf)[NCH]) {
+    // fp32 -> fp16 (x * 2^-shift) into the tile; returns true if some |x| * 2^-shift is not fp16-safe
+    __device__ static inline bool store_tile(_Float16 *tile, int tid, const float4 (&pf)[NCH], int shift) {
+        float amax = 0.f;
+        const float sc = __builtin_ldexpf(1.0f, -shift);
 #pragma unroll
         for (int r = 0; r < NCH; ++r) {
             const int c = tid + r * NTHR;
             const int row = c >> 5, col = (c & 31) * 4;
-            const float x[4] = {pf[r].x, pf[r].y, pf[r].z, pf[r].w};
-            uint16_t hi[4], lo[4];
+            const float x[4] = {pf[r].x * sc, pf[r].y * sc, pf[r].z * sc, pf[r].w * sc};
+            amax = fmaxf(fmaxf(amax, fmaxf(fabsf(x[0]), fabsf(x[1]))), fmaxf(fabsf(x[2]), fabsf(x[3])));
+            typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+            half4 hv = {(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3]};
+            *reinterpret_cast<half4 *>(tile + row * SKS + col) = hv;
+        }
+        return !(amax < S_FP16_SAFE);              // also true for NaN / Inf
+    }
+
+    // Stage the prefetched tile; returns the power-of-two exponent the tile was scaled down by (normally 0).
+    // Contains workgroup barriers: every thread calls it.
+    __device__ static inline void stage_tile(_Float16 *tile, int tid, const float4 (&pf)[NCH], int *s_flag,
+                                             int *s_shift) {
+        const bool bad = store_tile(tile, tid, pf, 0);
+        if (bad) *s_flag = 1;
+        if (tid == 0 && *s_shift != 0) *s_shift = 0;     // the stage's previous occupant may have been scaled
+        __syncthreads();
+        if (*s_flag) {                             // rare: re-stage with the tile's own scale
+            float amax = 0.f;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                hi[e] = float_to_bf16(x[e]);
-                lo[e] = float_to_bf16(x[e] - bf16_to_float(hi[e]));
-            }
-            uint2 h2, l2;
-            h2.x = hi[0] | ((uint32_t)hi[1] << 16);
-            h2.y = hi[2] | ((uint32_t)hi[3] << 16);
-            l2.x = lo[0] | ((uint32_t)lo[1] << 16);
-            l2.y = lo[2] | ((uint32_t)lo[3] << 16);
-            *reinterpret_cast<uint2 *>(stage + row * SKS + col) = h2;
-            *reinterpret_cast<uint2 *>(stage + S_TILE + row * SKS + col) = l2;
+            for (int r = 0; r < NCH; ++r)
+                amax = fmaxf(fmaxf(amax, fmaxf(fabsf(pf[r].x), fabsf(pf[r].y))), fmaxf(fabsf(pf[r].z), fabsf(pf[r].w)));
+            if (!(amax < 3.0e38f)) amax = 3.0e38f;  // Inf / NaN inputs: keep going, results are Inf / NaN anyway
+            atomicMax(reinterpret_cast<unsigned *>(s_shift), __float_as_uint(amax));
+            __syncthreads();
+            const int shift = fp16_shift(__uint_as_float(*reinterpret_cast<unsigned *>(s_shift)));
+            __syncthreads();
+            (void)store_tile(tile, tid, pf, shift);
+            if (tid == 0) { *s_flag = 0; *s_shift = shift; }
+            __syncthreads();
         }
     }
 
-    // acc[i][nt] = Q_i (16 heads x 128) . kc_tile^T (128 x 16 keys of n-tile nt); B fragments shared by the tokens
-    template <bool WITH_LO>
-    __device__ static inline void tile_mma(const bf16x8 (&qf)[TPW][4], const uint16_t *stage, int lane,
-                                           const bool (&active)[TPW], f32x4 (&acc)[TPW][4]) {
+    // acc[i][nt] = Q_i (16 heads x 128) . kc_tile^T (128 x 16 keys of n-tile nt); each B fragment read from
+    // LDS feeds the TPW tokens of the wave, through a rolling window of 4 fragments
+    __device__ static inline void tile_mma(const half8 (&qf)[TPW][4], const _Float16 *tile, int lane,
+                                           f32x4 (&acc)[TPW][4]) {
         const int n16 = lane & 15, g = lane >> 4;
-        const uint16_t *bp = stage + n16 * SKS + g * 8;
+        const _Float16 *bp = tile + n16 * SKS + g * 8;
+        half8 b[4];
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
+        for (int u = 0; u < 4; ++u)            // u -> (nt = u / 4, ks = u % 4)
+            b[u] = *reinterpret_cast<const half8 *>(bp + (u >> 2) * 16 * SKS + (u & 3) * 32);
 #pragma unroll
-            for (int i = 0; i < TPW; ++i) acc[i][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int u = 0; u < 16; ++u) {
+            const int nt = u >> 2, ks = u & 3;
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const bf16x8 bh = *reinterpret_cast<const bf16x8 *>(bp + nt * 16 * SKS + ks * 32);
-                bf16x8 bl;
-                if (WITH_LO) bl = *reinterpret_cast<const bf16x8 *>(bp + S_TILE + nt * 16 * SKS + ks * 32);
-#pragma unroll
-                for (int i = 0; i < TPW; ++i) {
-                    if (active[i]) {
-                        acc[i][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[i][ks], bh, acc[i][nt], 0, 0, 0);
-                        if (WITH_LO)
-                            acc[i][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[i][ks], bl, acc[i][nt], 0, 0, 0);
-                    }
-                }
+            for (int i = 0; i < TPW; ++i) {
+                if (ks == 0) acc[i][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                acc[i][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qf[i][ks], b[u & 3], acc[i][nt], 0, 0, 0);
             }
+            if (u + 4 < 16) b[u & 3] = *reinterpret_cast<const half8 *>(bp + ((u + 4) >> 2) * 16 * SKS + ((u + 4) & 3) * 32);
         }
     }
 
     __device__ static void run(const ScoreArgs &a, int num_tiles) {
-        extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-        __shared__ int s_seq, s_tile;
+        extern __shared__ __attribute__((aligned(16))) _Float16 smem[];     // two tiles (double buffer)
+        __shared__ int s_seq, s_tile, s_flag, s_shift[2];
         const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
         const int h = blockIdx.y;
         const int tile_id = num_tiles - 1 - (int)blockIdx.x;     // longest rows first
@@ -216,6 +246,8 @@ struct ScoreKernel {
             }
             s_seq = s;
             s_tile = rem;
+            s_flag = 0;
+            s_shift[0] = s_shift[1] = 0;
         }
         __syncthreads();
         const int seq = s_seq;
@@ -230,71 +262,97 @@ struct ScoreKernel {
         const int nkt = (vis_last + kBlock - 1) / kBlock;
         const int row0 = tok0 + t0;
         const float *kcb = a.kc + ((int64_t)h * a.map.kc_total_c + a.map.cu_c[seq]) * SD;
-        const float c = a.scale * S_LOG2E;
         const int n16 = lane & 15, g = lane >> 4;
 
-        bf16x8 qf[TPW][4];
+        // ---- Q rows of this wave's tokens: bf16 -> fp16, each token scaled by a power of two into fp16 range
+        half8 qf[TPW][4];
         int vis[TPW];
+        float cq[TPW];                   // scale * log2(e) * 2^(token's exponent): multiplies the accumulator
+        int vis_min = 1 << 30;
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             const int ti = w * TPW + i;
             vis[i] = ti < ntok ? min(visible_cmp(t0 + ti, a.lc, a.sc), nc) : 0;
+            vis_min = min(vis_min, vis[i]);
             const uint16_t *qp = a.q + ((int64_t)(row0 + ti) * a.hq + h * SG + n16) * SD + g * 8;
+            float x[4][8];
+            float amax = 0.f;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                uint4 raw = ti < ntok ? *reinterpret_cast<const uint4 *>(qp + ks * 32) : make_uint4(0, 0, 0, 0);
-                qf[i][ks] = __builtin_bit_cast(bf16x8, raw);
+                const uint4 raw = ti < ntok ? *reinterpret_cast<const uint4 *>(qp + ks * 32) : make_uint4(0, 0, 0, 0);
+                const uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    x[ks][2 * e] = __uint_as_float(u[e] << 16);
+                    x[ks][2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
+                    amax = fmaxf(amax, fmaxf(fabsf(x[ks][2 * e]), fabsf(x[ks][2 * e + 1])));
+                }
             }
+            amax = wave_max(amax);
+            if (!(amax < 3.0e38f)) amax = 3.0e38f;
+            const int shift = fp16_shift(amax);
+            const float sc = __builtin_ldexpf(1.0f, -shift);
+            cq[i] = a.scale * S_LOG2E * __builtin_ldexpf(1.0f, shift);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qf[i][ks][e] = (_Float16)(x[ks][e] * sc);
         }
 
         float4 pf[NCH];
         f32x4 acc[TPW][4];
-        bool active[TPW];
-        float m[TPW][4], l[TPW][4];
+        float m[TPW][4], l[TPW][4];      // per lane: reference (log2 domain) and sum of 2^(y - reference)
 #pragma unroll
         for (int i = 0; i < TPW; ++i)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) { m[i][r] = -INFINITY; l[i][r] = 0.f; }
+            for (int r = 0; r < 4; ++r) { m[i][r] = -1.0e30f; l[i][r] = 0.f; }
 
         // ------------------------------------------------ pass 1: log-sum-exp of every (token, head) row
         load_tile(kcb, 0, nc, tid, pf);
-        store_tile(smem, tid, pf);
-        __syncthreads();
+        stage_tile(smem, tid, pf, &s_flag, &s_shift[0]);
         for (int kt = 0; kt < nkt; ++kt) {
             if (kt + 1 < nkt) load_tile(kcb, kt + 1, nc, tid, pf);
-            const uint16_t *stage = smem + (kt & 1) * S_STAGE;
+            const _Float16 *tile = smem + (kt & 1) * S_TILE;
             const int kbase = kt * kBlock;
-#pragma unroll
-            for (int i = 0; i < TPW; ++i) active[i] = kbase < vis[i];
-            if (P1_LO) tile_mma<true>(qf, stage, lane, active, acc);
-            else tile_mma<false>(qf, stage, lane, active, acc);
+            const float tsc = __builtin_ldexpf(1.0f, s_shift[kt & 1]);
+            tile_mma(qf, tile, lane, acc);
+            const bool edge_tile = kbase + kBlock > vis_min;
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
-                if (!active[i]) continue;
-                const bool edge = kbase + kBlock > vis[i];
+                const float cs = cq[i] * tsc;
+                if (edge_tile) {
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt)
+                        if (kbase + nt * 16 + n16 >= vis[i]) acc[i][nt] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+                }
+                bool grow = false;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    float z[4];
+                    const float mx = fmaxf(fmaxf(acc[i][0][r], acc[i][1][r]), fmaxf(acc[i][2][r], acc[i][3][r]));
+                    grow |= mx * cs > m[i][r] + S_SLACK;
+                }
+                if (__any(grow)) {
 #pragma unroll
-                    for (int nt = 0; nt < 4; ++nt) {
-                        z[nt] = acc[i][nt][r];
-                        if (edge && kbase + nt * 16 + n16 >= vis[i]) z[nt] = -INFINITY;
+                    for (int r = 0; r < 4; ++r) {
+                        const float mx = fmaxf(fmaxf(acc[i][0][r], acc[i][1][r]), fmaxf(acc[i][2][r], acc[i][3][r])) * cs;
+                        const float mn = fmaxf(m[i][r], mx);            // finite: m starts at -1e30
+                        l[i][r] *= s_exp2(m[i][r] - mn);
+                        m[i][r] = mn;
                     }
-                    const float mx = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
-                    const float mn = fmaxf(m[i][r], mx);
-                    const float ms = mn == -INFINITY ? 0.f : mn;
-                    const float msc = ms * c;
-                    float sum = l[i][r] * __builtin_amdgcn_exp2f((m[i][r] - ms) * c);
+                }
 #pragma unroll
-                    for (int nt = 0; nt < 4; ++nt) sum += __builtin_amdgcn_exp2f(z[nt] * c - msc);
+                for (int r = 0; r < 4; ++r) {
+                    const float nm = -m[i][r];
+                    float sum = l[i][r];
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) sum += s_exp2(__builtin_fmaf(acc[i][nt][r], cs, nm));
                     l[i][r] = sum;
-                    m[i][r] = mn;
                 }
             }
-            if (kt + 1 < nkt) store_tile(smem + ((kt + 1) & 1) * S_STAGE, tid, pf);
-            __syncthreads();
+            if (kt + 1 < nkt) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf, &s_flag, &s_shift[(kt + 1) & 1]);
+            else __syncthreads();
         }
-        // merge the 16 key lanes of each lane group; lse2 = log2 of the row's sum of 2^(c z)
+        // merge the 16 key lanes of each lane group; lse2 = log2 of the row's sum of 2^y
         float lse2[TPW][4];
 #pragma unroll
         for (int i = 0; i < TPW; ++i)
@@ -305,33 +363,30 @@ struct ScoreKernel {
                 for (int o = 1; o < 16; o <<= 1) {
                     const float mo = __shfl_xor(mm, o), lo = __shfl_xor(ll, o);
                     const float mn = fmaxf(mm, mo);
-                    const float ms = mn == -INFINITY ? 0.f : mn;
-                    ll = ll * __builtin_amdgcn_exp2f((mm - ms) * c) + lo * __builtin_amdgcn_exp2f((mo - ms) * c);
+                    ll = ll * s_exp2(mm - mn) + lo * s_exp2(mo - mn);
                     mm = mn;
                 }
-                lse2[i][r] = mm * c + __log2f(ll);
+                lse2[i][r] = mm + __log2f(ll);
             }
 
         // ------------------------------------------------ pass 2: normalised scores, group sum, store
         load_tile(kcb, 0, nc, tid, pf);
-        store_tile(smem, tid, pf);
-        __syncthreads();
+        stage_tile(smem, tid, pf, &s_flag, &s_shift[0]);
         for (int kt = 0; kt < nkt; ++kt) {
             if (kt + 1 < nkt) load_tile(kcb, kt + 1, nc, tid, pf);
-            const uint16_t *stage = smem + (kt & 1) * S_STAGE;
+            const _Float16 *tile = smem + (kt & 1) * S_TILE;
             const int kbase = kt * kBlock;
-#pragma unroll
-            for (int i = 0; i < TPW; ++i) active[i] = kbase < vis[i];
-            tile_mma<true>(qf, stage, lane, active, acc);
+            const float tsc = __builtin_ldexpf(1.0f, s_shift[kt & 1]);
+            tile_mma(qf, tile, lane, acc);
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
-                if (!active[i]) continue;
+                const float cs = cq[i] * tsc;
                 float s[4];
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt) {
                     float t = 0.f;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) t += __builtin_amdgcn_exp2f(acc[i][nt][r] * c - lse2[i][r]);
+                    for (int r = 0; r < 4; ++r) t += s_exp2(__builtin_fmaf(acc[i][nt][r], cs, -lse2[i][r]));
                     s[nt] = t;
                 }
                 // butterfly over the four lane groups: afterwards lane (n16, g) holds n-tile 2*(g&1) + (g>>1)
@@ -343,30 +398,26 @@ struct ScoreKernel {
                 if (key < vis[i])
                     a.out[((int64_t)h * a.map.total_rows + row0 + w * TPW + i) * a.row_stride + key] = f;
             }
-            if (kt + 1 < nkt) store_tile(smem + ((kt + 1) & 1) * S_STAGE, tid, pf);
-            __syncthreads();
+            if (kt + 1 < nkt) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf, &s_flag, &s_shift[(kt + 1) & 1]);
+            else __syncthreads();
         }
     }
 };
 
-template <int NW, int TPW, bool P1_LO>
+template <int NW, int TPW>
 __global__ void __launch_bounds__(NW * 64) block_scores_mfma_kernel(ScoreArgs a, int num_tiles) {
-    ScoreKernel<NW, TPW, P1_LO>::run(a, num_tiles);
+    ScoreKernel<NW, TPW>::run(a, num_tiles);
 }
 
-template <int NW, int TPW, bool P1_LO>
+template <int NW, int TPW>
 int launch_scores_mfma(const Launch &L, const ScoreArgs &a, const int32_t *cu_h) {
     constexpr int T = NW * TPW;
     int64_t tiles = 0;
     for (int s = 0; s < L.map.batch; ++s) tiles += (cu_h[s + 1] - cu_h[s] + T - 1) / T;
     if (tiles == 0) return INFLLMV2_OK;
-    const size_t lds = (size_t)2 * S_STAGE * sizeof(uint16_t);
-    auto kern = block_scores_mfma_kernel<NW, TPW, P1_LO>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return INFLLMV2_ERR_HIP;
+    const size_t lds = (size_t)2 * S_TILE * sizeof(_Float16);
     dim3 grid((unsigned)tiles, L.p->num_kv_heads);
-    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, L.stream, a, (int)tiles);
+    hipLaunchKernelGGL((block_scores_mfma_kernel<NW, TPW>), grid, dim3(NW * 64), lds, L.stream, a, (int)tiles);
     return hip_status(hipGetLastError());
 }
 
@@ -379,8 +430,7 @@ int launch_block_scores(const Launch &L, const void *q, const float *kc, float *
         L.p->num_q_heads / L.p->num_kv_heads == SG && (((uintptr_t)q | (uintptr_t)kc) & 15) == 0) {
         ScoreArgs a{(const uint16_t *)q, kc, s_shared, L.map, L.p->num_q_heads, L.p->cmp_len, L.p->cmp_stride,
                     L.p->dense_threshold, L.p->softmax_scale, row_stride};
-        static const bool p1_hi_only = getenv("INFLLMV2_SCORES_P1_HI") != nullptr;   // experiment switch
-        return p1_hi_only ? launch_scores_mfma<8, 4, false>(L, a, cu_h) : launch_scores_mfma<8, 4, true>(L, a, cu_h);
+        return launch_scores_mfma<8, 4>(L, a, cu_h);
     }
     if (L.p->head_dim == 128)
         return bf ? launch_generic<bf16_t, 128>(L, q, kc, s_shared, row_stride)

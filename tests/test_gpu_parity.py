@@ -63,13 +63,16 @@ def _run_prefill_case(m, oracle, w, gp, op, dtype, rows=None, check_stages=True)
                 nc = kc_o.shape[0]
                 assert cu_c[s + 1] - cu_c[s] == nc
                 if check_stages:
-                    np.testing.assert_allclose(kc_g[h, cu_c[s]:cu_c[s] + nc], kc_o, rtol=0, atol=2e-6)
+                    np.testing.assert_allclose(kc_g[h, cu_c[s]:cu_c[s] + nc], kc_o, rtol=0,
+                                               atol=2e-6 * max(1.0, float(np.abs(kc_o).max()) if nc else 1.0))
                 sh_o = oracle.block_scores(Qh, pos, kc_o, op)
                 idx_o, cmp_o = oracle.topk_blocks(sh_o, pos, op, return_cmp=True)
                 if check_stages:
                     for r, t in enumerate(pos):
                         vis = oracle.visible_cmp(int(t), op)
-                        np.testing.assert_allclose(sh_g[h, sel[r], :vis], sh_o[r, :vis], rtol=2e-4, atol=1e-7)
+                        # stage 2 rounds K^{C1} to an 11-bit significand (fp16 MFMA operands): per-logit error
+                        # ~1e-4, so scores agree to a few 1e-4 relative -- well inside the 1e-3 tie window
+                        np.testing.assert_allclose(sh_g[h, sel[r], :vis], sh_o[r, :vis], rtol=5e-4, atol=1e-7)
                     # stage 3 alone: oracle top-k of the GPU's scores must equal the GPU's list bit for bit
                     shg_rows = np.zeros_like(sh_o)
                     for r, t in enumerate(pos):
@@ -124,6 +127,19 @@ def test_paper_head_shape_bf16(m, oracle, n):
     """h_q 32 / h_kv 2 / d 128 (the paper's model shape): the MFMA kernels' home."""
     w = synth.make_prefill(n, 32, 2, 128, seed=300 + n, dtype="bf16")
     gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=8, topk_total=16)
+    _run_prefill_case(m, oracle, w, gp, op, "bf16")
+
+
+@pytest.mark.parametrize("qexp,kexp", [(14, -7), (-3, 17), (0, 0)])
+def test_scores_survive_large_magnitudes(m, oracle, qexp, kexp):
+    """Stage 2 works on fp16 operands internally; power-of-two input scalings that leave every logit unchanged
+    (compensated in softmax_scale) must leave the selection unchanged, including magnitudes beyond 65504."""
+    n = 3000
+    w = synth.make_prefill(n, 32, 2, 128, seed=404, dtype="bf16")
+    w["q"] = (w["q"] * np.float32(2.0 ** qexp)).astype(np.float32)       # exact in bf16: power-of-two scaling
+    w["k"] = (w["k"] * np.float32(2.0 ** kexp)).astype(np.float32)
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=4, topk_total=12,
+                     softmax_scale=128 ** -0.5 * 2.0 ** (-qexp - kexp))
     _run_prefill_case(m, oracle, w, gp, op, "bf16")
 
 
