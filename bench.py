@@ -38,7 +38,7 @@ def main() -> int:
     ap.add_argument("--dense-steps", type=int, default=1, help="timed runs of the dense path at the same shape (0 = skip)")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--cpu-rows", type=int, default=512, help="query rows per KV head the oracle is timed on")
+    ap.add_argument("--cpu-rows", type=int, default=6144, help="query rows per KV head the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)

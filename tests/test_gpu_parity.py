@@ -31,7 +31,7 @@ def _params(m, oracle, dtype, hq, hkv, d, **kw):
 
 
 def _run_prefill_case(m, oracle, w, gp, op, dtype, rows=None, check_stages=True):
-    """Full sparse path on one packed workload; returns stats."""
+    """Full sparse path on one packed workload, checked on `rows` (packed token indices, default all)."""
     cu = w["cu_seqlens"]
     T, hq, d = w["q"].shape
     hkv = w["k"].shape[0]
@@ -39,17 +39,23 @@ def _run_prefill_case(m, oracle, w, gp, op, dtype, rows=None, check_stages=True)
     q, k, v = (to_dev(w[x], dtype) for x in ("q", "k", "v"))
     res = m.sparse_prefill(gp, q, k, v, cu)
     torch.cuda.synchronize()
-    out_g, lse_g, idx_g = to_np(res["out"]), to_np(res["lse"]), to_np(res["block_idx"])
-    sh_g, kc_g = to_np(res["s_shared"]), to_np(res["kc"])
-    rows = np.arange(T) if rows is None else np.asarray(rows)
-    stats = dict(rows_diff=0, blocks_diff=0)
+    rows = np.arange(T) if rows is None else np.unique(np.asarray(rows))
+    rows_d = torch.from_numpy(rows).cuda()
+    # only the sampled rows leave the GPU (S^shared alone is 8.6 GB at 128K)
+    out_g = to_np(res["out"][rows_d])                       # [R, hq, d]
+    lse_g = to_np(res["lse"][:, rows_d])                    # [hq, R]
+    idx_g = to_np(res["block_idx"][:, rows_d])              # [hkv, R, K]
+    sh_g = to_np(res["s_shared"][:, rows_d])                # [hkv, R, rs]
+    kc_g = to_np(res["kc"])
+    stats = dict(rows_diff=0, blocks_diff=0, rows=len(rows), max_abs=0.0)
     cu_c = to_np(res["cu_seqlens_c"].int())
     for s in range(len(cu) - 1):
         a, b = int(cu[s]), int(cu[s + 1])
         n = b - a
-        sel = rows[(rows >= a) & (rows < b)]
-        if len(sel) == 0:
+        loc = np.nonzero((rows >= a) & (rows < b))[0]        # positions in the sampled arrays
+        if len(loc) == 0:
             continue
+        sel = rows[loc]
         pos = (sel - a).astype(np.int32)
         dense = n < op.dense_threshold
         for h in range(hkv):
@@ -57,7 +63,7 @@ def _run_prefill_case(m, oracle, w, gp, op, dtype, rows=None, check_stages=True)
             Kh, Vh = w["k"][h, a:b], w["v"][h, a:b]
             if dense:
                 O, L = oracle.dense_attn(Qh, pos, Kh, Vh, op)
-                assert np.all(idx_g[h, sel] == -1)
+                assert np.all(idx_g[h, loc] == -1)
             else:
                 kc_o = oracle.compress_k(Kh, op)
                 nc = kc_o.shape[0]
@@ -68,27 +74,26 @@ def _run_prefill_case(m, oracle, w, gp, op, dtype, rows=None, check_stages=True)
                 sh_o = oracle.block_scores(Qh, pos, kc_o, op)
                 idx_o, cmp_o = oracle.topk_blocks(sh_o, pos, op, return_cmp=True)
                 if check_stages:
+                    shg_rows = np.zeros_like(sh_o)
                     for r, t in enumerate(pos):
                         vis = oracle.visible_cmp(int(t), op)
                         # stage 2 rounds K^{C1} to an 11-bit significand (fp16 MFMA operands): per-logit error
                         # ~1e-4, so scores agree to a few 1e-4 relative -- well inside the 1e-3 tie window
-                        np.testing.assert_allclose(sh_g[h, sel[r], :vis], sh_o[r, :vis], rtol=5e-4, atol=1e-7)
+                        np.testing.assert_allclose(sh_g[h, loc[r], :vis], sh_o[r, :vis], rtol=5e-4, atol=1e-7)
+                        shg_rows[r, :vis] = sh_g[h, loc[r], :vis]
                     # stage 3 alone: oracle top-k of the GPU's scores must equal the GPU's list bit for bit
-                    shg_rows = np.zeros_like(sh_o)
-                    for r, t in enumerate(pos):
-                        vis = oracle.visible_cmp(int(t), op)
-                        shg_rows[r, :vis] = sh_g[h, sel[r], :vis]
-                    np.testing.assert_array_equal(idx_g[h, sel], oracle.topk_blocks(shg_rows, pos, op))
-                rd, bd = check_selection(idx_g[h, sel], idx_o, cmp_o, pos, op.n_init, op.n_local)
+                    np.testing.assert_array_equal(idx_g[h, loc], oracle.topk_blocks(shg_rows, pos, op))
+                rd, bd = check_selection(idx_g[h, loc], idx_o, cmp_o, pos, op.n_init, op.n_local)
                 stats["rows_diff"] += rd
                 stats["blocks_diff"] += bd
                 # attention error alone: oracle attention over the GPU's selection
-                O_iso, L_iso = oracle.sparse_attn(Qh, pos, Kh, Vh, idx_g[h, sel], op)
-                assert_out_close(out_g[sel, h * G:(h + 1) * G], O_iso, dtype, "out | GPU selection")
-                np.testing.assert_allclose(lse_g[h * G:(h + 1) * G, sel].T, L_iso, atol=2e-3 if dtype == "bf16" else 1e-4)
+                O_iso, L_iso = oracle.sparse_attn(Qh, pos, Kh, Vh, idx_g[h, loc], op)
+                mx, _ = assert_out_close(out_g[loc, h * G:(h + 1) * G], O_iso, dtype, "out | GPU selection")
+                stats["max_abs"] = max(stats["max_abs"], mx)
+                np.testing.assert_allclose(lse_g[h * G:(h + 1) * G, loc].T, L_iso, atol=2e-3 if dtype == "bf16" else 1e-4)
                 O, L = oracle.sparse_attn(Qh, pos, Kh, Vh, idx_o, op)
             if rd_ok(stats):
-                assert_out_close(out_g[sel, h * G:(h + 1) * G], O, dtype, "out end-to-end")
+                assert_out_close(out_g[loc, h * G:(h + 1) * G], O, dtype, "out end-to-end")
     return stats
 
 
