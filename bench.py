@@ -39,6 +39,8 @@ def main() -> int:
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=6144, help="query rows per KV head the oracle is timed on")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic, to scale PMC byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -64,6 +66,13 @@ def main() -> int:
     v = torch.from_numpy(w["v"]).to(torch.bfloat16).cuda()
     gen_s = time.time() - t0
     si = m.SeqInfo([0, n])
+
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------------ whole path, K timed steps
     bufs = m.sparse_prefill(gp, q, k, v, si)          # first call allocates every buffer once
