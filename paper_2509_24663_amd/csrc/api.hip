@@ -264,7 +264,10 @@ int launch_attn(const Launch &L, const void *q, const void *k, const void *v, co
                 int dense_below, void *out, float *lse, const int32_t *cu_h) {
     const bool aligned = (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) == 0 &&
                          L.map.kv_tok_stride % 8 == 0 && L.map.kv_head_stride % 8 == 0;
-    if (attn_mfma_supported(L.p) && aligned) return launch_attn_mfma(L, q, k, v, idx, dense_below, out, lse, cu_h);
+    if (attn_mfma_supported(L.p) && aligned) {
+        const int rc = launch_attn_mfma(L, q, k, v, idx, dense_below, out, lse, cu_h);
+        if (rc != INFLLMV2_ERR_UNSUPPORTED) return rc;      // strides or sizes outside the tile kernel's limits
+    }
     return launch_attn_generic(L, q, k, v, idx, dense_below, out, lse);
 }
 }  // namespace ifv2

@@ -22,6 +22,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <type_traits>
+
 #include "attn_unit.h"
 
 namespace ifv2 {
@@ -42,73 +44,32 @@ struct AttnArgs {
     int list_cap;      // entries reserved for the union list
 };
 
-#ifdef IFV2_RING_PROF
-__device__ unsigned long long g_prof[8];
-#define PROF_DECL() long long prof_acc[5] = {0, 0, 0, 0, 0}
-#define PROF_T0() const long long prof_t0 = __builtin_amdgcn_s_memtime()
-#define PROF_ADD(slot) prof_acc[slot] += __builtin_amdgcn_s_memtime() - prof_t0
-#define PROF_FLUSH() do { if (lane == 0) for (int i_ = 0; i_ < 5; ++i_) atomicAdd(&g_prof[i_], (unsigned long long)prof_acc[i_]); } while (0)
-#else
-#define PROF_DECL() do {} while (0)
-#define PROF_T0() do {} while (0)
-#define PROF_ADD(slot) do {} while (0)
-#define PROF_FLUSH() do {} while (0)
+#ifdef IFV2_DEBUG_MODES
+// debug build only: 1 = skip the units (loads and barriers only), 2 = skip the loads
+__device__ int g_dbg_mode;
+__device__ unsigned long long g_dbg_stats[4];
 #endif
 
-template <int NW, int TPW, int S>
+// NW waves, TPW tokens per wave, SLOTS union entries per barrier interval.
+template <int NW, int TPW, int SLOTS>
 struct TileKernel {
     static constexpr int T = NW * TPW;
     static constexpr int NTHR = NW * 64;
-    static constexpr bool RING = S > 2;       // S == 2: lock-step double buffering; S > 2: flag-driven ring
-    static_assert(!RING || TPW == 1, "the ring schedule counts one consumer per wave");
-    static_assert(32 % NW == 0 || NW == 32, "32 one-KB load instructions are dealt round-robin to the waves");
-
-    // ---- block j of the sequence: global -> LDS stage (K tile then V tile), asynchronously; the 32 one-KB
-    // pieces are dealt round-robin to the waves.
-    __device__ static inline void issue_block_load(const AttnArgs &a, const uint16_t *kb, const uint16_t *vb, int j,
-                                                   int len, uint16_t *stage, int w, int lane) {
-#pragma unroll
-        for (int qi = w; qi < 32; qi += NW)
-            load_piece(qi < 16 ? kb : vb, a.map.kv_tok_stride, j, len, stage + (qi < 16 ? 0 : TILE_ELEMS), qi & 15, lane);
-    }
-
-    // ---- the same load issued by a single wave (ring schedule: the wave on duty for this entry)
-    __device__ static inline void issue_block_load_wave(const AttnArgs &a, const uint16_t *kb, const uint16_t *vb, int j,
-                                                        int len, uint16_t *stage, int lane) {
-#pragma unroll 4
-        for (int qi = 0; qi < 32; ++qi)
-            load_piece(qi < 16 ? kb : vb, a.map.kv_tok_stride, j, len, stage + (qi < 16 ? 0 : TILE_ELEMS), qi & 15, lane);
-    }
-
-    // Per-entry state word of the ring schedule: bits 16.. count the load pieces that have landed (NW = all of
-    // them), bits 0..15 count the waves that have finished consuming the entry.  Both only grow.
-    __device__ static inline int st_ready(int v) { return v >> 16; }
-    __device__ static inline int st_done(int v) { return v & 0xffff; }
-
-    // Bounded waits on a state word.  They return false (and raise *err for the whole workgroup) if the bound
-    // is hit, so that a logic error can never hang the GPU: every wave then leaves its loop.
-    template <bool READY>
-    __device__ static inline bool wait_state(volatile int *word, int target, volatile int *err) {
-        int spins = 0;
-        while ((READY ? st_ready(*word) : st_done(*word)) < target) {
-            __builtin_amdgcn_s_sleep(1);
-            if (++spins > (1 << 22) || *err) {
-                *err = 1;
-                return false;
-            }
-        }
-        return true;
-    }
+    static constexpr int NSTAGE = 2 * SLOTS;        // double buffering of an interval's blocks
+    static constexpr int PPW = 32 / NW;             // one-KB load pieces per wave and block
+    static constexpr int NONE = -1;
+    static_assert(32 % NW == 0, "32 one-KB load instructions are dealt round-robin to the waves");
+    static_assert(TPW == 1 || TPW == 2, "a wave holds one token or two neighbours");
+    static_assert(SLOTS == 1 || (SLOTS == 2 && TPW == 1), "pairing is per wave, one token each");
 
     __device__ static void run(const AttnArgs &a, int num_tiles) {
         extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
         uint16_t *stages = smem;
-        uint32_t *masks = reinterpret_cast<uint32_t *>(smem + S * STAGE_ELEMS);
-        int32_t *list_j = reinterpret_cast<int32_t *>(masks + a.nb_cap);
-        int *state = reinterpret_cast<int *>(list_j + a.list_cap);      // ring schedule: one word per union entry
-        __shared__ int s_seq, s_tile, s_ne;
+        uint32_t *masks = reinterpret_cast<uint32_t *>(smem + NSTAGE * STAGE_ELEMS);
+        int2 *rec = reinterpret_cast<int2 *>(masks + a.nb_cap);          // union list: (block, token mask) per entry
+        __shared__ int s_seq, s_tile, s_ne, s_ni;
 
-        const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+        const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
         const int h = blockIdx.y;
         // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  Neighbouring tiles share most
         // of their K/V blocks, so runs of XG consecutive tiles are sent to the same XCD; late (long-context)
@@ -134,19 +95,21 @@ struct TileKernel {
             s_tile = rem;
         }
         __syncthreads();
-        const int seq = s_seq;
+        const int seq = __builtin_amdgcn_readfirstlane(s_seq);
         if (seq >= a.map.batch) return;
         const int tok0 = a.map.cu[seq], len = a.map.cu[seq + 1] - tok0;
-        const int t0 = s_tile * T;                       // first token of the tile (position in the sequence)
+        const int t0 = __builtin_amdgcn_readfirstlane(s_tile) * T;       // first token of the tile (position in the sequence)
         const int ntok = min(T, len - t0);
         const int bt = t0 / kBlock, nblk = bt + 1;       // T divides 64: the tile lies in one block
         const bool dense = a.idx == nullptr || len < a.dense_below;
         const int row0 = tok0 + t0;                      // packed row of the tile's first token
         const uint16_t *kb = a.k + (int64_t)tok0 * a.map.kv_tok_stride + (int64_t)h * a.map.kv_head_stride;
         const uint16_t *vb = a.v + (int64_t)tok0 * a.map.kv_tok_stride + (int64_t)h * a.map.kv_head_stride;
+        const uint32_t full = ntok >= 32 ? 0xffffffffu : ((1u << ntok) - 1u);
 
-        // ---- union of the tile's block lists: masks[j] has bit ti set if token ti selected block j
-        int ne;
+        // ---- union of the tile's block lists: masks[j] has bit ti set if token ti selected block j.  The tile's
+        // own block is the largest one any of its tokens selects, and every token selects it: it is the last entry.
+        int ni;                                          // number of barrier intervals
         if (!dense) {
             for (int j = tid; j < nblk; j += NTHR) masks[j] = 0u;
             __syncthreads();
@@ -163,153 +126,138 @@ struct TileKernel {
                     const int j = cbase + lane;
                     const uint32_t mk = j < nblk ? masks[j] : 0u;
                     const uint64_t b = __ballot(mk != 0u);
-                    if (mk != 0u) list_j[base + __popcll(b & ((1ull << lane) - 1ull))] = j;
+                    if (mk != 0u) rec[base + __popcll(b & ((1ull << lane) - 1ull))] = make_int2(j, (int)mk);
                     base += __popcll(b);
                 }
-                if (lane == 0) s_ne = base;
+                if (lane == 0) { s_ne = base; s_ni = SLOTS == 2 && base > 0 ? base / 2 + 1 : base; }
             }
             __syncthreads();
-            ne = s_ne;
+            ni = __builtin_amdgcn_readfirstlane(s_ni);
+#ifdef IFV2_DEBUG_MODES
+            if (tid == 0) { atomicAdd(&g_dbg_stats[0], (unsigned long long)s_ne); atomicAdd(&g_dbg_stats[1], (unsigned long long)ni); atomicAdd(&g_dbg_stats[2], 1ull); }
+#endif
         } else {
-            ne = nblk;
+            ni = nblk;
         }
-        constexpr int PRE = RING ? S - 1 : 1;          // entries loaded cooperatively before the main loop
-        for (int e = 0; e < PRE && e < ne; ++e)
-            issue_block_load(a, kb, vb, dense ? e : list_j[e], len, stages + e * STAGE_ELEMS, w, lane);
+        // Interval i -> its blocks and consumer masks (unused slot: block NONE, mask 0).  With SLOTS == 2 an
+        // interval covers two consecutive entries of the union, so that a SIMD usually has two or more units to
+        // overlap between one pair of barriers; the tile's own block (the last entry) is alone in the last interval.
+        const int ne = dense ? nblk : __builtin_amdgcn_readfirstlane(s_ne);
+        auto interval = [&](int i) -> int4 {
+            if (dense) return make_int4(i, (int)full, NONE, 0);
+            if (SLOTS == 1) {
+                const int2 r = rec[i];
+                return make_int4(r.x, r.y, NONE, 0);
+            }
+            if (i == ni - 1) {
+                const int2 r = rec[ne - 1];
+                return make_int4(r.x, r.y, NONE, 0);
+            }
+            const int2 r0 = rec[2 * i];
+            const int2 r1 = 2 * i + 1 < ne - 1 ? rec[2 * i + 1] : make_int2(NONE, 0);
+            return make_int4(r0.x, r0.y, r1.x, r1.y);
+        };
 
-        // ---- this wave's tokens: ti = i * NW + w (interleaved so the waves' loads stay similar)
-        TokState st[TPW];
+        // ---- loads: the 32 one-KB pieces of a block (16 of K, 16 of V) are dealt round-robin to the waves.  A
+        // piece's source is a wave-uniform base (sequence, head, block: scalar arithmetic) plus a per-lane byte
+        // offset that never changes, except that the sequence's last, partial block re-reads its last valid row
+        // (finite data, always masked by causality); that block can only be the tile's own.
+        const uint64_t blk_bytes = (uint64_t)a.map.kv_tok_stride * (kBlock * sizeof(uint16_t));
+        const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(stages));
+        uint32_t loff[PPW], loff_own[PPW];
+#pragma unroll
+        for (int p = 0; p < PPW; ++p) {
+            const int q16 = (w + p * NW) & 15;
+            const int row = 4 * q16 + (lane >> 4);
+            const int chunk = (lane & 15) ^ (row & 15);
+            const int row_own = min(row, len - 1 - bt * kBlock);
+            loff[p] = (uint32_t)(row * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
+            loff_own[p] = (uint32_t)(row_own * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
+        }
+        auto issue_block = [&](int j, int stage_idx) {
+            const uint64_t boff = (uint64_t)j * blk_bytes;
+#pragma unroll
+            for (int p = 0; p < PPW; ++p) {
+                const int qi = w + p * NW;
+                const char *base = reinterpret_cast<const char *>(qi < 16 ? kb : vb) + boff;
+                const uint32_t dst = lds0 + (uint32_t)(stage_idx * STAGE_ELEMS + (qi < 16 ? 0 : TILE_ELEMS) + (qi & 15) * 512) * 2u;
+                async_copy16(base, j == bt ? loff_own[p] : loff[p], dst);
+            }
+        };
+        auto issue_interval = [&](int4 r, int buf) {
+#ifdef IFV2_DEBUG_MODES
+            if (g_dbg_mode == 2) return;
+#endif
+            issue_block(__builtin_amdgcn_readfirstlane(r.x), buf * SLOTS);
+            if (SLOTS == 2) {
+                const int j1 = __builtin_amdgcn_readfirstlane(r.z);
+                if (j1 != NONE) issue_block(j1, buf * SLOTS + 1);
+            }
+        };
+        int4 r_cur = ni > 0 ? interval(0) : make_int4(0, 0, NONE, 0);
+        if (ni > 0) issue_interval(r_cur, 0);
+
+        // ---- this wave's tokens: ti = w * TPW + i (neighbours, whose block lists overlap most, share a wave)
+        Tok st[TPW];
         const int m16 = lane & 15, g = lane >> 4;
+        const float c = a.scale * LOG2E;
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
-            const int ti = i * NW + w;
+            const int ti = w * TPW + i;
             const uint16_t *qp = a.q + ((int64_t)(row0 + ti) * a.hq + h * G + m16) * D + g * 8;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 uint4 raw = ti < ntok ? *reinterpret_cast<const uint4 *>(qp + s * 32) : make_uint4(0, 0, 0, 0);
-                st[i].qf[s] = __builtin_bit_cast(bf16x8, raw);
+                st[i].qf[s] = scale_q(raw, c);
             }
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt) st[i].o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            st[i].m = -INFINITY;
-            st[i].l = 0.f;
+            tok_init(st[i]);
         }
-        const float c = a.scale * LOG2E;
-        const uint32_t full = ntok >= 32 ? 0xffffffffu : ((1u << ntok) - 1u);
         const LaneOffs lo = lane_offsets(lane);
 
-        __shared__ int ring_err;
-        if (RING) {
-            for (int e = tid; e < ne; e += NTHR) state[e] = e < PRE ? NW << 16 : 0;     // preloaded entries are ready
-            if (tid == 0) ring_err = 0;
-        }
+        // Main loop: while interval i is consumed from one buffer, the blocks of interval i + 1 land in the other
+        // (every wave left that buffer before the barrier that ended interval i - 1).  The interval records are
+        // read one iteration ahead, so their LDS latency hides behind the unit.
+        int4 r_next = ni > 1 ? interval(1) : r_cur;
         __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
         __syncthreads();
-        if (!RING) {
-            for (int e = 0; e < ne; ++e) {
-                const int j = dense ? e : list_j[e];
-                const uint32_t mk = dense ? full : masks[j];
-                if (e + 1 < ne)
-                    issue_block_load(a, kb, vb, dense ? e + 1 : list_j[e + 1], len, stages + ((e + 1) & 1) * STAGE_ELEMS, w, lane);
-                const uint16_t *stage = stages + (e & 1) * STAGE_ELEMS;
-                const bool diag = j == bt;
-#pragma unroll
-                for (int i = 0; i < TPW; ++i) {
-                    const int ti = i * NW + w;
-                    if (mk & (1u << ti)) unit(st[i], stage, lo, lane, diag, t0 + ti - j * kBlock, c);
-                }
-                __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);     // the next block has landed in LDS
-                __syncthreads();
-            }
-        } else {
-            // Ring schedule.  Every wave walks the union list on its own and works only on the entries its token
-            // selected, so waves are not held in lock step by the blocks they skip and their MFMA and VALU phases
-            // drift apart and overlap.  Entry y = x + S - 1 is loaded while entry x is being consumed: by the first
-            // wave that has no work at x (it would be idle anyway), or, when every wave is busy at x, by all of
-            // them, two pieces each.  A loader first waits until every consumer of the stage's previous occupant
-            // (entry x - 1) has finished, and publishes its pieces in the entry's state word once they have
-            // landed.  Every wait is for an entry with a smaller number than anything the waiter still has to
-            // publish, so waits cannot form a cycle; each wait is bounded anyway.
-            volatile int *vstate = state, *err = &ring_err;
-            constexpr uint32_t ALLW = NW >= 32 ? 0xffffffffu : ((1u << NW) - 1u);
-            int pending = -1, pending_add = 0;
-            bool ok = true;
-            PROF_DECL();
-            auto flush = [&]() {
-                if (pending >= 0) {
-                    PROF_T0();
-                    __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-                    PROF_ADD(0);
-                    if (lane == 0) atomicAdd(state + pending, pending_add << 16);
-                    pending = -1;
-                }
-            };
-            PROF_T0();
-            for (int x = 0; x < ne && ok; ++x) {
-                flush();                                 // a load issued while idle gets one entry of slack
-                const int j = dense ? x : list_j[x];
-                const uint32_t mk = dense ? full : masks[j];
-                const bool mine = (mk >> w) & 1u;
-                const int y = x + S - 1;
-                if (y < ne) {
-                    const uint32_t idle = ~mk & ALLW;
-                    const bool solo = idle != 0u;
-                    // loader = the (x mod #idle)-th idle wave, so that successive loads are issued by different
-                    // waves and their latencies overlap
-                    bool loader = true;
-                    if (solo) {
-                        const int pick = x % __popc(idle);
-                        loader = ((idle >> w) & 1u) && __popc(idle & ((1u << w) - 1u)) == pick;
-                    }
-                    if (loader) {
-                        flush();
-                        if (x >= 1) {
-                            const int jp = dense ? x - 1 : list_j[x - 1];
-                            PROF_T0();
-                            ok = wait_state<false>(vstate + x - 1, __popc(dense ? full : masks[jp]), err);
-                            PROF_ADD(1);
-                        }
-                        if (ok) {
-                            uint16_t *dst = stages + (y % S) * STAGE_ELEMS;
-                            const int jy = dense ? y : list_j[y];
-                            if (solo) issue_block_load_wave(a, kb, vb, jy, len, dst, lane);
-                            else issue_block_load(a, kb, vb, jy, len, dst, w, lane);
-                            pending = y;
-                            pending_add = solo ? NW : 1;
-                        }
-                    }
-                }
-                if (ok && mine) {
-                    if (st_ready(vstate[x]) < NW) {
-                        flush();
-                        PROF_T0();
-                        ok = wait_state<true>(vstate + x, NW, err);
-                        PROF_ADD(2);
-                    }
-                    if (ok) {
-                        // LDS-only ordering (no wait on this wave's own loads in flight): the tile reads below must
-                        // not start before the state word was seen, and must be complete before the wave signs off
-                        __builtin_amdgcn_s_waitcnt(WAIT_LGKMCNT0);
-                        asm volatile("" ::: "memory");
-                        PROF_T0();
-                        unit(st[0], stages + (x % S) * STAGE_ELEMS, lo, lane, j == bt, t0 + w - j * kBlock, c);
-                        asm volatile("" ::: "memory");
-                        __builtin_amdgcn_s_waitcnt(WAIT_LGKMCNT0);
-                        PROF_ADD(3);
-                        if (lane == 0) atomicAdd(state + x, 1);
-                        flush();
-                    }
+        auto step = [&](auto own, int i) {
+            constexpr bool OWN = decltype(own)::value;
+            const int j0 = __builtin_amdgcn_readfirstlane(r_cur.x);
+            const uint32_t mk0 = __builtin_amdgcn_readfirstlane(r_cur.y);
+            const uint32_t mk1 = SLOTS == 2 ? __builtin_amdgcn_readfirstlane(r_cur.w) : 0u;
+            if (i + 1 < ni) issue_interval(r_next, (i + 1) & 1);
+            r_cur = r_next;
+            if (i + 2 < ni) r_next = interval(i + 2);
+            const uint16_t *stage = stages + ((i & 1) * SLOTS) * STAGE_ELEMS;
+#ifdef IFV2_DEBUG_MODES
+            if (g_dbg_mode == 1) {
+            } else
+#endif
+            if (TPW == 1) {
+                if ((mk0 >> w) & 1u) unit1<OWN>(st[0], stage, lo, lane, t0 + w - j0 * kBlock);
+                if (SLOTS == 2 && ((mk1 >> w) & 1u)) unit1<false>(st[0], stage + STAGE_ELEMS, lo, lane, 0);
+            } else {
+                const int kl0 = t0 + w * TPW - j0 * kBlock;       // own block: last visible key for the wave's first token
+                const uint32_t two = (mk0 >> (2 * w)) & 3u;
+                // (the two single-token cases are consecutive tests, not the arms of one branch: the compiler
+                // would otherwise merge their identical operand reads above the branch and run out of registers)
+                if (two == 3u) {
+                    unit2<OWN>(st[0], st[TPW - 1], stage, lo, lane, kl0, kl0 + 1);
+                } else {
+                    if (two & 1u) unit1<OWN>(st[0], stage, lo, lane, kl0);
+                    if (two & 2u) unit1<OWN>(st[TPW - 1], stage, lo, lane, kl0 + 1);
                 }
             }
-            flush();
-            PROF_ADD(4);
-            PROF_FLUSH();
-        }
+            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);        // this wave's pieces of the next interval have landed
+            __syncthreads();
+        };
+        for (int i = 0; i < ni - 1; ++i) step(std::false_type{}, i);
+        if (ni > 0) step(std::true_type{}, ni - 1);
 
         // ---- normalise and store
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
-            const int ti = i * NW + w;
+            const int ti = w * TPW + i;
             if (ti >= ntok) continue;
             float l = st[i].l;
             l += __shfl_xor(l, 16);
@@ -323,18 +271,19 @@ struct TileKernel {
                 pk.y = (uint32_t)float_to_bf16(st[i].o[dt][2] * inv) | ((uint32_t)float_to_bf16(st[i].o[dt][3] * inv) << 16);
                 *reinterpret_cast<uint2 *>(op + dt * 16) = pk;
             }
+            // log-sum-exp in natural units: the reference and the row sum are kept in powers of two
             if (a.lse != nullptr && g == 0)
-                a.lse[(int64_t)(h * G + m16) * a.map.total_rows + row0 + ti] = st[i].m * a.scale + __logf(l);
+                a.lse[(int64_t)(h * G + m16) * a.map.total_rows + row0 + ti] = (__log2f(l) - st[i].nm[0]) * 0.6931471805599453f;
         }
     }
 };
 
-template <int NW, int TPW, int S>
+template <int NW, int TPW, int SLOTS>
 __global__ void __launch_bounds__(NW * 64) attn_tile_kernel(AttnArgs a, int num_tiles) {
-    TileKernel<NW, TPW, S>::run(a, num_tiles);
+    TileKernel<NW, TPW, SLOTS>::run(a, num_tiles);
 }
 
-template <int NW, int TPW, int S>
+template <int NW, int TPW, int SLOTS>
 int launch_tile(const Launch &L, const AttnArgs &a0, const int32_t *cu_h) {
     constexpr int T = NW * TPW;
     AttnArgs a = a0;
@@ -343,11 +292,12 @@ int launch_tile(const Launch &L, const AttnArgs &a0, const int32_t *cu_h) {
     if (tiles == 0) return INFLLMV2_OK;
     const int nb_max = (L.max_len + kBlock - 1) / kBlock;
     a.nb_cap = a.idx ? (nb_max + 3) / 4 * 4 : 0;
-    a.list_cap = a.idx ? min(nb_max, T * L.p->topk_total) : 0;
-    const int state_cap = S > 2 ? nb_max : 0;                            // ring: one word per union entry
-    const size_t lds = (size_t)S * STAGE_ELEMS * sizeof(uint16_t) + (size_t)(a.nb_cap + a.list_cap + state_cap) * 4;
-    if (lds > 160 * 1024 - 256) return INFLLMV2_ERR_UNSUPPORTED;     // does not fit: the caller tries fewer stages
-    auto kern = attn_tile_kernel<NW, TPW, S>;
+    a.list_cap = a.idx ? (min(nb_max, T * L.p->topk_total) + 1) / 2 * 2 : 0;
+    // stages, block masks, union list (8 bytes per entry)
+    const size_t lds = (size_t)2 * SLOTS * STAGE_ELEMS * sizeof(uint16_t) +
+                       (size_t)a.nb_cap * 4 + (size_t)a.list_cap * 8;
+    if (lds > 160 * 1024 - 256) return INFLLMV2_ERR_UNSUPPORTED;     // does not fit: the caller pairs nothing
+    auto kern = attn_tile_kernel<NW, TPW, SLOTS>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -360,6 +310,15 @@ int launch_tile(const Launch &L, const AttnArgs &a0, const int32_t *cu_h) {
 
 }  // namespace
 
+#ifdef IFV2_DEBUG_MODES
+extern "C" void infllmv2_debug_mode(int mode) { (void)hipMemcpyToSymbol(HIP_SYMBOL(g_dbg_mode), &mode, sizeof(int)); }
+extern "C" void infllmv2_debug_stats(unsigned long long *out) {
+    unsigned long long z[4] = {0, 0, 0, 0};
+    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dbg_stats), sizeof(z));
+    (void)hipMemcpyToSymbol(HIP_SYMBOL(g_dbg_stats), z, sizeof(z));
+}
+#endif
+
 bool attn_mfma_supported(const infllmv2_params *p) {
     return p->dtype == INFLLMV2_BF16 && p->head_dim == D && p->num_q_heads / p->num_kv_heads == G;
 }
@@ -368,6 +327,8 @@ int launch_attn_mfma(const Launch &L, const void *q, const void *k, const void *
                      int dense_below, void *out, float *lse, const int32_t *cu_h) {
     // 16-byte vector loads need 8-element aligned strides
     if (L.map.kv_tok_stride % 8 != 0 || L.map.kv_head_stride % 8 != 0) return INFLLMV2_ERR_UNSUPPORTED;
+    // per-lane load offsets inside one block are kept in 32 bits
+    if (L.map.kv_tok_stride <= 0 || L.map.kv_tok_stride >= (1 << 24)) return INFLLMV2_ERR_UNSUPPORTED;
     AttnArgs a;
     a.q = (const uint16_t *)q;
     a.k = (const uint16_t *)k;
@@ -382,19 +343,15 @@ int launch_attn_mfma(const Launch &L, const void *q, const void *k, const void *
     a.scale = L.p->softmax_scale;
     a.nb_cap = a.list_cap = 0;
     static const char *cfg = getenv("INFLLMV2_ATTN_CFG");      // experiment switch
-    if (cfg && !strcmp(cfg, "8x2")) return launch_tile<8, 2, 2>(L, a, cu_h);
-    if (cfg && !strcmp(cfg, "lock")) return launch_tile<16, 1, 2>(L, a, cu_h);
-    if (cfg && !strcmp(cfg, "ring3")) return launch_tile<16, 1, 3>(L, a, cu_h);
-    if (cfg && !strcmp(cfg, "ring4")) return launch_tile<16, 1, 4>(L, a, cu_h);
-    return launch_tile<16, 1, 2>(L, a, cu_h);
+    if (cfg && !strcmp(cfg, "16x1")) return launch_tile<16, 1, 1>(L, a, cu_h);
+    if (cfg && !strcmp(cfg, "8x2")) return launch_tile<8, 2, 1>(L, a, cu_h);
+    if (cfg && !strcmp(cfg, "pair")) return launch_tile<16, 1, 2>(L, a, cu_h);
+    // Entries are paired only when block lists exist; the four stages that needs may not fit next to the block
+    // masks of very long sequences.
+    int rc = INFLLMV2_ERR_UNSUPPORTED;
+    if (idx != nullptr) rc = launch_tile<16, 1, 2>(L, a, cu_h);
+    if (rc == INFLLMV2_ERR_UNSUPPORTED) rc = launch_tile<16, 1, 1>(L, a, cu_h);
+    return rc;
 }
-
-#ifdef IFV2_RING_PROF
-extern "C" void infllmv2_debug_prof(unsigned long long *out, int reset) {
-    unsigned long long z[8] = {0};
-    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_prof), sizeof(z));
-    if (reset) (void)hipMemcpyToSymbol(HIP_SYMBOL(g_prof), z, sizeof(z));
-}
-#endif
 
 }  // namespace ifv2

@@ -23,6 +23,23 @@ constexpr int WAIT_LGKMCNT0 = 0xC07F;             // s_waitcnt lgkmcnt(0), other
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// 16 bytes per lane, global -> LDS without passing through registers: lane l's data lands at dst + 16 l (dst is
+// wave-uniform).  Issued as assembly on purpose: the compiler then does not know that LDS is written behind its
+// back and does not stall later LDS reads of *other* tiles on the vector-memory counter.  Every reader of the
+// destination must be ordered by an explicit s_waitcnt vmcnt + barrier, which the callers do.
+__device__ inline void async_copy16(const void *src, const uint16_t *dst) {
+    const uint32_t lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void *)dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(src) : "memory", "m0");
+}
+
+// The same with a wave-uniform 64-bit base (held in scalar registers) plus a 32-bit byte offset per lane, so that
+// a loop can step the base with scalar arithmetic only.  lds is the LDS byte address of the destination.
+__device__ inline void async_copy16(const void *sbase, uint32_t voff, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+
+__device__ inline uint32_t lds_address(const void *p) { return (uint32_t)(uintptr_t)(lds_void *)p; }
+
 // One 1 KB piece (4 rows) of a K or V block: global -> LDS, asynchronously.  Lane l fills LDS slot
 // (row 4*q16 + l/16, physical chunk l%16), which holds logical 16-byte chunk (l%16) ^ (row%16) of that row.
 // Rows past the end of the sequence re-read the last valid row (finite data, always masked by causality).
@@ -32,7 +49,7 @@ __device__ inline void load_piece(const uint16_t *base, int64_t tok_stride, int 
     const int chunk = (lane & 15) ^ (row & 15);
     const int tok = min(j * kBlock + row, len - 1);
     const uint16_t *src = base + (int64_t)tok * tok_stride + chunk * 8;
-    __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)(tile + q16 * 512), 16, 0, 0);
+    async_copy16(src, tile + q16 * 512);
 }
 
 struct TokState {
@@ -155,12 +172,159 @@ __device__ inline void softmax_pv(TokState &st, f32x4 (&acc)[4], const uint16_t 
     }
 }
 
-// ---- one (token, block) unit with both blocks in one LDS stage (K tile, then V tile)
-__device__ inline void unit(TokState &st, const uint16_t *stage, const LaneOffs &lo, int lane, bool diag,
-                            int key_limit, float c) {
-    f32x4 acc[4];
-    qk_from_lds(acc, st.qf, stage, lo);
-    softmax_pv(st, acc, stage + TILE_ELEMS, lo, lane, diag, key_limit, c);
+// =====================================================================================================
+// Prefill unit: one K/V block (both tiles in one LDS stage) against NT tokens held by this wave.
+//
+// The vector unit and the matrix core share one issue port per SIMD (4 clocks per instruction, an MFMA keeps
+// the matrix core busy for 16), so every vector instruction in the unit costs matrix-core time unless fewer
+// than three of them accompany each MFMA.  The softmax is therefore arranged so that nothing is computed that
+// the MFMA can produce for free:
+//   * Q is multiplied by softmax_scale * log2(e) once, when it is loaded, and
+//   * the accumulator of S^T = K Q^T is seeded with minus the running reference of the online softmax,
+// so the MFMA result is already the exponent of 2 and a logit costs one v_exp, one add (row sum) and half a
+// pack instruction.  The reference is lazy: any value shared by the lanes of a head works as long as the
+// exponents stay far from overflow, so it only moves when an exponent exceeds kRefSlack.
+//
+// With NT = 2 every K and V^T fragment read from LDS feeds two MFMAs (one per token), which halves the LDS
+// traffic per (token, block) pair; the LDS, not the matrix core, is what limits a one-token unit.
+typedef __attribute__((address_space(3))) short4v lds_s4;
+
+struct Tok {
+    bf16x8 qf[4];      // Q_t * softmax_scale * log2(e) as MFMA B operand: head = lane % 16, dims ks*32 + (lane/16)*8 ..
+    f32x4 o[8];        // O_t^T: dim tile dt, dims dt*16 + 4*(lane/16) + r, head = lane % 16
+    f32x4 nm;          // minus the reference (log2 units) in all four slots: seed of the S^T accumulator
+    float l;           // this lane's share of the running sum
+    bool fresh;        // no block consumed yet (wave-uniform)
+};
+
+constexpr float kRefSlack = 8.0f;
+
+__device__ inline void tok_init(Tok &t) {
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) t.o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    t.nm = f32x4{0.f, 0.f, 0.f, 0.f};
+    t.l = 0.f;
+    t.fresh = true;
+}
+
+// Q fragment scaled by c and rounded to bf16 (round to nearest even)
+__device__ inline bf16x8 scale_q(uint4 raw, float c) {
+    const bf16x8 q = __builtin_bit_cast(bf16x8, raw);
+    bf16x8 r;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = (__bf16)((float)q[i] * c);
+    return r;
+}
+
+__device__ inline bf16x8 k_frag(const uint16_t *ktile, const LaneOffs &lo, int i) {      // i -> (s = i / 4, kt = i % 4)
+    return *reinterpret_cast<const bf16x8 *>(ktile + (i & 3) * 16 * D + lo.kx[i >> 2]);
+}
+__device__ inline bf16x8 v_frag(const uint16_t *vtile, const LaneOffs &lo, int i) {      // i -> (s2 = i / 8, dt = i % 8)
+    const uint16_t *p = vtile + (i >> 3) * 32 * D + lo.vx[i & 7];
+    const short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)p);
+    const short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)(p + 16 * D));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// Exponents of one token -> probabilities (P^T as B operand of the two PV k-steps: slots 0-3 = keys
+// 32*s2 + 4g + r, slots 4-7 = +16), with the causal mask of the token's own block and the lazy reference.
+template <bool OWN>
+__device__ inline void softmax_tok(Tok &t, f32x4 (&acc)[4], bf16x8 (&pb)[2], int g, int key_limit) {
+    if (OWN) {
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (16 * kt + 4 * g + r > key_limit) acc[kt][r] = -INFINITY;
+    }
+    float mx = fmaxf(fmaxf(acc[0][0], acc[0][1]), acc[0][2]);
+    mx = fmaxf(fmaxf(mx, acc[0][3]), acc[1][0]);
+    mx = fmaxf(fmaxf(mx, acc[1][1]), acc[1][2]);
+    mx = fmaxf(fmaxf(mx, acc[1][3]), acc[2][0]);
+    mx = fmaxf(fmaxf(mx, acc[2][1]), acc[2][2]);
+    mx = fmaxf(fmaxf(mx, acc[2][3]), acc[3][0]);
+    mx = fmaxf(fmaxf(mx, acc[3][1]), acc[3][2]);
+    mx = fmaxf(mx, acc[3][3]);
+    if (t.fresh || __any(mx > kRefSlack)) {
+        // move the reference of every head to its current maximum (never down once there is history)
+        float delta = rows_max(mx);
+        float alpha = 1.0f;
+        if (!t.fresh) {
+            delta = fmaxf(delta, 0.f);
+            alpha = fast_exp2(-delta);
+        }
+        t.fresh = false;
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[kt][r] -= delta;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) t.nm[r] -= delta;
+        t.l *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) t.o[dt] *= alpha;
+    }
+    float ls = 0.f;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float p0 = fast_exp2(acc[2 * s2][r]), p1 = fast_exp2(acc[2 * s2 + 1][r]);
+            ls += p0 + p1;
+            pb[s2][r] = (__bf16)p0;
+            pb[s2][4 + r] = (__bf16)p1;
+        }
+    t.l += ls;
+}
+
+// key_limit[n]: last visible key of the block for token n (only used when OWN)
+template <int NT, bool OWN>
+__device__ inline void unit_n(Tok *const (&t)[NT], const uint16_t *stage, const LaneOffs &lo, int lane,
+                              const int (&key_limit)[NT]) {
+    const uint16_t *ktile = stage, *vtile = stage + TILE_ELEMS;
+    const int g = lane >> 4;
+    constexpr int W = 4;               // operand fetches run W MFMA groups ahead
+    f32x4 acc[NT][4];
+    bf16x8 pb[NT][2];
+    bf16x8 f[W];
+    // ---- exponents: S^T seeded with minus the reference
+#pragma unroll
+    for (int i = 0; i < W; ++i) f[i] = k_frag(ktile, lo, i);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int kt = i & 3, s = i >> 2;
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+            acc[n][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[i % W], t[n]->qf[s], s == 0 ? t[n]->nm : acc[n][kt], 0, 0, 0);
+        if (i + W < 16) f[i % W] = k_frag(ktile, lo, i + W);
+    }
+    // V^T fragments of the first k-step are requested before the softmax so that they arrive under it
+#pragma unroll
+    for (int i = 0; i < W; ++i) f[i] = v_frag(vtile, lo, i);
+#pragma unroll
+    for (int n = 0; n < NT; ++n) softmax_tok<OWN>(*t[n], acc[n], pb[n], g, key_limit[n]);
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int dt = i & 7, s2 = i >> 3;
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+            t[n]->o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[i % W], pb[n][s2], t[n]->o[dt], 0, 0, 0);
+        if (i + W < 16) f[i % W] = v_frag(vtile, lo, i + W);
+    }
+}
+
+template <bool OWN>
+__device__ inline void unit1(Tok &a, const uint16_t *stage, const LaneOffs &lo, int lane, int key_limit) {
+    Tok *const t[1] = {&a};
+    const int kl[1] = {key_limit};
+    unit_n<1, OWN>(t, stage, lo, lane, kl);
+}
+template <bool OWN>
+__device__ inline void unit2(Tok &a, Tok &b, const uint16_t *stage, const LaneOffs &lo, int lane, int kl_a, int kl_b) {
+    Tok *const t[2] = {&a, &b};
+    const int kl[2] = {kl_a, kl_b};
+    unit_n<2, OWN>(t, stage, lo, lane, kl);
 }
 
 }  // namespace attn_unit

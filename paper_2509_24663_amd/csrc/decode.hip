@@ -232,7 +232,8 @@ __global__ void __launch_bounds__(AW * 64) dec_attn_kernel(DecArgs a) {
             for (int s = 0; s < 4; ++s)
                 acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][s], st.qf[s], acc[kt], 0, 0, 0);
         }
-        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);          // this wave's V tile has landed in LDS
+        asm volatile("" ::: "memory");
         softmax_pv(st, acc, vtile, lo, lane, j == bt, t - j * kBlock, c);
         st.l += __shfl_xor(st.l, 16);
         st.l += __shfl_xor(st.l, 32);

@@ -25,6 +25,15 @@ def out_tolerances(dtype: str):
     return (FP32_MAX_ABS, None) if dtype == "fp32" else (BF16_MAX_ABS, BF16_MEAN_ABS)
 
 
+def prefill_lse_atol(dtype: str) -> float:
+    """Tolerance for the log-sum-exp of the prefill kernels.  The bf16 tile kernel multiplies Q by
+    softmax_scale * log2(e) before the matrix product and rounds the result to bf16 again (relative error at most
+    2^-9 per element, unbiased).  With d_h = 128 and unit-scale data that perturbs a logit by about
+    2^-9 / sqrt(3) * sqrt(128) * scale * |q_i k_i| ~ 1e-3 (one sigma) and the log-sum-exp, a weighted mean of logit
+    errors, by at most a few sigma; the outputs keep their own max-abs / mean-abs bars."""
+    return 1e-2 if dtype == "bf16" else 1e-4
+
+
 def assert_out_close(got: np.ndarray, want: np.ndarray, dtype: str, what: str = "out"):
     diff = np.abs(got.astype(np.float64) - want.astype(np.float64))
     max_abs, mean_abs = out_tolerances(dtype)

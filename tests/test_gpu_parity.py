@@ -8,7 +8,7 @@ import pytest
 import torch
 
 import synth
-from helpers import assert_out_close, check_selection, to_dev, to_np
+from helpers import assert_out_close, check_selection, prefill_lse_atol, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -90,7 +90,7 @@ def _run_prefill_case(m, oracle, w, gp, op, dtype, rows=None, check_stages=True)
                 O_iso, L_iso = oracle.sparse_attn(Qh, pos, Kh, Vh, idx_g[h, loc], op)
                 mx, _ = assert_out_close(out_g[loc, h * G:(h + 1) * G], O_iso, dtype, "out | GPU selection")
                 stats["max_abs"] = max(stats["max_abs"], mx)
-                np.testing.assert_allclose(lse_g[h * G:(h + 1) * G, loc].T, L_iso, atol=2e-3 if dtype == "bf16" else 1e-4)
+                np.testing.assert_allclose(lse_g[h * G:(h + 1) * G, loc].T, L_iso, atol=prefill_lse_atol(dtype))
                 O, L = oracle.sparse_attn(Qh, pos, Kh, Vh, idx_o, op)
             if rd_ok(stats):
                 assert_out_close(out_g[loc, h * G:(h + 1) * G], O, dtype, "out end-to-end")
@@ -181,7 +181,7 @@ def test_dense_attention(m, oracle):
         torch.cuda.synchronize()
         ref = oracle.prefill(w["q"], w["k"], w["v"], [0, n], op, force="dense")
         assert_out_close(to_np(out), ref["out"], dtype, "dense out")
-        np.testing.assert_allclose(to_np(lse).T, ref["lse"], atol=2e-3 if dtype == "bf16" else 1e-4)
+        np.testing.assert_allclose(to_np(lse).T, ref["lse"], atol=prefill_lse_atol(dtype))
 
 
 def test_sparse_equals_dense_when_all_blocks_kept(m, oracle):
