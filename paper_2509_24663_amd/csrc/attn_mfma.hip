@@ -34,6 +34,8 @@ using namespace attn_unit;
 
 struct AttnArgs {
     const uint16_t *q, *k, *v;
+    const uint16_t *vt;      // V^T blocks: [kv head][block of the batch][128 dims][64 keys]
+    int nblk_total;          // blocks of the whole batch (sum over sequences of ceil(len / 64))
     const int32_t *idx;
     uint16_t *out;
     float *lse;
@@ -67,7 +69,7 @@ struct TileKernel {
         uint16_t *stages = smem;
         uint32_t *masks = reinterpret_cast<uint32_t *>(smem + NSTAGE * STAGE_ELEMS);
         int2 *rec = reinterpret_cast<int2 *>(masks + a.nb_cap);          // union list: (block, token mask) per entry
-        __shared__ int s_seq, s_tile, s_ne, s_ni;
+        __shared__ int s_seq, s_tile, s_blk0, s_ne, s_ni;
 
         const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
         const int h = blockIdx.y;
@@ -85,14 +87,17 @@ struct TileKernel {
         }
         const int tile_id = num_tiles - 1 - lin;
         if (tid == 0) {
-            int rem = tile_id, s = 0;
+            int rem = tile_id, s = 0, blk0 = 0;
             for (; s < a.map.batch; ++s) {
-                const int nt = (a.map.cu[s + 1] - a.map.cu[s] + T - 1) / T;
+                const int ln = a.map.cu[s + 1] - a.map.cu[s];
+                const int nt = (ln + T - 1) / T;
                 if (rem < nt) break;
                 rem -= nt;
+                blk0 += (ln + kBlock - 1) / kBlock;
             }
             s_seq = s;
             s_tile = rem;
+            s_blk0 = blk0;
         }
         __syncthreads();
         const int seq = __builtin_amdgcn_readfirstlane(s_seq);
@@ -104,7 +109,7 @@ struct TileKernel {
         const bool dense = a.idx == nullptr || len < a.dense_below;
         const int row0 = tok0 + t0;                      // packed row of the tile's first token
         const uint16_t *kb = a.k + (int64_t)tok0 * a.map.kv_tok_stride + (int64_t)h * a.map.kv_head_stride;
-        const uint16_t *vb = a.v + (int64_t)tok0 * a.map.kv_tok_stride + (int64_t)h * a.map.kv_head_stride;
+        const uint16_t *vtb = a.vt + ((int64_t)h * a.nblk_total + __builtin_amdgcn_readfirstlane(s_blk0)) * VT_TILE_ELEMS;
         const uint32_t full = ntok >= 32 ? 0xffffffffu : ((1u << ntok) - 1u);
 
         // ---- union of the tile's block lists: masks[j] has bit ti set if token ti selected block j.  The tile's
@@ -158,28 +163,33 @@ struct TileKernel {
             return make_int4(r0.x, r0.y, r1.x, r1.y);
         };
 
-        // ---- loads: the 32 one-KB pieces of a block (16 of K, 16 of V) are dealt round-robin to the waves.  A
-        // piece's source is a wave-uniform base (sequence, head, block: scalar arithmetic) plus a per-lane byte
-        // offset that never changes, except that the sequence's last, partial block re-reads its last valid row
-        // (finite data, always masked by causality); that block can only be the tile's own.
+        // ---- loads: the 32 one-KB pieces of a block (16 of the K tile, 16 of the V^T tile) are dealt round-robin
+        // to the waves.  A piece's source is a wave-uniform base (sequence, head, block: scalar arithmetic) plus a
+        // per-lane byte offset that never changes, except that the sequence's last, partial K block re-reads its
+        // last valid row (finite data, always masked by causality); that block can only be the tile's own.  The
+        // V^T copy is zero-padded instead.
         const uint64_t blk_bytes = (uint64_t)a.map.kv_tok_stride * (kBlock * sizeof(uint16_t));
         const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(stages));
         uint32_t loff[PPW], loff_own[PPW];
 #pragma unroll
         for (int p = 0; p < PPW; ++p) {
-            const int q16 = (w + p * NW) & 15;
-            const int row = 4 * q16 + (lane >> 4);
-            const int chunk = (lane & 15) ^ (row & 15);
-            const int row_own = min(row, len - 1 - bt * kBlock);
-            loff[p] = (uint32_t)(row * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
-            loff_own[p] = (uint32_t)(row_own * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
+            const int qi = w + p * NW;
+            if (qi < 16) {
+                int row, chunk;
+                k_piece_src(qi, lane, row, chunk);
+                const int row_own = min(row, len - 1 - bt * kBlock);
+                loff[p] = (uint32_t)(row * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
+                loff_own[p] = (uint32_t)(row_own * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
+            } else {
+                loff[p] = loff_own[p] = vt_piece_src_bytes(qi - 16, lane);
+            }
         }
         auto issue_block = [&](int j, int stage_idx) {
-            const uint64_t boff = (uint64_t)j * blk_bytes;
 #pragma unroll
             for (int p = 0; p < PPW; ++p) {
                 const int qi = w + p * NW;
-                const char *base = reinterpret_cast<const char *>(qi < 16 ? kb : vb) + boff;
+                const char *base = qi < 16 ? reinterpret_cast<const char *>(kb) + (uint64_t)j * blk_bytes
+                                           : reinterpret_cast<const char *>(vtb) + (uint64_t)j * (VT_TILE_ELEMS * sizeof(uint16_t));
                 const uint32_t dst = lds0 + (uint32_t)(stage_idx * STAGE_ELEMS + (qi < 16 ? 0 : TILE_ELEMS) + (qi & 15) * 512) * 2u;
                 async_copy16(base, j == bt ? loff_own[p] : loff[p], dst);
             }
@@ -212,7 +222,7 @@ struct TileKernel {
             }
             tok_init(st[i]);
         }
-        const LaneOffs lo = lane_offsets(lane);
+        const LaneOffs2 lo = lane_offsets2(lane);
 
         // Main loop: while interval i is consumed from one buffer, the blocks of interval i + 1 land in the other
         // (every wave left that buffer before the barrier that ended interval i - 1).  The interval records are
@@ -278,6 +288,46 @@ struct TileKernel {
     }
 };
 
+// V -> V^T: one workgroup per (block of the batch, KV head); keys past the end of a sequence become zeros.
+__global__ void __launch_bounds__(256) vt_transpose_kernel(const uint16_t *v, uint16_t *vt, RowMap map, int nblk_total) {
+    __shared__ uint16_t tile[kBlock][D + 8];
+    __shared__ int s_tok, s_rows;
+    const int tid = threadIdx.x, h = blockIdx.y;
+    if (tid == 0) {
+        int rem = blockIdx.x, s = 0;
+        for (; s < map.batch; ++s) {
+            const int nb = (map.cu[s + 1] - map.cu[s] + kBlock - 1) / kBlock;
+            if (rem < nb) break;
+            rem -= nb;
+        }
+        s_tok = s < map.batch ? map.cu[s] + rem * kBlock : 0;
+        s_rows = s < map.batch ? min(kBlock, map.cu[s + 1] - map.cu[s] - rem * kBlock) : 0;
+    }
+    __syncthreads();
+    const int rows = s_rows;
+    const uint16_t *src = v + (int64_t)s_tok * map.kv_tok_stride + (int64_t)h * map.kv_head_stride;
+    for (int i = tid; i < kBlock * (D / 8); i += 256) {
+        const int r = i / (D / 8), c = i % (D / 8);
+        uint4 x = make_uint4(0, 0, 0, 0);
+        if (r < rows) x = *reinterpret_cast<const uint4 *>(src + (int64_t)r * map.kv_tok_stride + c * 8);
+        *reinterpret_cast<uint4 *>(&tile[r][c * 8]) = x;
+    }
+    __syncthreads();
+    uint16_t *dst = vt + ((int64_t)h * nblk_total + blockIdx.x) * VT_TILE_ELEMS;
+    for (int i = tid; i < D * (kBlock / 8); i += 256) {
+        const int d = i / (kBlock / 8), c = i % (kBlock / 8);
+        uint16_t e[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) e[u] = tile[c * 8 + u][d];
+        uint4 x;
+        x.x = e[0] | ((uint32_t)e[1] << 16);
+        x.y = e[2] | ((uint32_t)e[3] << 16);
+        x.z = e[4] | ((uint32_t)e[5] << 16);
+        x.w = e[6] | ((uint32_t)e[7] << 16);
+        *reinterpret_cast<uint4 *>(dst + d * kBlock + c * 8) = x;
+    }
+}
+
 template <int NW, int TPW, int SLOTS>
 __global__ void __launch_bounds__(NW * 64) attn_tile_kernel(AttnArgs a, int num_tiles) {
     TileKernel<NW, TPW, SLOTS>::run(a, num_tiles);
@@ -342,15 +392,40 @@ int launch_attn_mfma(const Launch &L, const void *q, const void *k, const void *
     a.dense_below = dense_below;
     a.scale = L.p->softmax_scale;
     a.nb_cap = a.list_cap = 0;
-    static const char *cfg = getenv("INFLLMV2_ATTN_CFG");      // experiment switch
-    if (cfg && !strcmp(cfg, "16x1")) return launch_tile<16, 1, 1>(L, a, cu_h);
-    if (cfg && !strcmp(cfg, "8x2")) return launch_tile<8, 2, 1>(L, a, cu_h);
-    if (cfg && !strcmp(cfg, "pair")) return launch_tile<16, 1, 2>(L, a, cu_h);
-    // Entries are paired only when block lists exist; the four stages that needs may not fit next to the block
-    // masks of very long sequences.
-    int rc = INFLLMV2_ERR_UNSUPPORTED;
-    if (idx != nullptr) rc = launch_tile<16, 1, 2>(L, a, cu_h);
-    if (rc == INFLLMV2_ERR_UNSUPPORTED) rc = launch_tile<16, 1, 1>(L, a, cu_h);
+    // V^T copy for the tile kernel: stream-ordered scratch, returned to the device's pool after the launch
+    int64_t nblk_total = 0;
+    for (int s = 0; s < L.map.batch; ++s) nblk_total += (cu_h[s + 1] - cu_h[s] + kBlock - 1) / kBlock;
+    if (nblk_total == 0) return INFLLMV2_OK;
+    {   // keep freed scratch in the pool instead of returning it to the driver at every synchronisation
+        static bool pool_set[64] = {};
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && !pool_set[dev]) {
+            hipMemPool_t pool;
+            uint64_t keep = UINT64_MAX;
+            if (hipDeviceGetDefaultMemPool(&pool, dev) == hipSuccess)
+                (void)hipMemPoolSetAttribute(pool, hipMemPoolAttrReleaseThreshold, &keep);
+            pool_set[dev] = true;
+        }
+    }
+    void *ws = nullptr;
+    const size_t ws_bytes = (size_t)nblk_total * L.p->num_kv_heads * VT_TILE_ELEMS * sizeof(uint16_t);
+    if (hipMallocAsync(&ws, ws_bytes, L.stream) != hipSuccess) return INFLLMV2_ERR_HIP;
+    a.vt = (const uint16_t *)ws;
+    a.nblk_total = (int)nblk_total;
+    hipLaunchKernelGGL(vt_transpose_kernel, dim3((unsigned)nblk_total, L.p->num_kv_heads), dim3(256), 0, L.stream,
+                       a.v, (uint16_t *)ws, L.map, (int)nblk_total);
+    int rc = hip_status(hipGetLastError());
+    if (rc == INFLLMV2_OK) {
+        static const char *cfg = getenv("INFLLMV2_ATTN_CFG");      // experiment switch
+        // Two entries per interval only when block lists exist; the four stages that needs may not fit next to
+        // the block masks of very long sequences.
+        rc = INFLLMV2_ERR_UNSUPPORTED;
+        if (cfg && !strcmp(cfg, "16x1")) rc = launch_tile<16, 1, 1>(L, a, cu_h);
+        else if (cfg && !strcmp(cfg, "8x2")) rc = launch_tile<8, 2, 1>(L, a, cu_h);
+        else if (idx != nullptr) rc = launch_tile<16, 1, 2>(L, a, cu_h);
+        if (rc == INFLLMV2_ERR_UNSUPPORTED) rc = launch_tile<16, 1, 1>(L, a, cu_h);
+    }
+    if (hipFreeAsync(ws, L.stream) != hipSuccess && rc == INFLLMV2_OK) rc = INFLLMV2_ERR_HIP;
     return rc;
 }
 

@@ -185,9 +185,48 @@ __device__ inline void softmax_pv(TokState &st, f32x4 (&acc)[4], const uint16_t 
 // pack instruction.  The reference is lazy: any value shared by the lanes of a head works as long as the
 // exponents stay far from overflow, so it only moves when an exponent exceeds kRefSlack.
 //
-// With NT = 2 every K and V^T fragment read from LDS feeds two MFMAs (one per token), which halves the LDS
-// traffic per (token, block) pair; the LDS, not the matrix core, is what limits a one-token unit.
-typedef __attribute__((address_space(3))) short4v lds_s4;
+// LDS bandwidth is the other limit (a one-token unit reads 32 KB for 32 MFMAs), and 8-byte transposing reads run
+// at half the rate of 16-byte reads.  V therefore comes from a transposed copy (V^T, one [128 dims][64 keys]
+// tile per block, made by a small pre-pass), so that both operands are fetched with ds_read_b128:
+//   * K tile  [64 keys][128 dims], 256-byte rows, 16-byte chunk c of row r stored at chunk c ^ f(r),
+//     f(r) = 4 * ((r >> 3) & 3) + (r & 3);
+//   * V^T tile [128 dims][64 keys], 128-byte rows, chunk c of row r stored at chunk c ^ (r & 7).
+// Row m of the A operand of S^T's key tile kt is key 32 (kt / 2) + 8 (m / 4) + 4 (kt % 2) + (m % 4): with that
+// order the exponents a lane ends up with are exactly the eight consecutive keys 32 s2 + 8 (lane / 16) .. + 7 it
+// must supply as B operand of PV k-step s2, and f(key) = m for every kt, so one address per k-step serves all
+// key tiles through the instruction's immediate offset.
+//
+// With NT = 2 every K and V^T fragment read from LDS feeds two MFMAs (one per token).
+constexpr int VT_TILE_ELEMS = D * kBlock;            // one V^T block: 128 rows x 128 B
+
+struct LaneOffs2 {
+    int kx[4];         // K operand, k-step s: element offset of (row 8 (m16 / 4) + m16 % 4, logical chunk 4s + g)
+    int vx[2];         // V^T operand, k-step s2: element offset of (row m16, logical chunk 4 s2 + g)
+};
+
+__device__ inline LaneOffs2 lane_offsets2(int lane) {
+    LaneOffs2 o;
+    const int m16 = lane & 15, g = lane >> 4;
+    const int krow = 8 * (m16 >> 2) + (m16 & 3);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) o.kx[s] = krow * D + (((4 * s + g) ^ m16) << 3);
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) o.vx[s2] = m16 * kBlock + (((4 * s2 + g) ^ (m16 & 7)) << 3);
+    return o;
+}
+
+// Per-lane byte offsets of the asynchronous loads that fill the two tiles; piece q is 1 KB of LDS.
+// K piece q (rows 4q .. 4q+3 of the block): lane l fills (row 4q + l / 16, physical chunk l % 16).
+__device__ inline void k_piece_src(int q, int lane, int &row, int &chunk) {
+    row = 4 * q + (lane >> 4);
+    chunk = (lane & 15) ^ (4 * ((row >> 3) & 3) + (row & 3));
+}
+// V^T piece q (rows 8q .. 8q+7 of the tile): lane l fills (row 8q + l / 8, physical chunk l % 8).
+__device__ inline uint32_t vt_piece_src_bytes(int q, int lane) {
+    const int row = 8 * q + (lane >> 3);
+    const int chunk = (lane & 7) ^ (row & 7);
+    return (uint32_t)(row * kBlock + chunk * 8) * 2u;
+}
 
 struct Tok {
     bf16x8 qf[4];      // Q_t * softmax_scale * log2(e) as MFMA B operand: head = lane % 16, dims ks*32 + (lane/16)*8 ..
@@ -216,18 +255,16 @@ __device__ inline bf16x8 scale_q(uint4 raw, float c) {
     return r;
 }
 
-__device__ inline bf16x8 k_frag(const uint16_t *ktile, const LaneOffs &lo, int i) {      // i -> (s = i / 4, kt = i % 4)
-    return *reinterpret_cast<const bf16x8 *>(ktile + (i & 3) * 16 * D + lo.kx[i >> 2]);
+__device__ inline bf16x8 k_frag(const uint16_t *ktile, const LaneOffs2 &lo, int i) {     // i -> (s = i / 4, kt = i % 4)
+    const int kt = i & 3;
+    return *reinterpret_cast<const bf16x8 *>(ktile + (32 * (kt >> 1) + 4 * (kt & 1)) * D + lo.kx[i >> 2]);
 }
-__device__ inline bf16x8 v_frag(const uint16_t *vtile, const LaneOffs &lo, int i) {      // i -> (s2 = i / 8, dt = i % 8)
-    const uint16_t *p = vtile + (i >> 3) * 32 * D + lo.vx[i & 7];
-    const short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)p);
-    const short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)(p + 16 * D));
-    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
+__device__ inline bf16x8 v_frag(const uint16_t *vtile, const LaneOffs2 &lo, int i) {     // i -> (s2 = i / 8, dt = i % 8)
+    return *reinterpret_cast<const bf16x8 *>(vtile + (i & 7) * 16 * kBlock + lo.vx[i >> 3]);
 }
 
-// Exponents of one token -> probabilities (P^T as B operand of the two PV k-steps: slots 0-3 = keys
-// 32*s2 + 4g + r, slots 4-7 = +16), with the causal mask of the token's own block and the lazy reference.
+// Exponents of one token -> probabilities (P^T as B operand of the two PV k-steps: slot i = key 32 s2 + 8g + i),
+// with the causal mask of the token's own block and the lazy reference.
 template <bool OWN>
 __device__ inline void softmax_tok(Tok &t, f32x4 (&acc)[4], bf16x8 (&pb)[2], int g, int key_limit) {
     if (OWN) {
@@ -235,7 +272,7 @@ __device__ inline void softmax_tok(Tok &t, f32x4 (&acc)[4], bf16x8 (&pb)[2], int
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                if (16 * kt + 4 * g + r > key_limit) acc[kt][r] = -INFINITY;
+                if (32 * (kt >> 1) + 8 * g + 4 * (kt & 1) + r > key_limit) acc[kt][r] = -INFINITY;
     }
     float mx = fmaxf(fmaxf(acc[0][0], acc[0][1]), acc[0][2]);
     mx = fmaxf(fmaxf(mx, acc[0][3]), acc[1][0]);
@@ -279,7 +316,7 @@ __device__ inline void softmax_tok(Tok &t, f32x4 (&acc)[4], bf16x8 (&pb)[2], int
 
 // key_limit[n]: last visible key of the block for token n (only used when OWN)
 template <int NT, bool OWN>
-__device__ inline void unit_n(Tok *const (&t)[NT], const uint16_t *stage, const LaneOffs &lo, int lane,
+__device__ inline void unit_n(Tok *const (&t)[NT], const uint16_t *stage, const LaneOffs2 &lo, int lane,
                               const int (&key_limit)[NT]) {
     const uint16_t *ktile = stage, *vtile = stage + TILE_ELEMS;
     const int g = lane >> 4;
@@ -315,13 +352,13 @@ __device__ inline void unit_n(Tok *const (&t)[NT], const uint16_t *stage, const 
 }
 
 template <bool OWN>
-__device__ inline void unit1(Tok &a, const uint16_t *stage, const LaneOffs &lo, int lane, int key_limit) {
+__device__ inline void unit1(Tok &a, const uint16_t *stage, const LaneOffs2 &lo, int lane, int key_limit) {
     Tok *const t[1] = {&a};
     const int kl[1] = {key_limit};
     unit_n<1, OWN>(t, stage, lo, lane, kl);
 }
 template <bool OWN>
-__device__ inline void unit2(Tok &a, Tok &b, const uint16_t *stage, const LaneOffs &lo, int lane, int kl_a, int kl_b) {
+__device__ inline void unit2(Tok &a, Tok &b, const uint16_t *stage, const LaneOffs2 &lo, int lane, int kl_a, int kl_b) {
     Tok *const t[2] = {&a, &b};
     const int kl[2] = {kl_a, kl_b};
     unit_n<2, OWN>(t, stage, lo, lane, kl);
