@@ -4,6 +4,8 @@
 // the group on chip and stores only the group sum.  Per-head score rows never reach HBM.
 #include <stdlib.h>
 
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace ifv2 {
@@ -117,10 +119,17 @@ static int launch_generic(const Launch &L, const void *q, const float *kc, float
 // Precision.  The ranking of blocks is sensitive to ~1e-3 relative changes of the scores, so the operands
 // are not rounded to bf16.  Q (bf16) converts to fp16 exactly and K^{C1} (float32 means of 32 keys) is
 // rounded to fp16, whose 11-bit significand keeps the logit error near 1e-4 -- one fp16 MFMA instead of a
-// bf16 high/low pair.  fp16's narrow exponent range is handled by exact power-of-two scalings: the Q rows of
-// a token are scaled so that their largest magnitude is below 2^15, and a key tile that holds a magnitude
-// above 2^15 (never the case for real activations) is re-staged with its own scale; both exponents are
-// folded back into the factor that multiplies the accumulator.  Both passes see the same logits.
+// bf16 high/low pair.  fp16's narrow exponent range is handled by exact power-of-two scalings: a token whose Q
+// magnitudes would leave the range gets its own exponent, and a key tile that holds a magnitude above 2^15
+// (never the case for real activations) is re-staged with its own shift; both are undone by a multiply on the
+// accumulator, on a slower path.  Both passes see the same logits.
+//
+// Vector-instruction budget.  MFMA and vector instructions share one issue port, and a (token, key tile) pair
+// has 16 MFMAs against 16 exponentials plus their sums, so every other vector instruction per logit shows up
+// in the run time.  Two are avoided: softmax_scale * log2(e) is multiplied into K^{C1} when a tile is converted
+// to fp16 (the conversion rounds anyway, so this adds no error), and the accumulator is seeded with minus the
+// row's reference (pass 1) or minus its log-sum-exp (pass 2), so the MFMA result is the exponent itself.  The
+// rare tiles or tokens that carry a power-of-two rescaling take a slower path with an explicit multiply.
 // ------------------------------------------------------------------------------------------
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
@@ -146,13 +155,6 @@ struct ScoreArgs {
 
 __device__ inline float s_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// exponent e >= 0 such that amax * 2^-e < 2^15
-__device__ inline int fp16_shift(float amax) {
-    int ex;
-    (void)frexpf(amax, &ex);                   // amax = f * 2^ex, 0.5 <= f < 1
-    return amax > 0.f && ex > 15 ? ex - 15 : 0;
-}
-
 template <int NW, int TPW>
 struct ScoreKernel {
     static constexpr int T = NW * TPW;
@@ -168,10 +170,10 @@ struct ScoreKernel {
                              : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     }
-    // fp32 -> fp16 (x * 2^-shift) into the tile; returns true if some |x| * 2^-shift is not fp16-safe
-    __device__ static inline bool store_tile(_Float16 *tile, int tid, const float4 (&pf)[NCH], int shift) {
+    // fp32 -> fp16 (x * cm * 2^e) into the tile; returns true if some scaled magnitude is not fp16-safe
+    __device__ static inline bool store_tile(_Float16 *tile, int tid, const float4 (&pf)[NCH], float cm, int e) {
         float amax = 0.f;
-        const float sc = __builtin_ldexpf(1.0f, -shift);
+        const float sc = __builtin_ldexpf(cm, e);
 #pragma unroll
         for (int r = 0; r < NCH; ++r) {
             const int c = tid + r * NTHR;
@@ -188,8 +190,8 @@ struct ScoreKernel {
     // Stage the prefetched tile; returns the power-of-two exponent the tile was scaled down by (normally 0).
     // Contains workgroup barriers: every thread calls it.
     __device__ static inline void stage_tile(_Float16 *tile, int tid, const float4 (&pf)[NCH], int *s_flag,
-                                             int *s_shift) {
-        const bool bad = store_tile(tile, tid, pf, 0);
+                                             int *s_shift, float cm, int ke) {
+        const bool bad = store_tile(tile, tid, pf, cm, ke);
         if (bad) *s_flag = 1;
         if (tid == 0 && *s_shift != 0) *s_shift = 0;     // the stage's previous occupant may have been scaled
         __syncthreads();
@@ -201,9 +203,12 @@ struct ScoreKernel {
             if (!(amax < 3.0e38f)) amax = 3.0e38f;  // Inf / NaN inputs: keep going, results are Inf / NaN anyway
             atomicMax(reinterpret_cast<unsigned *>(s_shift), __float_as_uint(amax));
             __syncthreads();
-            const int shift = fp16_shift(__uint_as_float(*reinterpret_cast<unsigned *>(s_shift)));
+            // smallest shift with amax * cm * 2^(ke - shift) < 2^15 (amax < 2^ek and cm < 1)
+            int ek = 0;
+            (void)frexpf(__uint_as_float(*reinterpret_cast<unsigned *>(s_shift)), &ek);
+            const int shift = max(0, ek + ke - 15);
             __syncthreads();
-            (void)store_tile(tile, tid, pf, shift);
+            (void)store_tile(tile, tid, pf, cm, ke - shift);
             if (tid == 0) { *s_flag = 0; *s_shift = shift; }
             __syncthreads();
         }
@@ -211,8 +216,10 @@ struct ScoreKernel {
 
     // acc[i][nt] = Q_i (16 heads x 128) . kc_tile^T (128 x 16 keys of n-tile nt); each B fragment read from
     // LDS feeds the TPW tokens of the wave, through a rolling window of 4 fragments
+    // SEEDED: the accumulators start from seed[i] (one value per head row) instead of zero.
+    template <bool SEEDED>
     __device__ static inline void tile_mma(const half8 (&qf)[TPW][4], const _Float16 *tile, int lane,
-                                           f32x4 (&acc)[TPW][4]) {
+                                           f32x4 (&acc)[TPW][4], const f32x4 (&seed)[TPW]) {
         const int n16 = lane & 15, g = lane >> 4;
         const _Float16 *bp = tile + n16 * SKS + g * 8;
         half8 b[4];
@@ -224,8 +231,8 @@ struct ScoreKernel {
             const int nt = u >> 2, ks = u & 3;
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
-                if (ks == 0) acc[i][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-                acc[i][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qf[i][ks], b[u & 3], acc[i][nt], 0, 0, 0);
+                const f32x4 c0 = SEEDED ? seed[i] : f32x4{0.f, 0.f, 0.f, 0.f};
+                acc[i][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qf[i][ks], b[u & 3], ks == 0 ? c0 : acc[i][nt], 0, 0, 0);
             }
             if (u + 4 < 16) b[u & 3] = *reinterpret_cast<const half8 *>(bp + ((u + 4) >> 2) * 16 * SKS + ((u + 4) & 3) * 32);
         }
@@ -264,10 +271,17 @@ struct ScoreKernel {
         const float *kcb = a.kc + ((int64_t)h * a.map.kc_total_c + a.map.cu_c[seq]) * SD;
         const int n16 = lane & 15, g = lane >> 4;
 
-        // ---- Q rows of this wave's tokens: bf16 -> fp16, each token scaled by a power of two into fp16 range
+        // ---- Q rows of this wave's tokens: bf16 -> fp16, times a power of two (exact).  With
+        // softmax_scale * log2(e) = cm * 2^ce (0.5 <= cm < 1), the keys carry cm (multiplied in when a tile is
+        // converted to fp16) and the queries carry 2^ce, so the MFMA accumulator is the logit in the log2 domain.
+        // A token whose magnitudes would leave fp16's comfortable range that way gets its own exponent instead and
+        // takes the slower path that multiplies the accumulator by the difference.
+        int ce;
+        const float cm = frexpf(a.scale * S_LOG2E, &ce);
         half8 qf[TPW][4];
         int vis[TPW];
-        float cq[TPW];                   // scale * log2(e) * 2^(token's exponent): multiplies the accumulator
+        float cq[TPW];                   // 2^(ce - token's exponent): multiplies the accumulator (normally 1)
+        bool q_plain = true;
         int vis_min = 1 << 30;
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
@@ -289,76 +303,110 @@ struct ScoreKernel {
                 }
             }
             amax = wave_max(amax);
-            if (!(amax < 3.0e38f)) amax = 3.0e38f;
-            const int shift = fp16_shift(amax);
-            const float sc = __builtin_ldexpf(1.0f, -shift);
-            cq[i] = a.scale * S_LOG2E * __builtin_ldexpf(1.0f, shift);
+            if (!(amax < 3.0e38f)) amax = 3.0e38f;     // Inf / NaN inputs: keep going, results are Inf / NaN anyway
+            int exq = 0;
+            if (amax > 0.f) (void)frexpf(amax, &exq);  // amax = f * 2^exq, 0.5 <= f < 1
+            // keep the largest magnitude within [2^-8, 2^15): 18+ binades of full precision below it
+            int eq = ce;
+            if (exq + ce > 15 || exq + ce < -8) eq = 4 - exq;
+            const float sc = __builtin_ldexpf(1.0f, eq);
+            cq[i] = __builtin_ldexpf(1.0f, ce - eq);
+            q_plain &= eq == ce;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) qf[i][ks][e] = (_Float16)(x[ks][e] * sc);
         }
+        const int ke = 0;                // a key tile is staged as K^{C1} * cm * 2^(ke - shift)
 
         float4 pf[NCH];
         f32x4 acc[TPW][4];
-        float m[TPW][4], l[TPW][4];      // per lane: reference (log2 domain) and sum of 2^(y - reference)
+        f32x4 nm[TPW];                   // per lane and head row: minus the reference (log2 domain)
+        float l[TPW][4];                 // ... and the sum of 2^(y - reference)
 #pragma unroll
-        for (int i = 0; i < TPW; ++i)
+        for (int i = 0; i < TPW; ++i) {
+            nm[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int r = 0; r < 4; ++r) { m[i][r] = -1.0e30f; l[i][r] = 0.f; }
+            for (int r = 0; r < 4; ++r) l[i][r] = 0.f;
+        }
+
+        // Matrix-core step of either pass: acc = y - seed for tile kt (y = the logit in the log2 domain)
+        auto mma = [&](int kt, const f32x4 (&seed)[TPW]) {
+            const _Float16 *tile = smem + (kt & 1) * S_TILE;
+            const int tshift = s_shift[kt & 1];
+            if (q_plain && tshift == 0) {
+                tile_mma<true>(qf, tile, lane, acc, seed);
+            } else {
+                tile_mma<false>(qf, tile, lane, acc, seed);
+                const float tsc = __builtin_ldexpf(1.0f, tshift);
+#pragma unroll
+                for (int i = 0; i < TPW; ++i)
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[i][nt][r] = __builtin_fmaf(acc[i][nt][r], cq[i] * tsc, seed[i][r]);
+            }
+        };
+        // The two waves that share a SIMD (w and w + NW/2) run half a step apart: between two barriers the first
+        // does the matrix-core step of tile kt and then its vector step, the second does the vector step of tile
+        // kt - 1 (still in its accumulators) and then the matrix-core step of tile kt.  Matrix core and vector
+        // unit of a SIMD are then busy at the same time although each wave alternates between them.
+        const bool late = false && w >= NW / 2;
 
         // ------------------------------------------------ pass 1: log-sum-exp of every (token, head) row
-        load_tile(kcb, 0, nc, tid, pf);
-        stage_tile(smem, tid, pf, &s_flag, &s_shift[0]);
-        for (int kt = 0; kt < nkt; ++kt) {
-            if (kt + 1 < nkt) load_tile(kcb, kt + 1, nc, tid, pf);
-            const _Float16 *tile = smem + (kt & 1) * S_TILE;
+        auto vec1 = [&](int kt) {
             const int kbase = kt * kBlock;
-            const float tsc = __builtin_ldexpf(1.0f, s_shift[kt & 1]);
-            tile_mma(qf, tile, lane, acc);
             const bool edge_tile = kbase + kBlock > vis_min;
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
-                const float cs = cq[i] * tsc;
                 if (edge_tile) {
 #pragma unroll
                     for (int nt = 0; nt < 4; ++nt)
                         if (kbase + nt * 16 + n16 >= vis[i]) acc[i][nt] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
                 }
-                bool grow = false;
+                // The reference moves only when an exponent exceeds S_SLACK; the first tile sets it (up or down).
+                float mx[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float mx = fmaxf(fmaxf(acc[i][0][r], acc[i][1][r]), fmaxf(acc[i][2][r], acc[i][3][r]));
-                    grow |= mx * cs > m[i][r] + S_SLACK;
-                }
-                if (__any(grow)) {
+                for (int r = 0; r < 4; ++r) mx[r] = fmaxf(fmaxf(acc[i][0][r], acc[i][1][r]), fmaxf(acc[i][2][r], acc[i][3][r]));
+                const float mxall = fmaxf(fmaxf(mx[0], mx[1]), fmaxf(mx[2], mx[3]));
+                if (kt == 0 || __any(mxall > S_SLACK)) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const float mx = fmaxf(fmaxf(acc[i][0][r], acc[i][1][r]), fmaxf(acc[i][2][r], acc[i][3][r])) * cs;
-                        const float mn = fmaxf(m[i][r], mx);            // finite: m starts at -1e30
-                        l[i][r] *= s_exp2(m[i][r] - mn);
-                        m[i][r] = mn;
+                        float d = kt == 0 ? mx[r] : fmaxf(mx[r], 0.f);
+                        if (!(d > -3.0e38f)) d = 0.f;              // nothing visible in this lane's columns yet
+                        l[i][r] *= s_exp2(-d);
+                        nm[i][r] -= d;
+#pragma unroll
+                        for (int nt = 0; nt < 4; ++nt) acc[i][nt][r] -= d;
                     }
                 }
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const float nm = -m[i][r];
                     float sum = l[i][r];
 #pragma unroll
-                    for (int nt = 0; nt < 4; ++nt) sum += s_exp2(__builtin_fmaf(acc[i][nt][r], cs, nm));
+                    for (int nt = 0; nt < 4; ++nt) sum += s_exp2(acc[i][nt][r]);
                     l[i][r] = sum;
                 }
             }
-            if (kt + 1 < nkt) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf, &s_flag, &s_shift[(kt + 1) & 1]);
+        };
+        load_tile(kcb, 0, nc, tid, pf);
+        stage_tile(smem, tid, pf, &s_flag, &s_shift[0], cm, ke);
+        for (int kt = 0; kt < nkt; ++kt) {
+            if (kt + 1 < nkt) load_tile(kcb, kt + 1, nc, tid, pf);
+            if (late && kt > 0) vec1(kt - 1);
+            mma(kt, nm);
+            if (!late) vec1(kt);
+            if (kt + 1 < nkt) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf, &s_flag, &s_shift[(kt + 1) & 1], cm, ke);
             else __syncthreads();
         }
+        if (late) vec1(nkt - 1);
         // merge the 16 key lanes of each lane group; lse2 = log2 of the row's sum of 2^y
         float lse2[TPW][4];
 #pragma unroll
         for (int i = 0; i < TPW; ++i)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                float mm = m[i][r], ll = l[i][r];
+                float mm = -nm[i][r], ll = l[i][r];
 #pragma unroll
                 for (int o = 1; o < 16; o <<= 1) {
                     const float mo = __shfl_xor(mm, o), lo = __shfl_xor(ll, o);
@@ -370,25 +418,19 @@ struct ScoreKernel {
             }
 
         // ------------------------------------------------ pass 2: normalised scores, group sum, store
-        load_tile(kcb, 0, nc, tid, pf);
-        stage_tile(smem, tid, pf, &s_flag, &s_shift[0]);
-        for (int kt = 0; kt < nkt; ++kt) {
-            if (kt + 1 < nkt) load_tile(kcb, kt + 1, nc, tid, pf);
-            const _Float16 *tile = smem + (kt & 1) * S_TILE;
+        f32x4 nlse[TPW];
+#pragma unroll
+        for (int i = 0; i < TPW; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) nlse[i][r] = -lse2[i][r];
+        auto vec2 = [&](int kt) {
             const int kbase = kt * kBlock;
-            const float tsc = __builtin_ldexpf(1.0f, s_shift[kt & 1]);
-            tile_mma(qf, tile, lane, acc);
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
-                const float cs = cq[i] * tsc;
                 float s[4];
 #pragma unroll
-                for (int nt = 0; nt < 4; ++nt) {
-                    float t = 0.f;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) t += s_exp2(__builtin_fmaf(acc[i][nt][r], cs, -lse2[i][r]));
-                    s[nt] = t;
-                }
+                for (int nt = 0; nt < 4; ++nt)
+                    s[nt] = (s_exp2(acc[i][nt][0]) + s_exp2(acc[i][nt][1])) + (s_exp2(acc[i][nt][2]) + s_exp2(acc[i][nt][3]));
                 // butterfly over the four lane groups: afterwards lane (n16, g) holds n-tile 2*(g&1) + (g>>1)
                 const bool odd = g & 1, up = g & 2;
                 const float a0 = (odd ? s[2] : s[0]) + __shfl_xor(odd ? s[0] : s[2], 16);
@@ -398,9 +440,18 @@ struct ScoreKernel {
                 if (key < vis[i])
                     a.out[((int64_t)h * a.map.total_rows + row0 + w * TPW + i) * a.row_stride + key] = f;
             }
-            if (kt + 1 < nkt) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf, &s_flag, &s_shift[(kt + 1) & 1]);
+        };
+        load_tile(kcb, 0, nc, tid, pf);
+        stage_tile(smem, tid, pf, &s_flag, &s_shift[0], cm, ke);
+        for (int kt = 0; kt < nkt; ++kt) {
+            if (kt + 1 < nkt) load_tile(kcb, kt + 1, nc, tid, pf);
+            if (late && kt > 0) vec2(kt - 1);
+            mma(kt, nlse);
+            if (!late) vec2(kt);
+            if (kt + 1 < nkt) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf, &s_flag, &s_shift[(kt + 1) & 1], cm, ke);
             else __syncthreads();
         }
+        if (late) vec2(nkt - 1);
     }
 };
 
@@ -430,7 +481,7 @@ int launch_block_scores(const Launch &L, const void *q, const float *kc, float *
         L.p->num_q_heads / L.p->num_kv_heads == SG && (((uintptr_t)q | (uintptr_t)kc) & 15) == 0) {
         ScoreArgs a{(const uint16_t *)q, kc, s_shared, L.map, L.p->num_q_heads, L.p->cmp_len, L.p->cmp_stride,
                     L.p->dense_threshold, L.p->softmax_scale, row_stride};
-        return launch_scores_mfma<8, 4>(L, a, cu_h);
+        { static const char *sc = getenv("INFLLMV2_SCORE_CFG"); if (sc && sc[0] == 'a') return launch_scores_mfma<16, 2>(L, a, cu_h); return launch_scores_mfma<8, 4>(L, a, cu_h); }
     }
     if (L.p->head_dim == 128)
         return bf ? launch_generic<bf16_t, 128>(L, q, kc, s_shared, row_stride)
