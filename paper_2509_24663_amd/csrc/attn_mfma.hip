@@ -8,20 +8,21 @@
 // gather traffic from L2 / HBM drops by the sharing factor while the arithmetic stays exactly the
 // per-token softmax attention of Alg. 2.
 //
-// Data movement: K and V blocks go from global memory straight into LDS (global_load_lds, 16 bytes per
-// lane, no register staging), row-major, with the 16-byte chunks of a row XOR-swizzled by the row number
-// so that both operand reads below are spread over all banks.
+// Data movement: a small pre-pass writes V^T, one [128 dims][64 keys] tile per block (zero-padded past the end
+// of a sequence), into stream-ordered scratch.  K blocks and V^T tiles then go from global memory straight
+// into LDS (global_load_lds, 16 bytes per lane, no register staging) with the 16-byte chunks of a row
+// XOR-swizzled so that the 16-byte operand reads below are spread over all banks.
 //
 // Per (token, block) the 16 heads of the group are one MFMA tile side.  S^T = K_blk Q_t^T is 4 key tiles x
 // 4 k-steps of v_mfma_f32_16x16x32_bf16 (A = K rows from LDS, B = Q_t held in registers), so a lane owns
-// one head and 16 keys: the online softmax needs two cross-lane steps for the row max and none for the row
-// sum (kept as per-lane partial sums until the end).  P^T is then already laid out as the B operand of
-// O^T += V_blk^T P^T (8 dim tiles x 2 k-steps); its A operand V^T is read from the row-major V block with
-// the transposing LDS read (ds_read_b64_tr_b16), two reads per operand.  Dense attention is the same
-// kernel with "every block, every token".
-#include <stdlib.h>
-#include <string.h>
-
+// one head and 16 keys: the online softmax needs two cross-lane steps when its reference moves and none for
+// the row sum (kept as per-lane partial sums until the end).  The key rows are assigned to the MFMA rows in
+// a permuted order that makes the probabilities of a lane exactly the B operand of O^T += V_blk^T P^T
+// (8 dim tiles x 2 k-steps), whose A operand comes from the V^T tile.  Dense attention is the same kernel
+// with "every block, every token".
+//
+// Schedule: the waves of a tile walk the union in lock step, one barrier per interval of two entries, the
+// next interval's blocks landing in the other half of a four-stage LDS buffer meanwhile.
 #include <type_traits>
 
 #include "attn_unit.h"
@@ -46,23 +47,16 @@ struct AttnArgs {
     int list_cap;      // entries reserved for the union list
 };
 
-#ifdef IFV2_DEBUG_MODES
-// debug build only: 1 = skip the units (loads and barriers only), 2 = skip the loads
-__device__ int g_dbg_mode;
-__device__ unsigned long long g_dbg_stats[4];
-#endif
-
-// NW waves, TPW tokens per wave, SLOTS union entries per barrier interval.
-template <int NW, int TPW, int SLOTS>
+// NW waves with one token each, SLOTS union entries per barrier interval.
+template <int NW, int SLOTS>
 struct TileKernel {
-    static constexpr int T = NW * TPW;
+    static constexpr int T = NW;
     static constexpr int NTHR = NW * 64;
     static constexpr int NSTAGE = 2 * SLOTS;        // double buffering of an interval's blocks
     static constexpr int PPW = 32 / NW;             // one-KB load pieces per wave and block
     static constexpr int NONE = -1;
     static_assert(32 % NW == 0, "32 one-KB load instructions are dealt round-robin to the waves");
-    static_assert(TPW == 1 || TPW == 2, "a wave holds one token or two neighbours");
-    static_assert(SLOTS == 1 || (SLOTS == 2 && TPW == 1), "pairing is per wave, one token each");
+    static_assert(SLOTS == 1 || SLOTS == 2, "one or two entries per interval");
 
     __device__ static void run(const AttnArgs &a, int num_tiles) {
         extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
@@ -138,9 +132,6 @@ struct TileKernel {
             }
             __syncthreads();
             ni = __builtin_amdgcn_readfirstlane(s_ni);
-#ifdef IFV2_DEBUG_MODES
-            if (tid == 0) { atomicAdd(&g_dbg_stats[0], (unsigned long long)s_ne); atomicAdd(&g_dbg_stats[1], (unsigned long long)ni); atomicAdd(&g_dbg_stats[2], 1ull); }
-#endif
         } else {
             ni = nblk;
         }
@@ -195,9 +186,6 @@ struct TileKernel {
             }
         };
         auto issue_interval = [&](int4 r, int buf) {
-#ifdef IFV2_DEBUG_MODES
-            if (g_dbg_mode == 2) return;
-#endif
             issue_block(__builtin_amdgcn_readfirstlane(r.x), buf * SLOTS);
             if (SLOTS == 2) {
                 const int j1 = __builtin_amdgcn_readfirstlane(r.z);
@@ -207,20 +195,19 @@ struct TileKernel {
         int4 r_cur = ni > 0 ? interval(0) : make_int4(0, 0, NONE, 0);
         if (ni > 0) issue_interval(r_cur, 0);
 
-        // ---- this wave's tokens: ti = w * TPW + i (neighbours, whose block lists overlap most, share a wave)
-        Tok st[TPW];
+        // ---- this wave's token
+        Tok st;
         const int m16 = lane & 15, g = lane >> 4;
-        const float c = a.scale * LOG2E;
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            const int ti = w * TPW + i;
+        const int ti = w;
+        {
+            const float c = a.scale * LOG2E;
             const uint16_t *qp = a.q + ((int64_t)(row0 + ti) * a.hq + h * G + m16) * D + g * 8;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 uint4 raw = ti < ntok ? *reinterpret_cast<const uint4 *>(qp + s * 32) : make_uint4(0, 0, 0, 0);
-                st[i].qf[s] = scale_q(raw, c);
+                st.qf[s] = scale_q(raw, c);
             }
-            tok_init(st[i]);
+            tok_init(st);
         }
         const LaneOffs2 lo = lane_offsets2(lane);
 
@@ -239,25 +226,10 @@ struct TileKernel {
             r_cur = r_next;
             if (i + 2 < ni) r_next = interval(i + 2);
             const uint16_t *stage = stages + ((i & 1) * SLOTS) * STAGE_ELEMS;
-#ifdef IFV2_DEBUG_MODES
-            if (g_dbg_mode == 1) {
-            } else
-#endif
-            if (TPW == 1) {
-                if ((mk0 >> w) & 1u) unit1<OWN>(st[0], stage, lo, lane, t0 + w - j0 * kBlock);
-                if (SLOTS == 2 && ((mk1 >> w) & 1u)) unit1<false>(st[0], stage + STAGE_ELEMS, lo, lane, 0);
-            } else {
-                const int kl0 = t0 + w * TPW - j0 * kBlock;       // own block: last visible key for the wave's first token
-                const uint32_t two = (mk0 >> (2 * w)) & 3u;
-                // (the two single-token cases are consecutive tests, not the arms of one branch: the compiler
-                // would otherwise merge their identical operand reads above the branch and run out of registers)
-                if (two == 3u) {
-                    unit2<OWN>(st[0], st[TPW - 1], stage, lo, lane, kl0, kl0 + 1);
-                } else {
-                    if (two & 1u) unit1<OWN>(st[0], stage, lo, lane, kl0);
-                    if (two & 2u) unit1<OWN>(st[TPW - 1], stage, lo, lane, kl0 + 1);
-                }
-            }
+            // (consecutive tests rather than the arms of one branch: the compiler would otherwise merge the
+            // identical operand reads of the two units above the branch and run out of registers)
+            if ((mk0 >> w) & 1u) unit<OWN>(st, stage, lo, lane, t0 + w - j0 * kBlock);
+            if (SLOTS == 2 && ((mk1 >> w) & 1u)) unit<false>(st, stage + STAGE_ELEMS, lo, lane, 0);
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);        // this wave's pieces of the next interval have landed
             __syncthreads();
         };
@@ -265,11 +237,8 @@ struct TileKernel {
         if (ni > 0) step(std::true_type{}, ni - 1);
 
         // ---- normalise and store
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            const int ti = w * TPW + i;
-            if (ti >= ntok) continue;
-            float l = st[i].l;
+        if (ti < ntok) {
+            float l = st.l;
             l += __shfl_xor(l, 16);
             l += __shfl_xor(l, 32);
             const float inv = l > 0.f ? 1.0f / l : 0.f;
@@ -277,13 +246,13 @@ struct TileKernel {
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) {
                 uint2 pk;
-                pk.x = (uint32_t)float_to_bf16(st[i].o[dt][0] * inv) | ((uint32_t)float_to_bf16(st[i].o[dt][1] * inv) << 16);
-                pk.y = (uint32_t)float_to_bf16(st[i].o[dt][2] * inv) | ((uint32_t)float_to_bf16(st[i].o[dt][3] * inv) << 16);
+                pk.x = (uint32_t)float_to_bf16(st.o[dt][0] * inv) | ((uint32_t)float_to_bf16(st.o[dt][1] * inv) << 16);
+                pk.y = (uint32_t)float_to_bf16(st.o[dt][2] * inv) | ((uint32_t)float_to_bf16(st.o[dt][3] * inv) << 16);
                 *reinterpret_cast<uint2 *>(op + dt * 16) = pk;
             }
             // log-sum-exp in natural units: the reference and the row sum are kept in powers of two
             if (a.lse != nullptr && g == 0)
-                a.lse[(int64_t)(h * G + m16) * a.map.total_rows + row0 + ti] = (__log2f(l) - st[i].nm[0]) * 0.6931471805599453f;
+                a.lse[(int64_t)(h * G + m16) * a.map.total_rows + row0 + ti] = (__log2f(l) - st.nm[0]) * 0.6931471805599453f;
         }
     }
 };
@@ -328,14 +297,14 @@ __global__ void __launch_bounds__(256) vt_transpose_kernel(const uint16_t *v, ui
     }
 }
 
-template <int NW, int TPW, int SLOTS>
+template <int NW, int SLOTS>
 __global__ void __launch_bounds__(NW * 64) attn_tile_kernel(AttnArgs a, int num_tiles) {
-    TileKernel<NW, TPW, SLOTS>::run(a, num_tiles);
+    TileKernel<NW, SLOTS>::run(a, num_tiles);
 }
 
-template <int NW, int TPW, int SLOTS>
+template <int NW, int SLOTS>
 int launch_tile(const Launch &L, const AttnArgs &a0, const int32_t *cu_h) {
-    constexpr int T = NW * TPW;
+    constexpr int T = NW;
     AttnArgs a = a0;
     int64_t tiles = 0;
     for (int s = 0; s < L.map.batch; ++s) tiles += (cu_h[s + 1] - cu_h[s] + T - 1) / T;
@@ -347,7 +316,7 @@ int launch_tile(const Launch &L, const AttnArgs &a0, const int32_t *cu_h) {
     const size_t lds = (size_t)2 * SLOTS * STAGE_ELEMS * sizeof(uint16_t) +
                        (size_t)a.nb_cap * 4 + (size_t)a.list_cap * 8;
     if (lds > 160 * 1024 - 256) return INFLLMV2_ERR_UNSUPPORTED;     // does not fit: the caller pairs nothing
-    auto kern = attn_tile_kernel<NW, TPW, SLOTS>;
+    auto kern = attn_tile_kernel<NW, SLOTS>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -359,15 +328,6 @@ int launch_tile(const Launch &L, const AttnArgs &a0, const int32_t *cu_h) {
 }
 
 }  // namespace
-
-#ifdef IFV2_DEBUG_MODES
-extern "C" void infllmv2_debug_mode(int mode) { (void)hipMemcpyToSymbol(HIP_SYMBOL(g_dbg_mode), &mode, sizeof(int)); }
-extern "C" void infllmv2_debug_stats(unsigned long long *out) {
-    unsigned long long z[4] = {0, 0, 0, 0};
-    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dbg_stats), sizeof(z));
-    (void)hipMemcpyToSymbol(HIP_SYMBOL(g_dbg_stats), z, sizeof(z));
-}
-#endif
 
 bool attn_mfma_supported(const infllmv2_params *p) {
     return p->dtype == INFLLMV2_BF16 && p->head_dim == D && p->num_q_heads / p->num_kv_heads == G;
@@ -416,14 +376,11 @@ int launch_attn_mfma(const Launch &L, const void *q, const void *k, const void *
                        a.v, (uint16_t *)ws, L.map, (int)nblk_total);
     int rc = hip_status(hipGetLastError());
     if (rc == INFLLMV2_OK) {
-        static const char *cfg = getenv("INFLLMV2_ATTN_CFG");      // experiment switch
         // Two entries per interval only when block lists exist; the four stages that needs may not fit next to
         // the block masks of very long sequences.
         rc = INFLLMV2_ERR_UNSUPPORTED;
-        if (cfg && !strcmp(cfg, "16x1")) rc = launch_tile<16, 1, 1>(L, a, cu_h);
-        else if (cfg && !strcmp(cfg, "8x2")) rc = launch_tile<8, 2, 1>(L, a, cu_h);
-        else if (idx != nullptr) rc = launch_tile<16, 1, 2>(L, a, cu_h);
-        if (rc == INFLLMV2_ERR_UNSUPPORTED) rc = launch_tile<16, 1, 1>(L, a, cu_h);
+        if (idx != nullptr) rc = launch_tile<16, 2>(L, a, cu_h);
+        if (rc == INFLLMV2_ERR_UNSUPPORTED) rc = launch_tile<16, 1>(L, a, cu_h);
     }
     if (hipFreeAsync(ws, L.stream) != hipSuccess && rc == INFLLMV2_OK) rc = INFLLMV2_ERR_HIP;
     return rc;

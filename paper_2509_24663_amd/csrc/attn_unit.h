@@ -351,17 +351,12 @@ __device__ inline void unit_n(Tok *const (&t)[NT], const uint16_t *stage, const 
     }
 }
 
+// one token against one block; OWN: the block is the token's own, keys past key_limit are masked
 template <bool OWN>
-__device__ inline void unit1(Tok &a, const uint16_t *stage, const LaneOffs2 &lo, int lane, int key_limit) {
+__device__ inline void unit(Tok &a, const uint16_t *stage, const LaneOffs2 &lo, int lane, int key_limit) {
     Tok *const t[1] = {&a};
     const int kl[1] = {key_limit};
     unit_n<1, OWN>(t, stage, lo, lane, kl);
-}
-template <bool OWN>
-__device__ inline void unit2(Tok &a, Tok &b, const uint16_t *stage, const LaneOffs2 &lo, int lane, int kl_a, int kl_b) {
-    Tok *const t[2] = {&a, &b};
-    const int kl[2] = {kl_a, kl_b};
-    unit_n<2, OWN>(t, stage, lo, lane, kl);
 }
 
 }  // namespace attn_unit

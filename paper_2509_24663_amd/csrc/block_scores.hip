@@ -2,9 +2,6 @@
 // Both kernels follow the two-pass scheme of Alg. 1 / Sec. 3.4: pass 1 finds the log-sum-exp of
 // every (token, head) row on chip, pass 2 recomputes the logits, normalises, sums the G heads of
 // the group on chip and stores only the group sum.  Per-head score rows never reach HBM.
-#include <stdlib.h>
-
-#include <stdlib.h>
 
 #include "common.h"
 
@@ -351,7 +348,7 @@ struct ScoreKernel {
         // does the matrix-core step of tile kt and then its vector step, the second does the vector step of tile
         // kt - 1 (still in its accumulators) and then the matrix-core step of tile kt.  Matrix core and vector
         // unit of a SIMD are then busy at the same time although each wave alternates between them.
-        const bool late = false && w >= NW / 2;
+        const bool late = w >= NW / 2;
 
         // ------------------------------------------------ pass 1: log-sum-exp of every (token, head) row
         auto vec1 = [&](int kt) {
@@ -481,7 +478,7 @@ int launch_block_scores(const Launch &L, const void *q, const float *kc, float *
         L.p->num_q_heads / L.p->num_kv_heads == SG && (((uintptr_t)q | (uintptr_t)kc) & 15) == 0) {
         ScoreArgs a{(const uint16_t *)q, kc, s_shared, L.map, L.p->num_q_heads, L.p->cmp_len, L.p->cmp_stride,
                     L.p->dense_threshold, L.p->softmax_scale, row_stride};
-        { static const char *sc = getenv("INFLLMV2_SCORE_CFG"); if (sc && sc[0] == 'a') return launch_scores_mfma<16, 2>(L, a, cu_h); return launch_scores_mfma<8, 4>(L, a, cu_h); }
+        return launch_scores_mfma<8, 4>(L, a, cu_h);
     }
     if (L.p->head_dim == 128)
         return bf ? launch_generic<bf16_t, 128>(L, q, kc, s_shared, row_stride)
