@@ -13,6 +13,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -133,16 +134,17 @@ def main() -> int:
 
     # roofline of the dominant kernel (largest share of the step)
     dom = max(stage_names, key=lambda s: stage_ms[s])
+    traffic = measured_traffic(dom, args.workload)
     if dom in ("sparse_attn_fwd", "block_scores"):
         fl = attn_flops if dom == "sparse_attn_fwd" else score_flops
         ach = fl / (stage_ms[dom] * 1e-3) / 1e12
         roof = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": None}
+                "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": traffic}
     else:
         by = tk_bytes if dom == "topk_blocks" else kbytes
         ach = by / (stage_ms[dom] * 1e-3) / 1e9
         roof = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
+                "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": traffic}
 
     # ------------------------------------------------------------------ the library's own dense path
     dense = None
