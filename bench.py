@@ -30,6 +30,19 @@ def _events(torch, n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
+def measured_traffic(stage: str, workload: str):
+    """HBM bytes per launch of a stage's kernel, as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
+    what the same counters read for a plain copy of known size) and recorded in the committed profile summary.
+    None when the summary has no figure for this stage and workload."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "prefill_c3_decode_c4_rocprofv3.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    mt = re.search(rf"^TRAFFIC {re.escape(stage)} {re.escape(workload)} bytes_per_launch=(\d+)", text, re.M)
+    return int(mt.group(1)) if mt else None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
