@@ -17,9 +17,12 @@
  * General rules
  *   - Every pointer named *_d or documented "device" is GPU memory on the current
  *     HIP device; pointers named *_h are host memory and are only read during the
- *     call.  The library allocates nothing, keeps no state and never synchronises:
- *     all work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
- *     default stream).  The caller owns every buffer and keeps it alive until the
+ *     call.  The library keeps no state and never synchronises: all work is
+ *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream).  The two prefill attention calls obtain a V-sized scratch buffer
+ *     from the device's stream-ordered memory pool (hipMallocAsync / hipFreeAsync
+ *     on `stream`) for bf16 data with 16 query heads per KV head and head_dim 128;
+ *     nothing else is allocated.  The caller owns every buffer and keeps it alive until the
  *     stream work has finished.  Calls are thread-safe.
  *   - All indices are 0-based.  Token t of a sequence lies in block t / block_size.
  *     Sequences are packed along the token axis; cu_seqlens has batch+1 int32
@@ -143,6 +146,7 @@ int infllmv2_topk_blocks(const infllmv2_params *p, const float *s_shared_d, int6
  *                  numbers <= b_t or -1; as produced by infllmv2_topk_blocks)
  *   out_d          device out, dtype [total_tokens, num_q_heads, head_dim]
  *   lse_d          device out float32 [num_q_heads, total_tokens]: ln sum_u exp(scale * <q, k_u>); may be NULL
+ * Returns INFLLMV2_ERR_HIP if the scratch buffer (see the general rules) cannot be obtained.
  */
 int infllmv2_sparse_attn_fwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
                              int64_t kv_tok_stride, int64_t kv_head_stride, const int32_t *block_idx_d,
