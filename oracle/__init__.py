@@ -46,6 +46,8 @@ def _load():
         lib.oracle_compress_k.argtypes = [P, i32, i32, i32, i32, P]
         lib.oracle_block_scores.restype = None
         lib.oracle_block_scores.argtypes = [P, P, i32, i32, i32, P, i32, i32, i32, f64, P, i64]
+        lib.oracle_block_scores_lse_approx.restype = None
+        lib.oracle_block_scores_lse_approx.argtypes = [P, P, i32, i32, i32, P, i32, i32, i32, P, i32, i32, i32, f64, P, i64]
         lib.oracle_topk_blocks.restype = None
         lib.oracle_topk_blocks.argtypes = [P, i64, P, i32, i32, i32, i32, i32, i32, i32, i32, i32, i32, P, P, i64]
         lib.oracle_sparse_attn.restype = None
@@ -83,6 +85,7 @@ class Params:
     topk_total: int = 64        # |I|
     dense_threshold: int = 0    # sequences shorter than this run dense attention
     softmax_scale: float = 128 ** -0.5
+    lse_mode: int = 0           # 1: LSE Approximation (Sec. 3.4): normalise with the log-sum-exp over K^{C2}
 
     @staticmethod
     def from_config(cfg) -> "Params":
@@ -99,23 +102,34 @@ def visible_cmp(t: int, p: Params) -> int:
     return _load().oracle_visible_cmp(int(t), p.cmp_len, p.cmp_stride)
 
 
-def compress_k(K: np.ndarray, p: Params) -> np.ndarray:
-    """Eq. 3.  K [n, d] (one KV head, one sequence) -> K^{C1} [nc, d]."""
+def compress_k(K: np.ndarray, p: Params, level: int = 1) -> np.ndarray:
+    """Eq. 3 (level 1: K^{C1}) or Eq. 7 (level 2: K^{C2}, window and stride four times as long).
+    K [n, d] (one KV head, one sequence) -> [nc, d]."""
     K = _f32(K)
     n, d = K.shape
-    kc = np.zeros((num_cmp(n, p), d), dtype=np.float32)
-    _load().oracle_compress_k(_p(K), n, d, p.cmp_len, p.cmp_stride, _p(kc))
+    lc, sc = (p.cmp_len, p.cmp_stride) if level == 1 else (4 * p.cmp_len, 4 * p.cmp_stride)
+    kc = np.zeros((_load().oracle_num_cmp(int(n), lc, sc), d), dtype=np.float32)
+    _load().oracle_compress_k(_p(K), n, d, lc, sc, _p(kc))
     return kc
 
 
-def block_scores(Q: np.ndarray, pos: np.ndarray, kc: np.ndarray, p: Params) -> np.ndarray:
-    """Eq. 4-5.  Q [rows, G, d], pos [rows], kc [nc, d] -> S^shared [rows, nc]."""
+def block_scores(Q: np.ndarray, pos: np.ndarray, kc: np.ndarray, p: Params, kc2: Optional[np.ndarray] = None) -> np.ndarray:
+    """Eq. 4-5.  Q [rows, G, d], pos [rows], kc [nc, d] -> S^shared [rows, nc].
+    With p.lse_mode == 1 (LSE Approximation, Sec. 3.4) kc2 = K^{C2} [nc2, d] is required."""
     Q, pos, kc = _f32(Q), _i32(pos), _f32(kc)
     nr, G, d = Q.shape
     nc = kc.shape[0]
     out = np.zeros((nr, max(nc, 1)), dtype=np.float32)
-    _load().oracle_block_scores(_p(Q), _p(pos), nr, G, d, _p(kc), nc, p.cmp_len, p.cmp_stride,
-                                float(p.softmax_scale), _p(out), out.shape[1])
+    if p.lse_mode == 0:
+        _load().oracle_block_scores(_p(Q), _p(pos), nr, G, d, _p(kc), nc, p.cmp_len, p.cmp_stride,
+                                    float(p.softmax_scale), _p(out), out.shape[1])
+    else:
+        if kc2 is None:
+            raise ValueError("lse_mode 1 needs K^{C2}")
+        kc2 = _f32(kc2)
+        _load().oracle_block_scores_lse_approx(_p(Q), _p(pos), nr, G, d, _p(kc), nc, p.cmp_len, p.cmp_stride,
+                                               _p(kc2), kc2.shape[0], 4 * p.cmp_len, 4 * p.cmp_stride,
+                                               float(p.softmax_scale), _p(out), out.shape[1])
     return out[:, :nc]
 
 
@@ -167,7 +181,7 @@ def dense_attn(Q, pos, K, V, p: Params):
 def select_blocks(Qh, pos, Kh, p: Params, return_scores: bool = False):
     """Stages 1-3 for one KV head of one sequence: Q rows [rows, G, d], K [n, d] -> idx."""
     kc = compress_k(Kh, p)
-    sh = block_scores(Qh, pos, kc, p)
+    sh = block_scores(Qh, pos, kc, p, kc2=compress_k(Kh, p, level=2) if p.lse_mode == 1 else None)
     idx = topk_blocks(sh, pos, p)
     return (idx, sh, kc) if return_scores else idx
 

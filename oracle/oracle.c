@@ -24,7 +24,11 @@
  *     ends at or before t;
  *   - rows with no visible compressed key have all-zero scores;
  *   - the top-k budget is min(N_topk, #remaining blocks), ties go to the
- *     smaller block index.
+ *     smaller block index;
+ *   - LSE Approximation (Sec. 3.4, Eq. 7, Alg. 1): the first pass of Alg. 1 runs
+ *     over K^{C2} (window 4 l_C1, stride 4 s_C1, same visibility rule) and its
+ *     log-sum-exp is used as printed, with no correction for the 4x smaller key
+ *     count; a row that sees no K^{C2} key has all-zero scores.
  *
  * Parity pins (tests/test_oracle_*.py): closed forms for the mean pooling,
  * softmax rows summing to G, brute-force masked dense attention, sparse == dense
@@ -97,6 +101,53 @@ void oracle_block_scores(const float *Q, const int32_t *pos, int nr, int G, int 
         }
         free(z);
         free(acc);
+    }
+}
+
+/* Stage 2 with LSE Approximation, Sec. 3.4 Eq. 7 and Alg. 1: the log-sum-exp of every (row, head) is taken
+ * over the coarse keys kc2 (first pass), the fine scores exp(z_i - lse) over kc (second pass) are summed
+ * over the G heads.   kc [nc][d] with (lc, sc), kc2 [nc2][d] with (lc2, sc2). */
+void oracle_block_scores_lse_approx(const float *Q, const int32_t *pos, int nr, int G, int d, const float *kc,
+                                    int nc, int lc, int sc, const float *kc2, int nc2, int lc2, int sc2,
+                                    double scale, float *shared, int64_t row_stride) {
+#pragma omp parallel
+    {
+        double *acc = (double *)malloc(sizeof(double) * (size_t)(nc > 0 ? nc : 1));
+        double *z2 = (double *)malloc(sizeof(double) * (size_t)(nc2 > 0 ? nc2 : 1));
+#pragma omp for schedule(dynamic, 16)
+        for (int r = 0; r < nr; ++r) {
+            int v = visible_cmp(pos[r], lc, sc);
+            int v2 = visible_cmp(pos[r], lc2, sc2);
+            if (v > nc) v = nc;
+            if (v2 > nc2) v2 = nc2;
+            float *out = shared + (size_t)r * row_stride;
+            for (int i = 0; i < nc; ++i) out[i] = 0.0f;
+            if (v == 0 || v2 == 0) continue;
+            for (int i = 0; i < v; ++i) acc[i] = 0.0;
+            for (int g = 0; g < G; ++g) {
+                const float *q = Q + ((size_t)r * G + g) * d;
+                /* first pass: lse over the coarse keys */
+                double zmax = -INFINITY;
+                for (int i = 0; i < v2; ++i) {
+                    double dot = 0.0;
+                    for (int c = 0; c < d; ++c) dot += (double)q[c] * (double)kc2[(size_t)i * d + c];
+                    z2[i] = scale * dot;
+                    if (z2[i] > zmax) zmax = z2[i];
+                }
+                double den = 0.0;
+                for (int i = 0; i < v2; ++i) den += exp(z2[i] - zmax);
+                double lse = zmax + log(den);
+                /* second pass: fine scores normalised with it */
+                for (int i = 0; i < v; ++i) {
+                    double dot = 0.0;
+                    for (int c = 0; c < d; ++c) dot += (double)q[c] * (double)kc[(size_t)i * d + c];
+                    acc[i] += exp(scale * dot - lse);
+                }
+            }
+            for (int i = 0; i < v; ++i) out[i] = (float)acc[i];
+        }
+        free(acc);
+        free(z2);
     }
 }
 

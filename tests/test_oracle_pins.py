@@ -112,6 +112,91 @@ def test_scores_match_library_softmax(oracle):
         np.testing.assert_allclose(sh[r, :v], prob.numpy(), rtol=2e-6, atol=1e-8)
 
 
+# ----------------------------------------------------------------------------- LSE Approximation (Sec. 3.4, Eq. 7)
+def _vis2(t):
+    return _vis(t, 128, 64)
+
+
+def test_lse_approx_coarse_keys_are_means_of_four_fine_windows(oracle):
+    """K^{C2}_i = mean of 128 keys from 64 i = mean of the four disjoint 32-key windows it consists of,
+    i.e. of K^{C1} rows 4i, 4i+2, 4i+4, 4i+6 (the kernels derive K^{C2} that way)."""
+    p = oracle.Params(lse_mode=1)
+    w = _small(n=700)
+    K = w["k"][0]
+    kc, kc2 = oracle.compress_k(K, p), oracle.compress_k(K, p, level=2)
+    assert kc2.shape[0] == (700 - 128) // 64 + 1
+    kt = torch.from_numpy(K).double().unfold(0, 128, 64).mean(-1).numpy()
+    np.testing.assert_allclose(kc2, kt, atol=1e-6)
+    i = np.arange(kc2.shape[0])
+    np.testing.assert_allclose(kc2, (kc[4 * i] + kc[4 * i + 2] + kc[4 * i + 4] + kc[4 * i + 6]) / 4, atol=1e-6)
+
+
+def test_lse_approx_constant_keys_closed_form(oracle):
+    """With identical keys every logit of a head is the same number, so exp(z - lse_C2) = 1 / v2(t):
+    S^shared[t, i] = G / v2(t) for every visible fine key, and 0 for rows that see no coarse key."""
+    p = oracle.Params(lse_mode=1, softmax_scale=0.3)
+    rng = np.random.default_rng(1)
+    K = np.tile(rng.standard_normal((1, 16)).astype(np.float32), (600, 1))
+    Q = rng.standard_normal((600, 3, 16)).astype(np.float32)
+    pos = np.arange(600, dtype=np.int32)
+    sh = oracle.block_scores(Q, pos, oracle.compress_k(K, p), p, oracle.compress_k(K, p, level=2))
+    for t in (0, 31, 126, 127, 190, 191, 599):
+        v, v2 = _vis(t), _vis2(t)
+        if v2 == 0:
+            assert np.all(sh[t] == 0)
+        else:
+            np.testing.assert_allclose(sh[t, :v], 3.0 / v2, rtol=1e-5)
+            assert np.all(sh[t, v:] == 0)
+
+
+def test_lse_approx_against_plain_loops(oracle):
+    """Eq. 7 and Alg. 1 written out with Python loops from the raw keys on a tiny case."""
+    p = oracle.Params(lse_mode=1, softmax_scale=0.5)
+    rng = np.random.default_rng(2)
+    n, G, d = 330, 2, 4
+    K = rng.standard_normal((n, d))
+    Q = rng.standard_normal((n, G, d))
+    Kf, Qf = K.astype(np.float32), Q.astype(np.float32)
+    pos = np.array([100, 127, 200, 329], dtype=np.int32)
+    sh = oracle.block_scores(Qf[pos], pos, oracle.compress_k(Kf, p), p, oracle.compress_k(Kf, p, level=2))
+    K64, Q64 = Kf.astype(np.float64), Qf.astype(np.float64)
+    for r, t in enumerate(pos):
+        fine = [K64[16 * i:16 * i + 32].mean(0) for i in range(n) if 16 * i + 31 <= t]
+        coarse = [K64[64 * i:64 * i + 128].mean(0) for i in range(n) if 64 * i + 127 <= t]
+        want = np.zeros(len(fine))
+        if coarse:
+            for g in range(G):
+                lse = math.log(sum(math.exp(0.5 * float(Q64[t, g] @ c)) for c in coarse))
+                want += np.array([math.exp(0.5 * float(Q64[t, g] @ f) - lse) for f in fine])
+        np.testing.assert_allclose(sh[r, :len(fine)], want, rtol=2e-6, atol=1e-9)
+        assert np.all(sh[r, len(fine):] == 0)
+
+
+def test_lse_approx_rescales_each_head_of_the_exact_scores(oracle):
+    """Per head the approximation multiplies the exact softmax row by exp(lse_C1 - lse_C2): with G = 1 the
+    ranking of the keys, and therefore the selection, is the exact one."""
+    w = _small(n=900, hq=4, hkv=2, d=16, seed=11)
+    pe = oracle.Params(n_init=1, n_local=2, topk_total=6, softmax_scale=0.4)
+    pa = oracle.Params(n_init=1, n_local=2, topk_total=6, softmax_scale=0.4, lse_mode=1)
+    pos = np.arange(127, 900, dtype=np.int32)
+    K = w["k"][0]
+    kc, kc2 = oracle.compress_k(K, pe), oracle.compress_k(K, pa, level=2)
+    Q1 = w["q"][pos, :1]
+    se = oracle.block_scores(Q1, pos, kc, pe).astype(np.float64)
+    sa = oracle.block_scores(Q1, pos, kc, pa, kc2).astype(np.float64)
+    ratio = sa[:, :1] / se[:, :1]
+    np.testing.assert_allclose(sa, se * ratio, rtol=2e-5, atol=1e-12)
+    # the factor is exp(lse_C1 - lse_C2), computed here with torch from the logits
+    for r in (0, 300, len(pos) - 1):
+        t = int(pos[r])
+        q = torch.from_numpy(Q1[r, 0]).double()
+        l1 = torch.logsumexp(0.4 * torch.from_numpy(kc[:_vis(t)]).double() @ q, 0)
+        l2 = torch.logsumexp(0.4 * torch.from_numpy(kc2[:_vis2(t)]).double() @ q, 0)
+        np.testing.assert_allclose(ratio[r, 0], math.exp(float(l1 - l2)), rtol=1e-5)
+    np.testing.assert_array_equal(oracle.topk_blocks(sa.astype(np.float32), pos, pa),
+                                  oracle.topk_blocks(se.astype(np.float32), pos, pe))
+
+
 # ----------------------------------------------------------------------------- stage 3 (Eq. 2, 6)
 def test_pool_topk_hand_worked_fixture(oracle):
     g, _ = _read_gold("pool_topk_case.txt")
