@@ -4,7 +4,8 @@
  *
  * The path has four stages (Sec. 3.2-3.4 of the paper):
  *   1. infllmv2_compress_k      mean-pool keys into compressed keys K^{C1}            (Eq. 3)
- *   2. infllmv2_block_scores    softmax(scale * Q K^{C1 T}) summed over the GQA group (Eq. 4, 5, Alg. 1)
+ *   2. infllmv2_block_scores    softmax(scale * Q K^{C1 T}) summed over the GQA group (Eq. 4, 5, Alg. 1;
+ *                               optionally with the LSE Approximation of Sec. 3.4)
  *   3. infllmv2_topk_blocks     max-pool to selection blocks, keep init + local,
  *                               top-k of the rest                                     (Eq. 6, Eq. 2)
  *   4. infllmv2_sparse_attn_fwd causal attention over the selected 64-token blocks of
@@ -82,7 +83,11 @@ typedef struct infllmv2_params {
     int32_t topk_total;       /* |I|       [96]; n_init + n_local <= topk_total <= 1024                    */
     int32_t dense_threshold;  /* sequences with fewer tokens than this run dense attention                 */
     float   softmax_scale;    /* multiplies the logits in stage 2 and in attention; 1/sqrt(d_h)            */
-    int32_t lse_mode;         /* 0: exact two-pass normalisation of stage 2 (the only mode implemented)    */
+    int32_t lse_mode;         /* stage 2 normalisation.  0: exact, both passes of Alg. 1 over K^{C1}.
+                               * 1: LSE Approximation (Sec. 3.4, Eq. 7): the log-sum-exp of pass 1 is taken
+                               *    over K^{C2} (window 4 l_C1, stride 4 s_C1, formed inside the library from
+                               *    K^{C1}; needs l_C1 % s_C1 == 0, else UNSUPPORTED) and used as it is; a row
+                               *    that sees no K^{C2} key gets all-zero scores.                              */
 } infllmv2_params;
 
 /* Number of compressed keys of a sequence of n tokens: complete windows only,

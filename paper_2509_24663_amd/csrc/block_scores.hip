@@ -2,6 +2,11 @@
 // Both kernels follow the two-pass scheme of Alg. 1 / Sec. 3.4: pass 1 finds the log-sum-exp of
 // every (token, head) row on chip, pass 2 recomputes the logits, normalises, sums the G heads of
 // the group on chip and stores only the group sum.  Per-head score rows never reach HBM.
+//
+// LSE Approximation (Sec. 3.4, Eq. 7; lse_mode 1): pass 1 runs over the four times coarser keys K^{C2}
+// instead.  K^{C2}_i is the mean of 4 l_C1 keys starting at 4 s_C1 i, i.e. (when s_C1 divides l_C1) the mean of
+// the four disjoint K^{C1} windows 4i + m l_C1 / s_C1, m = 0..3, so it is formed on the fly from K^{C1} and
+// needs no input of its own.  A row that sees no coarse key gets all-zero scores.
 
 #include "common.h"
 
@@ -14,12 +19,20 @@ namespace ifv2 {
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
 block_scores_generic(const T *__restrict__ q, const float *__restrict__ kc, RowMap map, int hq, int lc, int sc,
-                     float scale, int dense_below, float *__restrict__ s_shared, int64_t row_stride) {
+                     float scale, int dense_below, int lse_mode, float *__restrict__ s_shared, int64_t row_stride) {
     const int row = blockIdx.x, h = blockIdx.y;
     const int G = hq / map.num_kv_heads;
     const RowLoc loc = locate(map, row);
     const int v = visible_cmp(loc.pos, lc, sc);
     if (v == 0 || loc.len < dense_below) return;      // dense sequences need no scores
+    // pass 1 runs over v1 keys: the fine ones, or the coarse ones made of `cstep`-spaced groups of four
+    const int cstep = lc / sc;
+    const int v1 = lse_mode == 0 ? v : min(visible_cmp(loc.pos, 4 * lc, 4 * sc), num_cmp(loc.len, 4 * lc, 4 * sc));
+    if (v1 == 0) {                                    // no coarse key visible yet: all-zero scores
+        float *out0 = s_shared + head_row(map, h, row) * row_stride;
+        for (int i = threadIdx.x; i < v; i += 256) out0[i] = 0.f;
+        return;
+    }
     __shared__ float qs[kMaxGroup][D];
     __shared__ float red_m[4][kMaxGroup], red_l[4][kMaxGroup];
     __shared__ float lse_s[kMaxGroup];
@@ -34,13 +47,22 @@ block_scores_generic(const T *__restrict__ q, const float *__restrict__ kc, RowM
 #pragma unroll
     for (int g = 0; g < kMaxGroup; ++g) { m[g] = -INFINITY; l[g] = 0.f; }
     // pass 1: running (max, sum exp) per head, private to the thread
-    for (int i = tid; i < v; i += 256) {
+    for (int i = tid; i < v1; i += 256) {
         float z[kMaxGroup];
 #pragma unroll
         for (int g = 0; g < kMaxGroup; ++g) z[g] = 0.f;
-        const float *kr = kcb + (int64_t)i * D;
+        const float *kr = kcb + (int64_t)(lse_mode == 0 ? i : 4 * i) * D;
         for (int c = 0; c < D; c += 4) {
             float4 kv = *reinterpret_cast<const float4 *>(kr + c);
+            if (lse_mode != 0) {
+                const float4 k1 = *reinterpret_cast<const float4 *>(kr + (int64_t)cstep * D + c);
+                const float4 k2 = *reinterpret_cast<const float4 *>(kr + (int64_t)2 * cstep * D + c);
+                const float4 k3 = *reinterpret_cast<const float4 *>(kr + (int64_t)3 * cstep * D + c);
+                kv.x = ((kv.x + k1.x) + (k2.x + k3.x)) * 0.25f;
+                kv.y = ((kv.y + k1.y) + (k2.y + k3.y)) * 0.25f;
+                kv.z = ((kv.z + k1.z) + (k2.z + k3.z)) * 0.25f;
+                kv.w = ((kv.w + k1.w) + (k2.w + k3.w)) * 0.25f;
+            }
 #pragma unroll
             for (int g = 0; g < kMaxGroup; ++g)
                 z[g] += qs[g][c] * kv.x + qs[g][c + 1] * kv.y + qs[g][c + 2] * kv.z + qs[g][c + 3] * kv.w;
@@ -96,7 +118,7 @@ static int launch_generic(const Launch &L, const void *q, const float *kc, float
     if (grid.x == 0) return INFLLMV2_OK;
     hipLaunchKernelGGL((block_scores_generic<T, D>), grid, dim3(256), 0, L.stream, (const T *)q, kc, L.map,
                        L.p->num_q_heads, L.p->cmp_len, L.p->cmp_stride, L.p->softmax_scale, L.p->dense_threshold,
-                       s_shared, row_stride);
+                       L.p->lse_mode, s_shared, row_stride);
     return hip_status(hipGetLastError());
 }
 
@@ -145,7 +167,7 @@ struct ScoreArgs {
     const float *kc;
     float *out;
     RowMap map;
-    int hq, lc, sc, dense_below;
+    int hq, lc, sc, dense_below, lse_mode;
     float scale;
     int64_t row_stride;
 };
@@ -165,6 +187,28 @@ struct ScoreKernel {
             const int row = kt * kBlock + (c >> 5), col = (c & 31) * 4;
             pf[r] = row < nc ? *reinterpret_cast<const float4 *>(kcb + (int64_t)row * SD + col)
                              : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    // the same for a tile of coarse keys (Eq. 7): row i = mean of K^{C1} rows 4i, 4i + cstep, .. + 3 cstep
+    __device__ static inline void load_tile_coarse(const float *kcb, int kt, int nc2, int cstep, int tid,
+                                                   float4 (&pf)[NCH]) {
+#pragma unroll
+        for (int r = 0; r < NCH; ++r) {
+            const int c = tid + r * NTHR;
+            const int row = kt * kBlock + (c >> 5), col = (c & 31) * 4;
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < nc2) {
+                const float *b = kcb + (int64_t)4 * row * SD + col;
+                const float4 k0 = *reinterpret_cast<const float4 *>(b);
+                const float4 k1 = *reinterpret_cast<const float4 *>(b + (int64_t)cstep * SD);
+                const float4 k2 = *reinterpret_cast<const float4 *>(b + (int64_t)2 * cstep * SD);
+                const float4 k3 = *reinterpret_cast<const float4 *>(b + (int64_t)3 * cstep * SD);
+                x.x = ((k0.x + k1.x) + (k2.x + k3.x)) * 0.25f;
+                x.y = ((k0.y + k1.y) + (k2.y + k3.y)) * 0.25f;
+                x.z = ((k0.z + k1.z) + (k2.z + k3.z)) * 0.25f;
+                x.w = ((k0.w + k1.w) + (k2.w + k3.w)) * 0.25f;
+            }
+            pf[r] = x;
         }
     }
     // fp32 -> fp16 (x * cm * 2^e) into the tile; returns true if some scaled magnitude is not fp16-safe
@@ -277,6 +321,10 @@ struct ScoreKernel {
         const float cm = frexpf(a.scale * S_LOG2E, &ce);
         half8 qf[TPW][4];
         int vis[TPW];
+        // keys of pass 1: the fine ones, or with the LSE Approximation the coarse ones (Eq. 7)
+        const int nc2 = num_cmp(len, 4 * a.lc, 4 * a.sc), cstep = a.lc / a.sc;
+        int vis1[TPW];
+        int vis1_min = 1 << 30;
         float cq[TPW];                   // 2^(ce - token's exponent): multiplies the accumulator (normally 1)
         bool q_plain = true;
         int vis_min = 1 << 30;
@@ -285,6 +333,8 @@ struct ScoreKernel {
             const int ti = w * TPW + i;
             vis[i] = ti < ntok ? min(visible_cmp(t0 + ti, a.lc, a.sc), nc) : 0;
             vis_min = min(vis_min, vis[i]);
+            vis1[i] = a.lse_mode == 0 ? vis[i] : (ti < ntok ? min(visible_cmp(t0 + ti, 4 * a.lc, 4 * a.sc), nc2) : 0);
+            vis1_min = min(vis1_min, vis1[i]);
             const uint16_t *qp = a.q + ((int64_t)(row0 + ti) * a.hq + h * SG + n16) * SD + g * 8;
             float x[4][8];
             float amax = 0.f;
@@ -353,13 +403,13 @@ struct ScoreKernel {
         // ------------------------------------------------ pass 1: log-sum-exp of every (token, head) row
         auto vec1 = [&](int kt) {
             const int kbase = kt * kBlock;
-            const bool edge_tile = kbase + kBlock > vis_min;
+            const bool edge_tile = kbase + kBlock > vis1_min;
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
                 if (edge_tile) {
 #pragma unroll
                     for (int nt = 0; nt < 4; ++nt)
-                        if (kbase + nt * 16 + n16 >= vis[i]) acc[i][nt] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+                        if (kbase + nt * 16 + n16 >= vis1[i]) acc[i][nt] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
                 }
                 // The reference moves only when an exponent exceeds S_SLACK; the first tile sets it (up or down).
                 float mx[4];
@@ -386,17 +436,25 @@ struct ScoreKernel {
                 }
             }
         };
-        load_tile(kcb, 0, nc, tid, pf);
-        stage_tile(smem, tid, pf, &s_flag, &s_shift[0], cm, ke);
-        for (int kt = 0; kt < nkt; ++kt) {
-            if (kt + 1 < nkt) load_tile(kcb, kt + 1, nc, tid, pf);
+        const int vis1_last = a.lse_mode == 0 ? vis_last : min(visible_cmp(t0 + ntok - 1, 4 * a.lc, 4 * a.sc), nc2);
+        const int nkt1 = (vis1_last + kBlock - 1) / kBlock;
+        auto load1 = [&](int kt) {
+            if (a.lse_mode == 0) load_tile(kcb, kt, nc, tid, pf);
+            else load_tile_coarse(kcb, kt, nc2, cstep, tid, pf);
+        };
+        if (nkt1 > 0) {
+            load1(0);
+            stage_tile(smem, tid, pf, &s_flag, &s_shift[0], cm, ke);
+        }
+        for (int kt = 0; kt < nkt1; ++kt) {
+            if (kt + 1 < nkt1) load1(kt + 1);
             if (late && kt > 0) vec1(kt - 1);
             mma(kt, nm);
             if (!late) vec1(kt);
-            if (kt + 1 < nkt) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf, &s_flag, &s_shift[(kt + 1) & 1], cm, ke);
+            if (kt + 1 < nkt1) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf, &s_flag, &s_shift[(kt + 1) & 1], cm, ke);
             else __syncthreads();
         }
-        if (late) vec1(nkt - 1);
+        if (late && nkt1 > 0) vec1(nkt1 - 1);
         // merge the 16 key lanes of each lane group; lse2 = log2 of the row's sum of 2^y
         float lse2[TPW][4];
 #pragma unroll
@@ -411,7 +469,9 @@ struct ScoreKernel {
                     ll = ll * s_exp2(mm - mn) + lo * s_exp2(mo - mn);
                     mm = mn;
                 }
-                lse2[i][r] = mm + __log2f(ll);
+                // a row that saw no key at all (possible with the coarse keys of the LSE Approximation while
+                // fine keys are already visible) normalises everything to zero
+                lse2[i][r] = ll > 0.f ? mm + __log2f(ll) : INFINITY;
             }
 
         // ------------------------------------------------ pass 2: normalised scores, group sum, store
@@ -477,7 +537,7 @@ int launch_block_scores(const Launch &L, const void *q, const float *kc, float *
     if (bf && cu_h != nullptr && L.map.ctx == nullptr && L.p->head_dim == SD &&
         L.p->num_q_heads / L.p->num_kv_heads == SG && (((uintptr_t)q | (uintptr_t)kc) & 15) == 0) {
         ScoreArgs a{(const uint16_t *)q, kc, s_shared, L.map, L.p->num_q_heads, L.p->cmp_len, L.p->cmp_stride,
-                    L.p->dense_threshold, L.p->softmax_scale, row_stride};
+                    L.p->dense_threshold, L.p->lse_mode, L.p->softmax_scale, row_stride};
         return launch_scores_mfma<8, 4>(L, a, cu_h);
     }
     if (L.p->head_dim == 128)

@@ -67,7 +67,7 @@ def test_validation_errors_before_launch(m):
         assert _call_compress(m, p, [0, 64]) == want
     for over, want in [(dict(n_local=0), INVALID), (dict(n_init=60, n_local=8, topk_total=64), INVALID),
                        (dict(block_size=128), UNSUPPORTED), (dict(cmp_stride=0), INVALID),
-                       (dict(cmp_len=8, cmp_stride=16), INVALID), (dict(lse_mode=1), UNSUPPORTED),
+                       (dict(cmp_len=8, cmp_stride=16), INVALID), (dict(lse_mode=2), INVALID), (dict(lse_mode=1, cmp_len=24), UNSUPPORTED),
                        (dict(softmax_scale=0.0), INVALID), (dict(topk_total=2048), UNSUPPORTED)]:
         p = m.Params.make("bf16", 32, 2, 128, **over)
         assert _call_compress(m, p, [0, 64]) == want, over

@@ -26,7 +26,7 @@ def _params(m, oracle, dtype, hq, hkv, d, **kw):
     op = oracle.Params(block_size=gp.block_size, cmp_len=gp.cmp_len, cmp_stride=gp.cmp_stride, pool_len=gp.pool_len,
                        pool_stride=gp.pool_stride, pool_pad=gp.pool_pad, n_init=gp.n_init, n_local=gp.n_local,
                        topk_total=gp.topk_total, dense_threshold=gp.dense_threshold,
-                       softmax_scale=float(gp.softmax_scale))
+                       softmax_scale=float(gp.softmax_scale), lse_mode=gp.lse_mode)
     return gp, op
 
 
@@ -71,7 +71,8 @@ def _run_prefill_case(m, oracle, w, gp, op, dtype, rows=None, check_stages=True)
                 if check_stages:
                     np.testing.assert_allclose(kc_g[h, cu_c[s]:cu_c[s] + nc], kc_o, rtol=0,
                                                atol=2e-6 * max(1.0, float(np.abs(kc_o).max()) if nc else 1.0))
-                sh_o = oracle.block_scores(Qh, pos, kc_o, op)
+                sh_o = oracle.block_scores(Qh, pos, kc_o, op,
+                                           kc2=oracle.compress_k(Kh, op, level=2) if op.lse_mode else None)
                 idx_o, cmp_o = oracle.topk_blocks(sh_o, pos, op, return_cmp=True)
                 if check_stages:
                     shg_rows = np.zeros_like(sh_o)
@@ -146,6 +147,35 @@ def test_scores_survive_large_magnitudes(m, oracle, qexp, kexp):
     gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=4, topk_total=12,
                      softmax_scale=128 ** -0.5 * 2.0 ** (-qexp - kexp))
     _run_prefill_case(m, oracle, w, gp, op, "bf16")
+
+
+@pytest.mark.parametrize("shape", [("bf16", 32, 2, 128, 2300), ("bf16", 32, 2, 128, 200), ("fp32", 4, 1, 64, 1500),
+                                   ("bf16", 8, 2, 64, 700)])
+def test_lse_approximation_prefill(m, oracle, shape):
+    """Stage 2 with the LSE Approximation (Sec. 3.4, Eq. 7; lse_mode 1) against the oracle's variant, through the
+    whole path: MFMA kernel (bf16, G 16, d 128) and generic kernel (other shapes); rows below token 127 see no
+    coarse key and must get all-zero scores."""
+    dtype, hq, hkv, d, n = shape
+    w = synth.make_prefill(n, hq, hkv, d, seed=77, dtype=dtype)
+    gp, op = _params(m, oracle, dtype, hq, hkv, d, n_init=1, n_local=2, topk_total=10, lse_mode=1)
+    assert op.lse_mode == 1
+    _run_prefill_case(m, oracle, w, gp, op, dtype)
+    res = m.sparse_prefill(gp, *(to_dev(w[x], dtype) for x in ("q", "k", "v")), w["cu_seqlens"])
+    sh = to_np(res["s_shared"])
+    for t in range(31, min(n, 127)):
+        assert np.all(sh[:, t, :oracle.visible_cmp(t, op)] == 0)
+
+
+def test_lse_approximation_varlen_and_decode(m, oracle):
+    """lse_mode 1 on packed sequences of different lengths (each has its own coarse-key count), and in the decode
+    entry point, which must give the last prefill row."""
+    lengths = (90, 128, 191, 1000, 2049)
+    w = synth.make_varlen(lengths, 32, 2, 128, seed=5, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=3, topk_total=9, lse_mode=1)
+    _run_prefill_case(m, oracle, w, gp, op, "bf16")
+    ctx = [300, 1500, 127, 64]
+    dw = synth.make_decode(ctx, 32, 2, 128, seed=6, dtype="bf16")
+    _check_decode(m, oracle, dw, ctx, gp, op, "bf16")
 
 
 @pytest.mark.parametrize("cfg", [(1, 1, 4), (2, 3, 9), (0, 1, 3), (1, 8, 64)])
@@ -278,7 +308,8 @@ def _check_decode(m, oracle, w, ctx, gp, op, dtype):
                 O, Ls = oracle.dense_attn(Qh, pos, Kh, Vh, op)
             else:
                 n_sparse += 1
-                sh = oracle.block_scores(Qh, pos, oracle.compress_k(Kh, op), op)
+                sh = oracle.block_scores(Qh, pos, oracle.compress_k(Kh, op), op,
+                                         kc2=oracle.compress_k(Kh, op, level=2) if op.lse_mode else None)
                 io, co = oracle.topk_blocks(sh, pos, op, return_cmp=True)
                 check_selection(idx[b, h][None], io, co, pos, op.n_init, op.n_local)
                 O, Ls = oracle.sparse_attn(Qh, pos, Kh, Vh, idx[b, h][None], op)
