@@ -42,6 +42,19 @@ def test_c2_32k_sampled(m, oracle):
     assert st["rows"] >= 700
 
 
+def test_c2_32k_sampled_lse_approximation(m, oracle):
+    """The same workload with the LSE Approximation of Sec. 3.4 (lse_mode 1) in stage 2."""
+    import dataclasses
+    cfg = synth.CONFIGS["C2"]
+    w = synth.make_config(cfg)
+    rows = _sample_rows(w["cu_seqlens"], np.random.default_rng(12), 4, 192)
+    gp = m.Params.from_config(cfg, lse_mode=1)
+    op = dataclasses.replace(oracle.Params.from_config(cfg), lse_mode=1)
+    st = _run_prefill_case(m, oracle, w, gp, op, "bf16", rows=rows)
+    print("C2 lse_mode 1", st)
+    assert st["rows"] >= 400
+
+
 def test_c3_128k_sampled_sparse_and_dense(m, oracle):
     cfg = synth.CONFIGS["C3"]
     w = synth.make_config(cfg)
