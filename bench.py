@@ -53,6 +53,9 @@ def main() -> int:
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=6144, help="query rows per KV head the oracle is timed on")
+    ap.add_argument("--paper-sweep", action="store_true",
+                    help="instead of the default line: the paper's own benchmark shapes (Sec. 4.3: 16 selected blocks "
+                         "at 32k..128k, and |I| = 96 at 128k), one JSON object")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, to scale PMC byte counters)")
     args = ap.parse_args()
@@ -68,6 +71,9 @@ def main() -> int:
     m.lib()     # fails loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.paper_sweep:
+        print(json.dumps(paper_sweep(torch, m, synth, args.steps)))
+        return 0
     cfg = synth.CONFIGS[args.workload]
     gp = m.Params.from_config(cfg)
     n, hq, hkv, d = cfg.seq_len, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim
@@ -243,6 +249,50 @@ def main() -> int:
     }
     print(json.dumps(line))
     return 0
+
+
+def paper_sweep(torch, m, synth, steps: int):
+    """The shapes of the paper's kernel benchmark (Sec. 4.3, Table "ablation_lse"): batch 1, 32 query / 2 KV heads,
+    d 128, 16 selected blocks (read here as 1 initial + 8 local + 7 top-k), sequence 32k..128k; block selection =
+    stages 1-3, with and without the LSE Approximation.  Then the paper's model setting |I| = 96 = 1 + 32 + 63
+    (Sec. 4.1) at 128k.  Synthetic inputs, same recipe as the other workloads."""
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        ev = _events(torch, 2)
+        ev[0].record()
+        for _ in range(steps):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / steps
+
+    def run(n, n_init, n_local, total, seed):
+        w = synth.make_prefill(n, 32, 2, 128, seed=seed, dtype="bf16")
+        q, k, v = (torch.from_numpy(w[x]).to(torch.bfloat16).cuda() for x in ("q", "k", "v"))
+        si = m.SeqInfo([0, n])
+        row = {"seq_len": n, "blocks": total}
+        for mode in (0, 1):
+            gp = m.Params.make("bf16", 32, 2, 128, n_init=n_init, n_local=n_local, topk_total=total, lse_mode=mode)
+            bufs = m.sparse_prefill(gp, q, k, v, si)
+            t1 = timed(lambda: m.compress_k(gp, k, si, out=(bufs["kc"], bufs["cu_seqlens_c"])))
+            t2 = timed(lambda: m.block_scores(gp, q, bufs["kc"], si, bufs["cu_seqlens_c"], out=bufs["s_shared"]))
+            t3 = timed(lambda: m.topk_blocks(gp, bufs["s_shared"], si, out=bufs["block_idx"]))
+            t4 = timed(lambda: m.sparse_attn_fwd(gp, q, k, v, bufs["block_idx"], si, out=bufs["out"], lse=bufs["lse"]))
+            key = "exact" if mode == 0 else "lse_approx"
+            row[key] = {"block_selection_ms": round(t1 + t2 + t3, 3), "sparse_attn_ms": round(t4, 3)}
+            if mode == 0:
+                td = timed(lambda: m.dense_attn_fwd(gp, q, k, v, si, out=bufs["out"], lse=bufs["lse"]))
+                row["dense_attn_ms"] = round(td, 3)
+                row["speedup_attn_only"] = round(td / t4, 2)
+                row["speedup_with_selection"] = round(td / (t1 + t2 + t3 + t4), 2)
+            del bufs
+        return row
+
+    res = {"what": "paper-native shapes on one MI355X, bf16, synthetic inputs; ms per layer",
+           "sixteen_blocks": [run(n, 1, 8, 16, 900 + i) for i, n in enumerate((32768, 65536, 98304, 131072))],
+           "ninety_six_blocks_128k": run(131072, 1, 32, 96, 950)}
+    return res
 
 
 def bench_decode(torch, m, synth, iters: int = 40, nsets: int = 4):
