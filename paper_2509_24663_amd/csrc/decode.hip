@@ -6,9 +6,11 @@
 // way to make one workgroup's results visible to another on a multi-die GPU):
 //   scores  : grid (key chunks, pairs)  logits of 128 compressed keys x 16 heads per workgroup, written once
 //             as log2-domain logits, plus per-chunk (max, sum) partials of the softmax normaliser
-//   group sum: grid (key chunks, pairs) merge the partials into the normaliser, sum the normalised scores of
-//             the 16 heads for 128 keys
-//   top-k   : the prefill stage-3 kernel on the one row per pair
+//   select  : grid (pairs)              one 1024-thread workgroup per pair merges the partials into the normaliser,
+//             sums the normalised scores of the 16 heads (Eq. 5) into LDS, max-pools them to blocks (Eq. 6) and
+//             selects (Eq. 2) with a workgroup-wide radix select: a single wavefront per row, as in prefill, would
+//             leave the chip empty and spend ~16 us on latency here.  Contexts whose score row does not fit in
+//             LDS use the separate group-sum kernel and the prefill stage-3 kernel instead.
 //   attend  : grid (splits, pairs)      one wavefront per selected block: K fragments straight from global
 //             memory into MFMA operands, V through a 16 KB LDS tile (MFMA unit shared with prefill); the
 //             eight partial results of a workgroup are merged in LDS
@@ -176,6 +178,175 @@ __global__ void __launch_bounds__(256) dec_gsum_kernel(DecArgs a) {
     if (hh == 1) half_sum[tid & 127] = sum;
     __syncthreads();
     if (hh == 0 && key < v) a.sh[(int64_t)pair * a.zs + key] = sum + half_sum[tid];
+}
+
+// ------------------------------------------------------------------------------------------ select
+// Stages 2b-3 for one (sequence, KV head) pair in one workgroup.  Selection rule and tie handling are those of
+// topk_row: keys above the k-th largest, then the first `need` keys equal to it in ascending block order.
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_WAVES = SEL_THREADS / 64;
+
+// exclusive prefix count of `flag` over the workgroup's threads in thread order (+ total); two barriers
+__device__ inline int wg_prefix_count(bool flag, int *wave_tot, int tid, int &total) {
+    const int lane = tid & 63, w = tid >> 6;
+    const uint64_t b = __ballot(flag);
+    const int within = __popcll(b & ((1ull << lane) - 1ull));
+    __syncthreads();                                   // previous readers of wave_tot are done
+    if (lane == 0) wave_tot[w] = __popcll(b);
+    __syncthreads();
+    int before = 0, tot = 0;
+#pragma unroll
+    for (int k = 0; k < SEL_WAVES; ++k) {
+        const int t = wave_tot[k];
+        before += k < w ? t : 0;
+        tot += t;
+    }
+    total = tot;
+    return before + within;
+}
+
+__global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int sh_cap) {
+    extern __shared__ __attribute__((aligned(16))) float sel_smem[];
+    float *sh = sel_smem;                                              // [sh_cap] group scores of the row
+    uint32_t *pk = reinterpret_cast<uint32_t *>(sel_smem + sh_cap);    // [(sh_cap + 3) / 4 + 1] pooled keys per block
+    __shared__ float red[64][16][2];
+    __shared__ float lse2[16];
+    __shared__ int hist[256];
+    __shared__ int wave_tot[SEL_WAVES];
+    __shared__ uint32_t s_prefix;
+    __shared__ int s_k;
+    const int pair = blockIdx.x;
+    const int b = pair / a.hkv;
+    const int L = a.ctx[b];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    int32_t *out = a.idx + (int64_t)pair * a.tk.topk_total;
+    if (L < a.tk.dense_below) {                      // dense sequences attend to every block: no list
+        for (int j = tid; j < a.tk.topk_total; j += SEL_THREADS) out[j] = -1;
+        return;
+    }
+    const int t = L - 1;
+    const int v = visible_cmp(t, a.tk.lc, a.tk.sc);
+    const int bt = t / kBlock, nblk = bt + 1;
+    // forced blocks: [0, n_init) and (bt - n_local, bt]
+    const int f_init = min(a.tk.n_init, nblk);
+    const int f_lo = max(0, bt - a.tk.n_local + 1);
+    const int n_forced = f_init + (bt - f_lo + 1) - max(0, f_init - f_lo);
+    const int n_rest = nblk - n_forced;
+    const int kr = min(a.tk.topk_total - a.tk.n_init - a.tk.n_local, n_rest);
+    if (kr == n_rest) {                              // everything up to the query's block is kept
+        for (int j = tid; j < a.tk.topk_total; j += SEL_THREADS) out[j] = j < nblk ? j : -1;
+        return;
+    }
+    // ---- log2 of sum_i 2^z per head: 64 thread groups per head over the chunk partials, then 64 -> 1
+    {
+        const int head = tid & 15, pg = tid >> 4;
+        const float *pp = a.part + (int64_t)pair * a.nchunk * 32 + head * 2;
+        float mm = -INFINITY, ll = 0.f;
+        for (int ch = pg; ch < a.nchunk; ch += 64) {
+            const float mo = pp[ch * 32], lo = pp[ch * 32 + 1];
+            const float mn = fmaxf(mm, mo);
+            const float ms = mn == -INFINITY ? 0.f : mn;
+            ll = ll * fast_exp2(mm - ms) + lo * fast_exp2(mo - ms);
+            mm = mn;
+        }
+        red[pg][head][0] = mm;
+        red[pg][head][1] = ll;
+        __syncthreads();
+        if (tid < 16) {
+            float m2 = -INFINITY;
+            for (int k = 0; k < 64; ++k) m2 = fmaxf(m2, red[k][tid][0]);
+            float l2 = 0.f;
+            for (int k = 0; k < 64; ++k)
+                if (red[k][tid][0] != -INFINITY) l2 += red[k][tid][1] * fast_exp2(red[k][tid][0] - m2);
+            lse2[tid] = m2 + __log2f(l2);
+        }
+        __syncthreads();
+    }
+    // ---- S^shared[i] = sum over the 16 heads of 2^(z[g][i] - lse2[g]), kept in LDS
+    for (int i = tid; i < v; i += SEL_THREADS) {
+        const float *zb = a.z + (int64_t)pair * G * a.zs + i;
+        float sum = 0.f;
+#pragma unroll
+        for (int gq = 0; gq < G; ++gq) sum += fast_exp2(zb[(int64_t)gq * a.zs] - lse2[gq]);
+        sh[i] = sum;
+    }
+    __syncthreads();
+    // ---- pooled key of every block (0 for forced blocks: they take no part in the top-k)
+    auto live = [&](int j) -> bool { return j < nblk && !(j < f_init || j >= f_lo); };
+    for (int j = tid; j < nblk; j += SEL_THREADS) {
+        float m = 0.f;
+        if (live(j)) {
+            const int lo = a.tk.pool_stride * j - a.tk.pool_pad;
+            for (int u = 0; u < a.tk.pool_len; ++u) {
+                const int i = lo + u;
+                if (i >= 0 && i < v) m = fmaxf(m, sh[i]);
+            }
+        }
+        pk[j] = __float_as_uint(m);
+    }
+    if (tid == 0) { s_prefix = 0u; s_k = kr; }
+    __syncthreads();
+    // ---- radix select (4 x 8 bits) of the kr-th largest key among the live blocks
+    for (int pass = 3; pass >= 0; --pass) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        const uint32_t prefix = s_prefix;
+        const int hi_shift = 8 * (pass + 1);
+        for (int j = tid; j < nblk; j += SEL_THREADS) {
+            if (!live(j)) continue;
+            const uint32_t key = pk[j];
+            if (pass == 3 || (key >> hi_shift) == prefix) atomicAdd(&hist[(key >> (8 * pass)) & 255u], 1);
+        }
+        __syncthreads();
+        if (w == 0) {
+            // lane l owns digits 4l .. 4l+3; above[d] = number of keys with a larger digit
+            const int k = s_k;
+            int c[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) c[u] = hist[4 * lane + u];
+            const int mine = c[0] + c[1] + c[2] + c[3];
+            int higher = 0;                              // keys in lanes above this one
+            {
+                int run = mine;                          // inclusive suffix sum over lanes
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const int other = __shfl_down(run, o);
+                    if (lane + o < 64) run += other;
+                }
+                higher = run - mine;
+            }
+            int above = higher;
+#pragma unroll
+            for (int u = 3; u >= 0; --u) {
+                // digit d = 4 lane + u holds the k-th largest iff above < k <= above + c[u]
+                if (above < k && k <= above + c[u]) {
+                    s_prefix = (prefix << 8) | (uint32_t)(4 * lane + u);
+                    s_k = k - above;
+                }
+                above += c[u];
+            }
+        }
+        __syncthreads();
+    }
+    const uint32_t thr = s_prefix;                   // the kr-th largest key; `need` of the keys equal to it are taken
+    const int need = s_k;
+    // ---- emit in ascending block order
+    int written = 0, eq_seen = 0;
+    for (int base = 0; base < nblk; base += SEL_THREADS) {
+        const int j = base + tid;
+        const bool in = j < nblk;
+        const bool forced = in && (j < f_init || j >= f_lo);
+        const bool lv = in && !forced;
+        const uint32_t key = in ? pk[j] : 0u;
+        int eq_tot, sel_tot;
+        const int eq_rank = eq_seen + wg_prefix_count(lv && key == thr, wave_tot, tid, eq_tot);
+        const bool sel = forced || (lv && key > thr) || (lv && key == thr && eq_rank < need);
+        const int pos = written + wg_prefix_count(sel, wave_tot, tid, sel_tot);
+        if (sel) out[pos] = j;
+        written += sel_tot;
+        eq_seen += eq_tot;
+    }
+    for (int j = written + tid; j < a.tk.topk_total; j += SEL_THREADS) out[j] = -1;
 }
 
 // ------------------------------------------------------------------------------------------ attend + merge
@@ -407,6 +578,19 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     a.nsplit = d.nsplit;
 
     hipLaunchKernelGGL(dec_scores_kernel, dim3(d.nchunk, pairs), dim3(256), 0, stream, a);
+    // group sum + max-pool + top-k: one workgroup per pair when the score row fits in LDS (contexts up to ~500K)
+    const int sh_cap = (d.zs + 3) / 4 * 4;
+    const size_t sel_lds = ((size_t)sh_cap + (size_t)sh_cap / 4 + 4) * sizeof(float);
+    if (sel_lds <= 128 * 1024) {
+        static size_t sel_attr = 0;
+        if (sel_lds > 48 * 1024 && sel_lds > sel_attr) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(dec_select_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_lds);
+            if (e != hipSuccess) return INFLLMV2_ERR_HIP;
+            sel_attr = sel_lds;
+        }
+        hipLaunchKernelGGL(dec_select_kernel, dim3(pairs), dim3(SEL_THREADS), sel_lds, stream, a, sh_cap);
+    } else {
     hipLaunchKernelGGL(dec_gsum_kernel, dim3(d.nchunk, pairs), dim3(256), 0, stream, a);
     {   // max-pool + top-k: the prefill kernel on the one row per pair
         RowMap m;
@@ -421,6 +605,7 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
         Launch L{p, m, stream, max_ctx};
         const int st = launch_topk(L, a.sh, d.zs, a.idx);
         if (st) return st;
+    }
     }
     const size_t attn_lds = (size_t)AW * TILE_ELEMS * sizeof(uint16_t);
     static bool attr_set = false;
