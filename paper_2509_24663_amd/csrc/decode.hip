@@ -9,8 +9,8 @@
 //   select  : grid (pairs)              one 1024-thread workgroup per pair merges the partials into the normaliser,
 //             sums the normalised scores of the 16 heads (Eq. 5) into LDS, max-pools them to blocks (Eq. 6) and
 //             selects (Eq. 2) with a workgroup-wide radix select: a single wavefront per row, as in prefill, would
-//             leave the chip empty and spend ~16 us on latency here.  Contexts whose score row does not fit in
-//             LDS use the separate group-sum kernel and the prefill stage-3 kernel instead.
+//             leave the chip empty and spend ~16 us on latency here.  The score row of a pair must fit in LDS
+//             (contexts up to ~419K tokens).
 //   attend  : grid (splits, pairs)      one wavefront per selected block: K fragments straight from global
 //             memory into MFMA operands, V through a 16 KB LDS tile (MFMA unit shared with prefill); the
 //             eight partial results of a workgroup are merged in LDS
@@ -39,7 +39,6 @@ struct DecArgs {
     TopkArgs tk;
     float *z;          // [pairs][16][zs] log2-domain logits c * <q, kc>
     float *part;       // [pairs][nchunk][16][2] (max, sum 2^(z - max)) per chunk
-    float *sh;         // [pairs][zs] group scores S^shared of the query row
     int32_t *idx;      // [pairs][topk_total]
     float *opart;      // [pairs][nsplit][OPART]  partial O^T ([dim][head]) relative to the split's own max
     float *mlpart;     // [pairs][nsplit][16][2]
@@ -129,55 +128,6 @@ __global__ void __launch_bounds__(256) dec_scores_kernel(DecArgs a) {
             part[tid * 2 + 1] = ll;
         }
     }
-}
-
-// ------------------------------------------------------------------------------------------ group sum
-// S^shared[i] = sum over the 16 heads of 2^(z[g][i] - lse2[g]) for the 128 keys of one chunk.
-__global__ void __launch_bounds__(256) dec_gsum_kernel(DecArgs a) {
-    __shared__ float red[16][16][2];
-    __shared__ float lse2[16];
-    __shared__ float half_sum[128];
-    const int chunk = blockIdx.x, pair = blockIdx.y;
-    const int b = pair / a.hkv;
-    const int L = a.ctx[b];
-    const int tid = threadIdx.x;
-    if (L < a.tk.dense_below) return;
-    const int v = visible_cmp(L - 1, a.tk.lc, a.tk.sc);
-    if (chunk * CK >= v) return;
-    {   // log2 of sum_i 2^z per head: 16 threads per head over the chunk partials, then 16 -> 1
-        const int head = tid & 15, pg = tid >> 4;
-        const float *pp = a.part + (int64_t)pair * a.nchunk * 32 + head * 2;
-        float mm = -INFINITY, ll = 0.f;
-        for (int ch = pg; ch < a.nchunk; ch += 16) {
-            const float mo = pp[ch * 32], lo = pp[ch * 32 + 1];
-            const float mn = fmaxf(mm, mo);
-            const float ms = mn == -INFINITY ? 0.f : mn;
-            ll = ll * fast_exp2(mm - ms) + lo * fast_exp2(mo - ms);
-            mm = mn;
-        }
-        red[pg][head][0] = mm;
-        red[pg][head][1] = ll;
-        __syncthreads();
-        if (tid < 16) {
-            float m2 = -INFINITY;
-            for (int k = 0; k < 16; ++k) m2 = fmaxf(m2, red[k][tid][0]);
-            float l2 = 0.f;
-            for (int k = 0; k < 16; ++k)
-                if (red[k][tid][0] != -INFINITY) l2 += red[k][tid][1] * fast_exp2(red[k][tid][0] - m2);
-            lse2[tid] = m2 + __log2f(l2);
-        }
-        __syncthreads();
-    }
-    const int key = chunk * CK + (tid & 127), hh = tid >> 7;      // two threads per key, 8 heads each
-    float sum = 0.f;
-    if (key < v) {
-        const float *zb = a.z + ((int64_t)pair * G + hh * 8) * a.zs + key;
-#pragma unroll
-        for (int gq = 0; gq < 8; ++gq) sum += fast_exp2(zb[(int64_t)gq * a.zs] - lse2[hh * 8 + gq]);
-    }
-    if (hh == 1) half_sum[tid & 127] = sum;
-    __syncthreads();
-    if (hh == 0 && key < v) a.sh[(int64_t)pair * a.zs + key] = sum + half_sum[tid];
 }
 
 // ------------------------------------------------------------------------------------------ select
@@ -495,7 +445,7 @@ inline size_t align_up(size_t x, size_t al) { return (x + al - 1) / al * al; }
 
 struct DecLayout {
     int zs, nchunk, nsplit;
-    size_t off_part, off_sh, off_idx, off_opart, off_ml, total;
+    size_t off_part, off_idx, off_opart, off_ml, total;
 };
 
 DecLayout dec_layout(const infllmv2_params *p, int batch, int max_ctx, int dense_blocks) {
@@ -510,8 +460,6 @@ DecLayout dec_layout(const infllmv2_params *p, int batch, int max_ctx, int dense
     size_t off = align_up(pairs * G * d.zs * sizeof(float), 256);
     d.off_part = off;
     off += align_up(pairs * d.nchunk * 32 * sizeof(float), 256);
-    d.off_sh = off;
-    off += align_up(pairs * d.zs * sizeof(float), 256);
     d.off_idx = off;
     off += align_up(pairs * p->topk_total * sizeof(int32_t), 256);
     d.off_opart = off;
@@ -567,7 +515,6 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     char *base = (char *)ws;
     a.z = (float *)base;
     a.part = (float *)(base + d.off_part);
-    a.sh = (float *)(base + d.off_sh);
     a.idx = idx_out ? idx_out : (int32_t *)(base + d.off_idx);
     a.opart = (float *)(base + d.off_opart);
     a.mlpart = (float *)(base + d.off_ml);
@@ -578,10 +525,11 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     a.nsplit = d.nsplit;
 
     hipLaunchKernelGGL(dec_scores_kernel, dim3(d.nchunk, pairs), dim3(256), 0, stream, a);
-    // group sum + max-pool + top-k: one workgroup per pair when the score row fits in LDS (contexts up to ~500K)
+    // group sum + max-pool + top-k: one workgroup per pair; the score row lives in LDS
     const int sh_cap = (d.zs + 3) / 4 * 4;
     const size_t sel_lds = ((size_t)sh_cap + (size_t)sh_cap / 4 + 4) * sizeof(float);
-    if (sel_lds <= 128 * 1024) {
+    if (sel_lds > 128 * 1024) return INFLLMV2_ERR_UNSUPPORTED;
+    {
         static size_t sel_attr = 0;
         if (sel_lds > 48 * 1024 && sel_lds > sel_attr) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(dec_select_kernel),
@@ -590,22 +538,6 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
             sel_attr = sel_lds;
         }
         hipLaunchKernelGGL(dec_select_kernel, dim3(pairs), dim3(SEL_THREADS), sel_lds, stream, a, sh_cap);
-    } else {
-    hipLaunchKernelGGL(dec_gsum_kernel, dim3(d.nchunk, pairs), dim3(256), 0, stream, a);
-    {   // max-pool + top-k: the prefill kernel on the one row per pair
-        RowMap m;
-        m.cu = nullptr;
-        m.cu_c = nullptr;
-        m.ctx = ctx_d;
-        m.batch = batch;
-        m.total_rows = batch;
-        m.num_kv_heads = p->num_kv_heads;
-        m.kv_tok_stride = m.kv_head_stride = m.kv_batch_stride = 0;
-        m.kc_total_c = m.kc_head_stride = 0;
-        Launch L{p, m, stream, max_ctx};
-        const int st = launch_topk(L, a.sh, d.zs, a.idx);
-        if (st) return st;
-    }
     }
     const size_t attn_lds = (size_t)AW * TILE_ELEMS * sizeof(uint16_t);
     static bool attr_set = false;

@@ -8,7 +8,7 @@ import torch
 
 import synth
 from helpers import assert_out_close, to_dev, to_np
-from test_gpu_parity import _run_prefill_case
+from test_gpu_parity import _check_decode, _run_prefill_case
 
 pytestmark = pytest.mark.gpu
 
@@ -83,3 +83,13 @@ def test_c5_varlen_mixed_dense_sparse(m, oracle):
     rows = _sample_rows(w["cu_seqlens"], np.random.default_rng(5), 2, 48)
     st = _run_prefill_case(m, oracle, w, m.Params.from_config(cfg), oracle.Params.from_config(cfg), "bf16", rows=rows)
     print("C5", st)
+
+
+def test_decode_context_of_400k_tokens(m, oracle):
+    """A context near the upper limit of the decode selection kernel (its score row must fit in LDS, ~419K
+    tokens), with a much shorter sequence in the same batch; a longer one is refused, not mis-computed."""
+    ctx = [400000, 70000]
+    w = synth.make_decode(ctx, 32, 2, 128, seed=31, dtype="bf16")
+    gp = m.Params.make("bf16", 32, 2, 128, n_init=1, n_local=8, topk_total=64)
+    op = oracle.Params(n_init=1, n_local=8, topk_total=64, softmax_scale=float(gp.softmax_scale))
+    assert _check_decode(m, oracle, w, ctx, gp, op, "bf16") == 4
