@@ -4,6 +4,7 @@
  *
  * The path has four stages (Sec. 3.2-3.4 of the paper):
  *   1. infllmv2_compress_k      mean-pool keys into compressed keys K^{C1}            (Eq. 3)
+ *      infllmv2_compress_k_append   the same for the rows a growing cache has just completed
  *   2. infllmv2_block_scores    softmax(scale * Q K^{C1 T}) summed over the GQA group (Eq. 4, 5, Alg. 1;
  *                               optionally with the LSE Approximation of Sec. 3.4)
  *   3. infllmv2_topk_blocks     max-pool to selection blocks, keep init + local,
@@ -112,6 +113,22 @@ const char *infllmv2_version(void);
 int infllmv2_compress_k(const infllmv2_params *p, const void *k_d, int64_t kv_tok_stride, int64_t kv_head_stride,
                         const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
                         float *kc_d, int32_t *cu_seqlens_c_d, int64_t total_c, void *stream);
+
+/*
+ * Stage 1 for a growing cache (decode): Sec. 3.3, Eq. 3 applied to the tail of each sequence.  Sequence b had
+ * prev_lens[b] tokens in its K cache when its compressed-key cache was last brought up to date and has
+ * ctx_lens[b] >= prev_lens[b] now; this writes the compressed keys that became complete in between, rows
+ * nc(prev_lens[b]) .. nc(ctx_lens[b]) - 1 of every KV head's plane (one new row every s_C1 tokens), and leaves
+ * the other rows alone.  The result equals infllmv2_compress_k on the first ctx_lens[b] tokens.
+ *   k_cache_d      device, dtype, token t of (b, h) at  base + b * kv_batch_stride + h * kv_head_stride + t * kv_tok_stride
+ *   kc_cache_d     device in/out, float32; plane (b, h) at  base + (b * num_kv_heads + h) * kc_head_stride,
+ *                  row i at + i * head_dim  (kc_head_stride >= max_b nc(ctx_lens[b]) * head_dim, else INVALID_ARGUMENT)
+ *   prev_lens_h/d, ctx_lens_h/d   host / device int32 [batch]
+ */
+int infllmv2_compress_k_append(const infllmv2_params *p, const void *k_cache_d, int64_t kv_batch_stride,
+                               int64_t kv_head_stride, int64_t kv_tok_stride, float *kc_cache_d, int64_t kc_head_stride,
+                               const int32_t *prev_lens_h, const int32_t *prev_lens_d, const int32_t *ctx_lens_h,
+                               const int32_t *ctx_lens_d, int32_t batch, void *stream);
 
 /*
  * Stage 2 -- Sec. 3.3 Eq. 4-5, computed as in Alg. 1 (two passes, head-group sum on chip):

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     SeqInfo,
     block_scores,
     compress_k,
+    compress_k_append,
     decode_workspace_bytes,
     dense_attn_fwd,
     lib,

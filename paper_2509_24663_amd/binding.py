@@ -64,6 +64,7 @@ _SIGNATURES = {
     "infllmv2_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "infllmv2_version": (ctypes.c_char_p, []),
     "infllmv2_compress_k": (ctypes.c_int, [_PP, _P, _I64, _I64, _P, _P, _I32, _P, _P, _I64, _P]),
+    "infllmv2_compress_k_append": (ctypes.c_int, [_PP, _P, _I64, _I64, _I64, _P, _I64, _P, _P, _P, _P, _I32, _P]),
     "infllmv2_block_scores": (ctypes.c_int, [_PP, _P, _P, _I64, _P, _P, _P, _I32, _P, _I64, _P]),
     "infllmv2_topk_blocks": (ctypes.c_int, [_PP, _P, _I64, _P, _P, _I32, _P, _P]),
     "infllmv2_sparse_attn_fwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _P, _I32, _P, _P, _P]),
@@ -161,6 +162,19 @@ def compress_k(p: Params, k: torch.Tensor, cu_seqlens, out=None):
                                    _ptr(cu_c), kc.shape[1], _stream())
     _check(st, "infllmv2_compress_k")
     return kc, cu_c
+
+
+def compress_k_append(p: Params, k_cache: torch.Tensor, kc_cache: torch.Tensor, prev_lens, ctx_lens):
+    """Brings a decode compressed-key cache up to date in place.  k_cache [B, hkv, Lmax, d]; kc_cache
+    [B, hkv, max_nc, d] fp32; prev_lens / ctx_lens: sequences of ints or DecodeInfo (cache lengths then and now)."""
+    pv = prev_lens if isinstance(prev_lens, DecodeInfo) else DecodeInfo(prev_lens)
+    cx = ctx_lens if isinstance(ctx_lens, DecodeInfo) else DecodeInfo(ctx_lens)
+    assert k_cache.dim() == 4 and k_cache.stride(3) == 1 and kc_cache.dim() == 4 and kc_cache.is_contiguous()
+    st = lib().infllmv2_compress_k_append(ctypes.byref(p), _ptr(k_cache), k_cache.stride(0), k_cache.stride(1),
+                                          k_cache.stride(2), _ptr(kc_cache), kc_cache.stride(1), _ptr(pv.ctx_h),
+                                          _ptr(pv.ctx_d), _ptr(cx.ctx_h), _ptr(cx.ctx_d), cx.batch, _stream())
+    _check(st, "infllmv2_compress_k_append")
+    return kc_cache
 
 
 def block_scores(p: Params, q: torch.Tensor, kc: torch.Tensor, cu_seqlens, cu_seqlens_c: torch.Tensor,

@@ -116,6 +116,31 @@ int infllmv2_compress_k(const infllmv2_params *p, const void *k_d, int64_t kv_to
     return launch_compress_k(L, k_d, kc_d, need);
 }
 
+int infllmv2_compress_k_append(const infllmv2_params *p, const void *k_cache_d, int64_t kv_batch_stride,
+                               int64_t kv_head_stride, int64_t kv_tok_stride, float *kc_cache_d, int64_t kc_head_stride,
+                               const int32_t *prev_lens_h, const int32_t *prev_lens_d, const int32_t *ctx_lens_h,
+                               const int32_t *ctx_lens_d, int32_t batch, void *stream) {
+    int st = check_params(p);
+    if (st) return st;
+    if (batch < 0) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if (batch == 0) return INFLLMV2_OK;
+    if (prev_lens_h == nullptr || prev_lens_d == nullptr || ctx_lens_h == nullptr || ctx_lens_d == nullptr)
+        return INFLLMV2_ERR_INVALID_ARGUMENT;
+    int max_new = 0, max_nc = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (prev_lens_h[b] < 0 || ctx_lens_h[b] < prev_lens_h[b]) return INFLLMV2_ERR_INVALID_ARGUMENT;
+        const int n1 = num_cmp(ctx_lens_h[b], p->cmp_len, p->cmp_stride);
+        const int grown = n1 - num_cmp(prev_lens_h[b], p->cmp_len, p->cmp_stride);
+        if (grown > max_new) max_new = grown;
+        if (n1 > max_nc) max_nc = n1;
+    }
+    if (max_new == 0) return INFLLMV2_OK;
+    if (k_cache_d == nullptr || kc_cache_d == nullptr) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if (kv_tok_stride < p->head_dim || kc_head_stride < (int64_t)max_nc * p->head_dim) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    return launch_compress_k_append(p, k_cache_d, kv_batch_stride, kv_head_stride, kv_tok_stride, kc_cache_d,
+                                    kc_head_stride, prev_lens_d, ctx_lens_d, batch, max_new, (hipStream_t)stream);
+}
+
 int infllmv2_block_scores(const infllmv2_params *p, const void *q_d, const float *kc_d, int64_t total_c,
                           const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d,
                           const int32_t *cu_seqlens_c_d, int32_t batch,

@@ -122,6 +122,9 @@ struct Launch {
 
 int launch_cu_c(const infllmv2_params *p, const int32_t *cu_d, int batch, int32_t *cu_c_d, hipStream_t s);
 int launch_compress_k(const Launch &L, const void *k, float *kc, int64_t total_c_rows);
+int launch_compress_k_append(const infllmv2_params *p, const void *k, int64_t kv_batch_stride, int64_t kv_head_stride,
+                             int64_t kv_tok_stride, float *kc, int64_t kc_head_stride, const int32_t *prev_d,
+                             const int32_t *ctx_d, int batch, int max_new, hipStream_t stream);
 // cu_h: host cu_seqlens for the tiled kernels' grid (nullptr: single-row / decode form)
 int launch_block_scores(const Launch &L, const void *q, const float *kc, float *s_shared, int64_t row_stride,
                         const int32_t *cu_h);

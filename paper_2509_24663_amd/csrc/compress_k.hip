@@ -60,6 +60,53 @@ static int launch_t(const Launch &L, const void *k, float *kc, int total_c) {
     return hip_status(hipGetLastError());
 }
 
+// Compressed keys that became complete while a cached sequence grew from prev[b] to ctx[b] tokens: rows
+// nc(prev[b]) .. nc(ctx[b]) - 1 of the pair's plane of the compressed-key cache.  One workgroup per new row.
+template <typename T, int D>
+__global__ void __launch_bounds__(D / 8)
+compress_k_append_kernel(const T *__restrict__ k, int64_t kv_batch_stride, int64_t kv_head_stride, int64_t kv_tok_stride,
+                         float *__restrict__ kc, int64_t kc_head_stride, const int32_t *__restrict__ prev,
+                         const int32_t *__restrict__ ctx, int hkv, int lc, int sc) {
+    const int pair = blockIdx.y, b = pair / hkv, h = pair - b * hkv;
+    const int i = num_cmp(prev[b], lc, sc) + (int)blockIdx.x;
+    if (i >= num_cmp(ctx[b], lc, sc)) return;
+    const int c0 = threadIdx.x * 8;
+    const T *src = k + (int64_t)b * kv_batch_stride + (int64_t)h * kv_head_stride + (int64_t)i * sc * kv_tok_stride + c0;
+    float acc[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = 0.f;
+    for (int u = 0; u < lc; ++u) {
+        const T *r = src + (int64_t)u * kv_tok_stride;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[c] += Elem<T>::load(r + c);
+    }
+    const float inv = 1.0f / (float)lc;
+    float *dst = kc + (int64_t)pair * kc_head_stride + (int64_t)i * D + c0;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) dst[c] = acc[c] * inv;
+}
+
+template <typename T, int D>
+static int launch_append_t(const infllmv2_params *p, const void *k, int64_t bs, int64_t hs, int64_t ts, float *kc,
+                           int64_t kc_head_stride, const int32_t *prev_d, const int32_t *ctx_d, int batch, int max_new,
+                           hipStream_t stream) {
+    hipLaunchKernelGGL((compress_k_append_kernel<T, D>), dim3(max_new, batch * p->num_kv_heads), dim3(D / 8), 0, stream,
+                       (const T *)k, bs, hs, ts, kc, kc_head_stride, prev_d, ctx_d, p->num_kv_heads, p->cmp_len,
+                       p->cmp_stride);
+    return hip_status(hipGetLastError());
+}
+
+int launch_compress_k_append(const infllmv2_params *p, const void *k, int64_t bs, int64_t hs, int64_t ts, float *kc,
+                             int64_t kc_head_stride, const int32_t *prev_d, const int32_t *ctx_d, int batch, int max_new,
+                             hipStream_t stream) {
+    const bool bf = p->dtype == INFLLMV2_BF16;
+    if (p->head_dim == 128)
+        return bf ? launch_append_t<bf16_t, 128>(p, k, bs, hs, ts, kc, kc_head_stride, prev_d, ctx_d, batch, max_new, stream)
+                  : launch_append_t<float, 128>(p, k, bs, hs, ts, kc, kc_head_stride, prev_d, ctx_d, batch, max_new, stream);
+    return bf ? launch_append_t<bf16_t, 64>(p, k, bs, hs, ts, kc, kc_head_stride, prev_d, ctx_d, batch, max_new, stream)
+              : launch_append_t<float, 64>(p, k, bs, hs, ts, kc, kc_head_stride, prev_d, ctx_d, batch, max_new, stream);
+}
+
 int launch_compress_k(const Launch &L, const void *k, float *kc, int64_t total_c_rows) {
     const int tc = (int)total_c_rows;
     const bool bf = L.p->dtype == INFLLMV2_BF16;

@@ -78,6 +78,18 @@ def test_validation_errors_before_launch(m):
     assert _call_compress(m, p, [0, 64], total_c=2) == INVALID      # kc too small: nc(64) = 3
     assert _call_compress(m, p, [0, 64], tok=64) == INVALID         # token stride < head_dim
     assert m.lib().infllmv2_compress_k(None, None, 0, 0, None, None, 0, None, None, 0, None) == INVALID
+    # cache append: shrinking lengths and a compressed-key plane that is too small are caught on the host;
+    # a step that completes no window returns before touching any pointer
+    L = m.lib()
+    def _app(prev, ctx, kc_stride):
+        pv, cx = np.array(prev, np.int32), np.array(ctx, np.int32)
+        return L.infllmv2_compress_k_append(ctypes.byref(p), ctypes.c_void_p(256), 1 << 20, 1 << 16, 128,
+                                            ctypes.c_void_p(256), kc_stride, pv.ctypes.data_as(ctypes.c_void_p),
+                                            ctypes.c_void_p(256), cx.ctypes.data_as(ctypes.c_void_p),
+                                            ctypes.c_void_p(256), len(prev), None)
+    assert _app([100], [90], 1 << 16) == INVALID
+    assert _app([0], [64], 2 * 128) == INVALID                       # nc(64) = 3 rows needed
+    assert _app([33], [47], 0) == 0                                  # no window completed: nothing to do
     # decode: workspace size query and too-small workspace
     need = m.decode_workspace_bytes(p, 16, 65536)
     assert need > 16 * 2 * 4095 * 4

@@ -318,6 +318,35 @@ def _check_decode(m, oracle, w, ctx, gp, op, dtype):
     return n_sparse
 
 
+def test_compress_k_append_keeps_the_decode_cache_current(m, oracle):
+    """Growing caches: the appended compressed keys must equal stage 1 on the grown sequence (oracle), rows that
+    already existed must stay untouched, and steps that complete no window must write nothing."""
+    for dtype, hkv, d in (("bf16", 2, 128), ("fp32", 2, 64)):
+        gp, op = _params(m, oracle, dtype, 2 * hkv, hkv, d)
+        prev = [0, 31, 47, 48, 1000, 500]
+        ctx = [40, 32, 47, 200, 1001, 564]
+        w = synth.make_decode(ctx, 2 * hkv, hkv, d, seed=21, dtype=dtype, max_len=1100)
+        kcache = to_dev(w["k_cache"], dtype)
+        max_nc = oracle.num_cmp(1100, op)
+        kcc = torch.full((len(ctx), hkv, max_nc, d), 7.0, dtype=torch.float32, device="cuda")
+        for b, L in enumerate(prev):                       # the cache as it stood at prev
+            nc = oracle.num_cmp(L, op)
+            if nc:
+                kcb, _ = m.compress_k(gp, kcache[b, :, :L], [0, L])
+                kcc[b, :, :nc] = kcb[:, :nc]
+        before = kcc.clone()
+        m.compress_k_append(gp, kcache, kcc, prev, ctx)
+        torch.cuda.synchronize()
+        got, before = to_np(kcc), to_np(before)
+        for b, (L0, L1) in enumerate(zip(prev, ctx)):
+            n0, n1 = oracle.num_cmp(L0, op), oracle.num_cmp(L1, op)
+            for h in range(hkv):
+                want = oracle.compress_k(w["k_cache"][b, h, :L1], op)
+                np.testing.assert_allclose(got[b, h, n0:n1], want[n0:n1], rtol=0, atol=2e-6)
+                np.testing.assert_array_equal(got[b, h, :n0], before[b, h, :n0])
+                np.testing.assert_array_equal(got[b, h, n1:], before[b, h, n1:])
+
+
 def test_decode_dense_switch_and_ragged(m, oracle):
     """Decode with sequences on both sides of the dense threshold, partial last blocks, tiny contexts."""
     ctx = [1, 2, 31, 32, 63, 64, 65, 127, 700, 1024, 1023, 2500, 4097]
