@@ -1,5 +1,9 @@
-// Building blocks shared by the prefill tile kernel and the decode kernel: LDS tile layout, asynchronous
-// block loads and the (token, block) MFMA unit.  bf16 data, G = 16 heads per KV head, d_h = 128.
+// Building blocks of the prefill tile kernel and the decode attention kernel: asynchronous global -> LDS copies,
+// LDS tile layouts and the (token, block) MFMA units.  bf16 data, G = 16 heads per KV head, d_h = 128.
+// Two units live here.  The decode unit (first part of the file) works on the caches as they are: K fragments
+// come straight from global memory, V through a row-major LDS tile read with transposing loads.  The prefill unit
+// (second part) works on a K tile and a pre-transposed V^T tile and is arranged around the issue-port and LDS
+// bandwidth limits described there.
 #pragma once
 #include "common.h"
 
@@ -40,6 +44,9 @@ __device__ inline void async_copy16(const void *sbase, uint32_t voff, uint32_t l
 
 __device__ inline uint32_t lds_address(const void *p) { return (uint32_t)(uintptr_t)(lds_void *)p; }
 
+// =====================================================================================================
+// Decode unit
+//
 // One 1 KB piece (4 rows) of a K or V block: global -> LDS, asynchronously.  Lane l fills LDS slot
 // (row 4*q16 + l/16, physical chunk l%16), which holds logical 16-byte chunk (l%16) ^ (row%16) of that row.
 // Rows past the end of the sequence re-read the last valid row (finite data, always masked by causality).
