@@ -382,6 +382,52 @@ def test_empty_batch_and_empty_sequences(m, oracle):
     assert torch.equal(a["out"], b["out"]) and torch.equal(a["block_idx"], b["block_idx"])
 
 
+def test_token_major_kv_layout_gives_identical_results(m, oracle):
+    """K and V may be addressed with any (token, head) strides: a token-major [T, hkv, d] buffer viewed as
+    [hkv, T, d] must give bit-identical results to the head-major copy, in prefill (MFMA and generic kernels)
+    and in decode (cache stored [B, Lmax, hkv, d])."""
+    for dtype, hq, hkv, d, n in (("bf16", 32, 2, 128, 1500), ("fp32", 4, 2, 64, 700)):
+        w = synth.make_prefill(n, hq, hkv, d, seed=41, dtype=dtype)
+        gp, _ = _params(m, oracle, dtype, hq, hkv, d, n_init=1, n_local=2, topk_total=9)
+        q, k, v = (to_dev(w[x], dtype) for x in ("q", "k", "v"))
+        kt = k.permute(1, 0, 2).contiguous().permute(1, 0, 2)         # same values, token-major storage
+        vt = v.permute(1, 0, 2).contiguous().permute(1, 0, 2)
+        assert kt.stride() == (d, hkv * d, 1)
+        a = m.sparse_prefill(gp, q, k, v, w["cu_seqlens"])
+        b = m.sparse_prefill(gp, q, kt, vt, w["cu_seqlens"])
+        torch.cuda.synchronize()
+        for key in ("out", "lse", "block_idx", "kc"):
+            assert torch.equal(a[key], b[key]), (dtype, key)
+        da, _ = m.dense_attn_fwd(gp, q, k, v, w["cu_seqlens"])
+        db, _ = m.dense_attn_fwd(gp, q, kt, vt, w["cu_seqlens"])
+        assert torch.equal(da, db)
+    ctx = [900, 65, 3000]
+    dw = synth.make_decode(ctx, 32, 2, 128, seed=42, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=2, topk_total=9)
+    q, kc_, vc_ = to_dev(dw["q"], "bf16"), to_dev(dw["k_cache"], "bf16"), to_dev(dw["v_cache"], "bf16")
+    kcc = torch.zeros((3, 2, max(oracle.num_cmp(3000, op), 1), 128), dtype=torch.float32, device="cuda")
+    m.compress_k_append(gp, kc_, kcc, [0, 0, 0], ctx)
+    kt = kc_.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)     # stored [B, Lmax, hkv, d]
+    vt = vc_.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    kcc2 = torch.zeros_like(kcc)
+    m.compress_k_append(gp, kt, kcc2, [0, 0, 0], ctx)
+    oa, la, ia = m.sparse_decode(gp, q, kc_, vc_, kcc, ctx)
+    ob, lb, ib = m.sparse_decode(gp, q, kt, vt, kcc2, ctx)
+    torch.cuda.synchronize()
+    assert torch.equal(kcc, kcc2) and torch.equal(oa, ob) and torch.equal(la, lb) and torch.equal(ia, ib)
+
+
+def test_shifted_pool_window_and_lse_approximation_with_switch(m, oracle):
+    """pool_pad = 1 (the shifted reading of Eq. 6) through the MFMA path, and lse_mode 1 on a packed batch with
+    sequences on both sides of the dense threshold."""
+    w = synth.make_prefill(2100, 32, 2, 128, seed=43, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=2, topk_total=11, pool_pad=1)
+    _run_prefill_case(m, oracle, w, gp, op, "bf16")
+    w = synth.make_varlen((300, 150, 1200, 640), 32, 2, 128, seed=44, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=3, topk_total=8, dense_threshold=600, lse_mode=1)
+    _run_prefill_case(m, oracle, w, gp, op, "bf16")
+
+
 def test_determinism(m, oracle):
     """No atomics on floats anywhere: two runs give bitwise identical results."""
     w = synth.make_prefill(3000, 32, 2, 128, seed=55, dtype="bf16")
