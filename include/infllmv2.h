@@ -23,8 +23,10 @@
  *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
  *     stream).  The two prefill attention calls obtain a V-sized scratch buffer
  *     from the device's stream-ordered memory pool (hipMallocAsync / hipFreeAsync
- *     on `stream`) for bf16 data with 16 query heads per KV head and head_dim 128;
- *     nothing else is allocated.  The caller owns every buffer and keeps it alive until the
+ *     on `stream`) for bf16 data with 16 query heads per KV head and head_dim 128,
+ *     and on first use raise that pool's release threshold so that the buffer is
+ *     served from the pool on later calls instead of being returned to the driver
+ *     at every synchronisation; nothing else is allocated.  The caller owns every buffer and keeps it alive until the
  *     stream work has finished.  Calls are thread-safe.
  *   - All indices are 0-based.  Token t of a sequence lies in block t / block_size.
  *     Sequences are packed along the token axis; cu_seqlens has batch+1 int32
