@@ -1,8 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the InfLLM-V2 attention hot path on one MI355X.
 
-A "step" is one pass of the whole sparse prefill path -- compress_k, block_scores, topk_blocks,
-sparse_attn_fwd -- over one synthetic batch that is already resident in HBM.  The default workload is
+A "step" is one pass of the whole sparse prefill path -- compress_k, block_scores_pooled, topk_pooled,
+sparse_attn_fwd (stages 2 and 3 in the form with the max-pooling fused into the score kernel; the block lists are
+identical to those of block_scores + topk_blocks, which are timed beside it) -- over one synthetic batch that is
+already resident in HBM.  The default workload is
 BASELINE config 3 (bf16, 131072 tokens, 32 query heads / 2 KV heads, d 128, 64 selected blocks), the one
 the headline metric is quoted on.  One JSON line is printed with the whole-step throughput, the per-stage
 times, the roofline of the dominant kernel (HIP-event timed on the launch stream), the library's own dense
@@ -95,28 +97,28 @@ def main() -> int:
         del src, dst
 
     # ------------------------------------------------------------------ whole path, K timed steps
-    bufs = m.sparse_prefill(gp, q, k, v, si)          # first call allocates every buffer once
+    bufs = m.sparse_prefill(gp, q, k, v, si, fused_pool=True)          # first call allocates every buffer once
     torch.cuda.synchronize()
     for _ in range(max(args.warmup - 1, 0)):
-        m.sparse_prefill(gp, q, k, v, si, buffers=bufs)
+        m.sparse_prefill(gp, q, k, v, si, buffers=bufs, fused_pool=True)
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for _ in range(args.steps):
-        m.sparse_prefill(gp, q, k, v, si, buffers=bufs)
+        m.sparse_prefill(gp, q, k, v, si, buffers=bufs, fused_pool=True)
     torch.cuda.synchronize()
     step_ms = (time.perf_counter() - t_start) * 1e3 / args.steps
 
     # ------------------------------------------------------------------ per-stage HIP-event timing
-    stage_names = ["compress_k", "block_scores", "topk_blocks", "sparse_attn_fwd"]
+    stage_names = ["compress_k", "block_scores_pooled", "topk_pooled", "sparse_attn_fwd"]
     acc = {s: 0.0 for s in stage_names}
     for _ in range(args.steps):
         ev = _events(torch, 5)
         ev[0].record()
         m.compress_k(gp, k, si, out=(bufs["kc"], bufs["cu_seqlens_c"]))
         ev[1].record()
-        m.block_scores(gp, q, bufs["kc"], si, bufs["cu_seqlens_c"], out=bufs["s_shared"])
+        m.block_scores_pooled(gp, q, bufs["kc"], si, bufs["cu_seqlens_c"], out=bufs["s_cmp"])
         ev[2].record()
-        m.topk_blocks(gp, bufs["s_shared"], si, out=bufs["block_idx"])
+        m.topk_pooled(gp, bufs["s_cmp"], si, out=bufs["block_idx"])
         ev[3].record()
         m.sparse_attn_fwd(gp, q, k, v, bufs["block_idx"], si, out=bufs["out"], lse=bufs["lse"])
         ev[4].record()
@@ -124,6 +126,25 @@ def main() -> int:
         for i, s in enumerate(stage_names):
             acc[s] += ev[i].elapsed_time(ev[i + 1])
     stage_ms = {s: acc[s] / args.steps for s in stage_names}
+
+    # the same two stages with S^shared written per compressed key (identical block lists)
+    s_shared = m.block_scores(gp, q, bufs["kc"], si, bufs["cu_seqlens_c"])
+    idx2 = m.topk_blocks(gp, s_shared, si)
+    torch.cuda.synchronize()
+    assert torch.equal(idx2, bufs["block_idx"]), "fused and two-stage selections differ"
+    ev = _events(torch, 3)
+    ev[0].record()
+    for _ in range(args.steps):
+        m.block_scores(gp, q, bufs["kc"], si, bufs["cu_seqlens_c"], out=s_shared)
+    ev[1].record()
+    for _ in range(args.steps):
+        m.topk_blocks(gp, s_shared, si, out=idx2)
+    ev[2].record()
+    torch.cuda.synchronize()
+    two_stage = {"block_scores_ms": round(ev[0].elapsed_time(ev[1]) / args.steps, 4),
+                 "topk_blocks_ms": round(ev[1].elapsed_time(ev[2]) / args.steps, 4),
+                 "s_shared_bytes": s_shared.numel() * 4, "s_cmp_bytes": bufs["s_cmp"].numel() * 4}
+    del idx2
 
     # executed attention flops from the actual selection: every selected block is full except the query's own
     idx = bufs["block_idx"]
@@ -136,31 +157,36 @@ def main() -> int:
     vis = torch.where(tpos < cfg.cmp_len - 1, torch.zeros_like(vis), vis)
     score_flops = 2 * 2.0 * d * hq * int(vis.sum())                          # two passes, 1x MFMA each
     score_bytes = 4.0 * hkv * int(vis.sum())
+    pooled_entries = int(torch.where(vis > 0, torch.minimum((vis + cfg.pool_pad + cfg.pool_stride - 1) // cfg.pool_stride,
+                                                            tpos // cfg.block_size + 1), torch.zeros_like(vis)).sum())
+    pooled_bytes = 4.0 * hkv * pooled_entries
 
     tflops = attn_flops / (step_ms * 1e-3) / 1e12
     stages = {s: {"ms": round(stage_ms[s], 4)} for s in stage_names}
     stages["sparse_attn_fwd"].update(tflops=round(attn_flops / (stage_ms["sparse_attn_fwd"] * 1e-3) / 1e12, 2),
                                      frac_mfma_peak=round(attn_flops / (stage_ms["sparse_attn_fwd"] * 1e-3) / 1e12 /
                                                           PEAK_BF16_MFMA_TFLOPS, 4))
-    stages["block_scores"].update(tflops=round(score_flops / (stage_ms["block_scores"] * 1e-3) / 1e12, 2),
-                                  frac_mfma_peak=round(score_flops / (stage_ms["block_scores"] * 1e-3) / 1e12 /
-                                                       PEAK_BF16_MFMA_TFLOPS, 4))
+    stages["block_scores_pooled"].update(
+        tflops=round(score_flops / (stage_ms["block_scores_pooled"] * 1e-3) / 1e12, 2),
+        frac_mfma_peak=round(score_flops / (stage_ms["block_scores_pooled"] * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4))
     kbytes = 2.0 * n * hkv * d + 4.0 * hkv * bufs["kc"].shape[1] * d
     stages["compress_k"].update(gbs=round(kbytes / (stage_ms["compress_k"] * 1e-3) / 1e9, 1))
-    tk_bytes = score_bytes + 4.0 * hkv * n * cfg.topk_total
-    stages["topk_blocks"].update(gbs=round(tk_bytes / (stage_ms["topk_blocks"] * 1e-3) / 1e9, 1),
-                                 frac_hbm_peak=round(tk_bytes / (stage_ms["topk_blocks"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4))
+    tk_bytes = pooled_bytes + 4.0 * hkv * n * cfg.topk_total
+    stages["topk_pooled"].update(gbs=round(tk_bytes / (stage_ms["topk_pooled"] * 1e-3) / 1e9, 1),
+                                 frac_hbm_peak=round(tk_bytes / (stage_ms["topk_pooled"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4))
+    tk2_bytes = score_bytes + 4.0 * hkv * n * cfg.topk_total
+    two_stage["topk_blocks_gbs"] = round(tk2_bytes / (two_stage["topk_blocks_ms"] * 1e-3) / 1e9, 1)
 
     # roofline of the dominant kernel (largest share of the step)
     dom = max(stage_names, key=lambda s: stage_ms[s])
     traffic = measured_traffic(dom, args.workload)
-    if dom in ("sparse_attn_fwd", "block_scores"):
+    if dom in ("sparse_attn_fwd", "block_scores_pooled"):
         fl = attn_flops if dom == "sparse_attn_fwd" else score_flops
         ach = fl / (stage_ms[dom] * 1e-3) / 1e12
         roof = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_MFMA_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": traffic}
     else:
-        by = tk_bytes if dom == "topk_blocks" else kbytes
+        by = tk_bytes if dom == "topk_pooled" else kbytes
         ach = by / (stage_ms[dom] * 1e-3) / 1e9
         roof = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": traffic}
@@ -168,13 +194,14 @@ def main() -> int:
     # ------------------------------------------------------------------ stage 2 with the LSE Approximation (Sec. 3.4)
     # reported beside the headline, which stays the exact two-pass form
     gp_lse = m.Params.from_config(cfg, lse_mode=1)
-    sc2 = torch.empty_like(bufs["s_shared"])
-    m.block_scores(gp_lse, q, bufs["kc"], si, bufs["cu_seqlens_c"], out=sc2)
+    del s_shared
+    sc2 = torch.empty_like(bufs["s_cmp"])
+    m.block_scores_pooled(gp_lse, q, bufs["kc"], si, bufs["cu_seqlens_c"], out=sc2)
     torch.cuda.synchronize()
     ev = _events(torch, 2)
     ev[0].record()
     for _ in range(args.steps):
-        m.block_scores(gp_lse, q, bufs["kc"], si, bufs["cu_seqlens_c"], out=sc2)
+        m.block_scores_pooled(gp_lse, q, bufs["kc"], si, bufs["cu_seqlens_c"], out=sc2)
     ev[1].record()
     torch.cuda.synchronize()
     lse_approx_ms = ev[0].elapsed_time(ev[1]) / args.steps
@@ -237,8 +264,9 @@ def main() -> int:
         "ms_per_layer": {**{s: round(stage_ms[s], 4) for s in stage_names}, "total": round(step_ms, 4)},
         "stages": stages,
         "roofline": roof,
-        "lse_approximation": {"block_scores_ms": round(lse_approx_ms, 4),
-                              "step_ms_with_it": round(step_ms - stage_ms["block_scores"] + lse_approx_ms, 4),
+        "two_stage_selection": two_stage,
+        "lse_approximation": {"block_scores_pooled_ms": round(lse_approx_ms, 4),
+                              "step_ms_with_it": round(step_ms - stage_ms["block_scores_pooled"] + lse_approx_ms, 4),
                               "note": "stage 2 with lse_mode 1 (pass 1 over K^C2, Sec. 3.4); the selection it produces "
                                       "differs from the exact one, so the headline keeps lse_mode 0"},
         "dense_same_shape": dense,
@@ -274,10 +302,10 @@ def paper_sweep(torch, m, synth, steps: int):
         row = {"seq_len": n, "blocks": total}
         for mode in (0, 1):
             gp = m.Params.make("bf16", 32, 2, 128, n_init=n_init, n_local=n_local, topk_total=total, lse_mode=mode)
-            bufs = m.sparse_prefill(gp, q, k, v, si)
+            bufs = m.sparse_prefill(gp, q, k, v, si, fused_pool=True)
             t1 = timed(lambda: m.compress_k(gp, k, si, out=(bufs["kc"], bufs["cu_seqlens_c"])))
-            t2 = timed(lambda: m.block_scores(gp, q, bufs["kc"], si, bufs["cu_seqlens_c"], out=bufs["s_shared"]))
-            t3 = timed(lambda: m.topk_blocks(gp, bufs["s_shared"], si, out=bufs["block_idx"]))
+            t2 = timed(lambda: m.block_scores_pooled(gp, q, bufs["kc"], si, bufs["cu_seqlens_c"], out=bufs["s_cmp"]))
+            t3 = timed(lambda: m.topk_pooled(gp, bufs["s_cmp"], si, out=bufs["block_idx"]))
             t4 = timed(lambda: m.sparse_attn_fwd(gp, q, k, v, bufs["block_idx"], si, out=bufs["out"], lse=bufs["lse"]))
             key = "exact" if mode == 0 else "lse_approx"
             row[key] = {"block_selection_ms": round(t1 + t2 + t3, 3), "sparse_attn_ms": round(t4, 3)}

@@ -163,6 +163,27 @@ int infllmv2_topk_blocks(const infllmv2_params *p, const float *s_shared_d, int6
                          int32_t *block_idx_d, void *stream);
 
 /*
+ * Stages 2 and 3 with the max-pooling of Eq. 6 moved into the score kernel (the fusion Sec. 3.4 names as future
+ * work): the group scores never reach memory per compressed key, only per selection block, a buffer
+ * pool_stride times smaller than S^shared, and the selection reads that.  The resulting block_idx is identical
+ * to infllmv2_block_scores followed by infllmv2_topk_blocks.
+ *   s_cmp_d        device float32 [num_kv_heads, total_tokens, row_stride], row_stride >= ceil(max len / 64).
+ *                  infllmv2_block_scores_pooled writes S^cmp[h, t, j] = max of S^shared[h, t, i] over
+ *                  i in [s*j - pad, s*j - pad + l) clipped to [0, v(t)) for every block j <= b_t whose clipped
+ *                  window is not empty, i.e. max(s*j - pad, 0) < v(t), and leaves the other entries untouched;
+ *                  infllmv2_topk_pooled reads exactly those entries and takes the others as 0.
+ *   Other arguments as for infllmv2_block_scores / infllmv2_topk_blocks.  Every pooling window is accepted; the
+ *   paper's (l = 5, s = 4, pad 0 or 1) with the paper's head shape in bfloat16 runs on the matrix cores.
+ */
+int infllmv2_block_scores_pooled(const infllmv2_params *p, const void *q_d, const float *kc_d, int64_t total_c,
+                                 const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d,
+                                 const int32_t *cu_seqlens_c_d, int32_t batch,
+                                 float *s_cmp_d, int64_t row_stride, void *stream);
+int infllmv2_topk_pooled(const infllmv2_params *p, const float *s_cmp_d, int64_t row_stride,
+                         const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
+                         int32_t *block_idx_d, void *stream);
+
+/*
  * Stage 4 -- Appendix Alg. 2: token t attends, with one softmax per query head, to the keys u <= t
  * whose block u / B is listed in block_idx[h, t, :]; O = softmax(scale * q K^T) V.
  * Sequences shorter than dense_threshold ignore block_idx and attend to every u <= t (Sec. 3.2).

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     Params,
     SeqInfo,
     block_scores,
+    block_scores_pooled,
     compress_k,
     compress_k_append,
     decode_workspace_bytes,
@@ -25,5 +26,6 @@ from .binding import (  # noqa: F401
     sparse_prefill,
     status_string,
     topk_blocks,
+    topk_pooled,
     version,
 )

@@ -67,6 +67,8 @@ _SIGNATURES = {
     "infllmv2_compress_k_append": (ctypes.c_int, [_PP, _P, _I64, _I64, _I64, _P, _I64, _P, _P, _P, _P, _I32, _P]),
     "infllmv2_block_scores": (ctypes.c_int, [_PP, _P, _P, _I64, _P, _P, _P, _I32, _P, _I64, _P]),
     "infllmv2_topk_blocks": (ctypes.c_int, [_PP, _P, _I64, _P, _P, _I32, _P, _P]),
+    "infllmv2_block_scores_pooled": (ctypes.c_int, [_PP, _P, _P, _I64, _P, _P, _P, _I32, _P, _I64, _P]),
+    "infllmv2_topk_pooled": (ctypes.c_int, [_PP, _P, _I64, _P, _P, _I32, _P, _P]),
     "infllmv2_sparse_attn_fwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _P, _I32, _P, _P, _P]),
     "infllmv2_dense_attn_fwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _I32, _P, _P, _P]),
     "infllmv2_sparse_decode": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _I64, _P, _I64, _P, _P, _I32, _P, _P, _P,
@@ -204,6 +206,34 @@ def topk_blocks(p: Params, s_shared: torch.Tensor, cu_seqlens, out: Optional[tor
     return out
 
 
+def block_scores_pooled(p: Params, q: torch.Tensor, kc: torch.Tensor, cu_seqlens, cu_seqlens_c: torch.Tensor,
+                        out: Optional[torch.Tensor] = None):
+    """Stages 2 with the max-pooling fused.  Returns S^cmp [hkv, T, row_stride >= ceil(max len / 64)] fp32; entry j of
+    a row is written iff the block's pooling window holds a visible key."""
+    cu_h, cu_d = _cu_pair(cu_seqlens)
+    batch = cu_h.numel() - 1
+    max_len = int((cu_h[1:] - cu_h[:-1]).max()) if batch else 0
+    if out is None:
+        rs = max(1, (max_len + p.block_size - 1) // p.block_size)
+        out = torch.empty((p.num_kv_heads, q.shape[0], rs), dtype=torch.float32, device=q.device)
+    st = lib().infllmv2_block_scores_pooled(ctypes.byref(p), _ptr(q), _ptr(kc), kc.shape[1], _ptr(cu_h), _ptr(cu_d),
+                                            _ptr(cu_seqlens_c), batch, _ptr(out), out.shape[2], _stream())
+    _check(st, "infllmv2_block_scores_pooled")
+    return out
+
+
+def topk_pooled(p: Params, s_cmp: torch.Tensor, cu_seqlens, out: Optional[torch.Tensor] = None):
+    """Stage 3 on pooled scores.  s_cmp [hkv, T, row_stride] -> block_idx [hkv, T, topk_total] int32."""
+    cu_h, cu_d = _cu_pair(cu_seqlens)
+    batch = cu_h.numel() - 1
+    if out is None:
+        out = torch.empty((p.num_kv_heads, s_cmp.shape[1], p.topk_total), dtype=torch.int32, device=s_cmp.device)
+    st = lib().infllmv2_topk_pooled(ctypes.byref(p), _ptr(s_cmp), s_cmp.shape[2], _ptr(cu_h), _ptr(cu_d), batch,
+                                    _ptr(out), _stream())
+    _check(st, "infllmv2_topk_pooled")
+    return out
+
+
 def sparse_attn_fwd(p: Params, q, k, v, block_idx, cu_seqlens, out=None, lse=None):
     """Stage 4.  Returns (out [T, hq, d], lse [hq, T])."""
     cu_h, cu_d = _cu_pair(cu_seqlens)
@@ -269,14 +299,21 @@ def sparse_decode(p: Params, q, k_cache, v_cache, kc_cache, ctx_lens, workspace=
     return out, lse, idx
 
 
-def sparse_prefill(p: Params, q, k, v, cu_seqlens, buffers: Optional[dict] = None):
+def sparse_prefill(p: Params, q, k, v, cu_seqlens, buffers: Optional[dict] = None, fused_pool: bool = False):
     """The four stages back to back (a convenience for tests and the benchmark; no arithmetic here).
     buffers: a dict returned by an earlier call, whose tensors are then reused (nothing is allocated).
-    Returns dict(out, lse, block_idx, s_shared, kc, cu_seqlens_c)."""
+    fused_pool: stages 2 and 3 through the pooled entry points (s_cmp instead of s_shared in the result).
+    Returns dict(out, lse, block_idx, s_shared | s_cmp, kc, cu_seqlens_c)."""
     b = buffers or {}
     si = cu_seqlens if isinstance(cu_seqlens, SeqInfo) else SeqInfo(cu_seqlens)
     kc, cu_c = compress_k(p, k, si, out=(b["kc"], b["cu_seqlens_c"]) if b else None)
-    sh = block_scores(p, q, kc, si, cu_c, out=b.get("s_shared"))
-    idx = topk_blocks(p, sh, si, out=b.get("block_idx"))
+    if fused_pool:
+        sc = block_scores_pooled(p, q, kc, si, cu_c, out=b.get("s_cmp"))
+        idx = topk_pooled(p, sc, si, out=b.get("block_idx"))
+        scores = dict(s_cmp=sc)
+    else:
+        sh = block_scores(p, q, kc, si, cu_c, out=b.get("s_shared"))
+        idx = topk_blocks(p, sh, si, out=b.get("block_idx"))
+        scores = dict(s_shared=sh)
     out, lse = sparse_attn_fwd(p, q, k, v, idx, si, out=b.get("out"), lse=b.get("lse"))
-    return dict(out=out, lse=lse, block_idx=idx, s_shared=sh, kc=kc, cu_seqlens_c=cu_c)
+    return dict(out=out, lse=lse, block_idx=idx, kc=kc, cu_seqlens_c=cu_c, **scores)

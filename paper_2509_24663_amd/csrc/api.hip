@@ -158,7 +158,7 @@ int infllmv2_block_scores(const infllmv2_params *p, const void *q_d, const float
         return INFLLMV2_ERR_INVALID_ARGUMENT;
     Launch L{p, prefill_map(p, cu_seqlens_d, cu_seqlens_c_d, batch, total, 0, 0, total_c), (hipStream_t)stream,
              max_len};
-    return launch_block_scores(L, q_d, kc_d, s_shared_d, row_stride, cu_seqlens_h);
+    return launch_block_scores(L, q_d, kc_d, s_shared_d, row_stride, cu_seqlens_h, false);
 }
 
 int infllmv2_topk_blocks(const infllmv2_params *p, const float *s_shared_d, int64_t row_stride,
@@ -174,7 +174,45 @@ int infllmv2_topk_blocks(const infllmv2_params *p, const float *s_shared_d, int6
     if (s_shared_d == nullptr || block_idx_d == nullptr) return INFLLMV2_ERR_INVALID_ARGUMENT;
     if (row_stride < num_cmp(max_len, p->cmp_len, p->cmp_stride) || row_stride < 4) return INFLLMV2_ERR_INVALID_ARGUMENT;
     Launch L{p, prefill_map(p, cu_seqlens_d, nullptr, batch, total, 0, 0, 0), (hipStream_t)stream, max_len};
-    return launch_topk(L, s_shared_d, row_stride, block_idx_d);
+    return launch_topk(L, s_shared_d, row_stride, block_idx_d, false);
+}
+
+// number of selection blocks of an n-token sequence
+static inline int num_blocks(int n) { return (n + kBlock - 1) / kBlock; }
+
+int infllmv2_block_scores_pooled(const infllmv2_params *p, const void *q_d, const float *kc_d, int64_t total_c,
+                                 const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d,
+                                 const int32_t *cu_seqlens_c_d, int32_t batch,
+                                 float *s_cmp_d, int64_t row_stride, void *stream) {
+    int st = check_params(p);
+    if (st) return st;
+    int64_t total;
+    int32_t max_len;
+    st = check_cu(cu_seqlens_h, cu_seqlens_d, batch, &total, &max_len);
+    if (st) return st;
+    if (total == 0) return INFLLMV2_OK;
+    if (q_d == nullptr || kc_d == nullptr || cu_seqlens_c_d == nullptr || s_cmp_d == nullptr)
+        return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if (row_stride < num_blocks(max_len)) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    Launch L{p, prefill_map(p, cu_seqlens_d, cu_seqlens_c_d, batch, total, 0, 0, total_c), (hipStream_t)stream,
+             max_len};
+    return launch_block_scores(L, q_d, kc_d, s_cmp_d, row_stride, cu_seqlens_h, true);
+}
+
+int infllmv2_topk_pooled(const infllmv2_params *p, const float *s_cmp_d, int64_t row_stride,
+                         const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
+                         int32_t *block_idx_d, void *stream) {
+    int st = check_params(p);
+    if (st) return st;
+    int64_t total;
+    int32_t max_len;
+    st = check_cu(cu_seqlens_h, cu_seqlens_d, batch, &total, &max_len);
+    if (st) return st;
+    if (total == 0) return INFLLMV2_OK;
+    if (s_cmp_d == nullptr || block_idx_d == nullptr) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if (row_stride < num_blocks(max_len)) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    Launch L{p, prefill_map(p, cu_seqlens_d, nullptr, batch, total, 0, 0, 0), (hipStream_t)stream, max_len};
+    return launch_topk(L, s_cmp_d, row_stride, block_idx_d, true);
 }
 
 static int attn_common(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
@@ -279,9 +317,9 @@ int infllmv2_sparse_decode(const infllmv2_params *p, const void *q_d, const void
     m.kc_total_c = 0;
     m.kc_head_stride = kc_head_stride;
     Launch L{p, m, (hipStream_t)stream, max_ctx};
-    st = launch_block_scores(L, q_d, kc_cache_d, scores, (int64_t)rs, nullptr);
+    st = launch_block_scores(L, q_d, kc_cache_d, scores, (int64_t)rs, nullptr, false);
     if (st) return st;
-    st = launch_topk(L, scores, (int64_t)rs, idx);
+    st = launch_topk(L, scores, (int64_t)rs, idx, false);
     if (st) return st;
     return launch_attn_generic(L, q_d, k_cache_d, v_cache_d, idx, p->dense_threshold, out_d, lse_d);
 }

@@ -8,6 +8,8 @@
 // the four disjoint K^{C1} windows 4i + m l_C1 / s_C1, m = 0..3, so it is formed on the fly from K^{C1} and
 // needs no input of its own.  A row that sees no coarse key gets all-zero scores.
 
+#include <type_traits>
+
 #include "common.h"
 
 namespace ifv2 {
@@ -19,7 +21,8 @@ namespace ifv2 {
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
 block_scores_generic(const T *__restrict__ q, const float *__restrict__ kc, RowMap map, int hq, int lc, int sc,
-                     float scale, int dense_below, int lse_mode, float *__restrict__ s_shared, int64_t row_stride) {
+                     float scale, int dense_below, int lse_mode, float *__restrict__ s_shared, int64_t row_stride,
+                     PoolArgs pool) {
     const int row = blockIdx.x, h = blockIdx.y;
     const int G = hq / map.num_kv_heads;
     const RowLoc loc = locate(map, row);
@@ -30,7 +33,11 @@ block_scores_generic(const T *__restrict__ q, const float *__restrict__ kc, RowM
     const int v1 = lse_mode == 0 ? v : min(visible_cmp(loc.pos, 4 * lc, 4 * sc), num_cmp(loc.len, 4 * lc, 4 * sc));
     if (v1 == 0) {                                    // no coarse key visible yet: all-zero scores
         float *out0 = s_shared + head_row(map, h, row) * row_stride;
-        for (int i = threadIdx.x; i < v; i += 256) out0[i] = 0.f;
+        if (pool.on) {
+            for (int j = threadIdx.x; j <= loc.pos / kBlock && max(pool.stride * j - pool.pad, 0) < v; j += 256) out0[j] = 0.f;
+        } else {
+            for (int i = threadIdx.x; i < v; i += 256) out0[i] = 0.f;
+        }
         return;
     }
     __shared__ float qs[kMaxGroup][D];
@@ -93,7 +100,7 @@ block_scores_generic(const T *__restrict__ q, const float *__restrict__ kc, RowM
     __syncthreads();
     // pass 2: recompute, normalise, sum the group
     float *out = s_shared + head_row(map, h, row) * row_stride;
-    for (int i = tid; i < v; i += 256) {
+    auto score = [&](int i) -> float {
         float z[kMaxGroup];
 #pragma unroll
         for (int g = 0; g < kMaxGroup; ++g) z[g] = 0.f;
@@ -108,17 +115,31 @@ block_scores_generic(const T *__restrict__ q, const float *__restrict__ kc, RowM
 #pragma unroll
         for (int g = 0; g < kMaxGroup; ++g)
             if (g < G) s += __expf(z[g] - lse_s[g]);
-        out[i] = s;
+        return s;
+    };
+    if (pool.on) {
+        // one thread per selection block up to the query's own: the max over its pooling window (Eq. 6), clipped
+        // to the visible keys
+        for (int j = tid; j <= loc.pos / kBlock && max(pool.stride * j - pool.pad, 0) < v; j += 256) {
+            const int lo = pool.stride * j - pool.pad;
+            float m = 0.f;
+            for (int u = 0; u < pool.len; ++u)
+                if (lo + u >= 0 && lo + u < v) m = fmaxf(m, score(lo + u));
+            out[j] = m;
+        }
+    } else {
+        for (int i = tid; i < v; i += 256) out[i] = score(i);
     }
 }
 
 template <typename T, int D>
-static int launch_generic(const Launch &L, const void *q, const float *kc, float *s_shared, int64_t row_stride) {
+static int launch_generic(const Launch &L, const void *q, const float *kc, float *s_shared, int64_t row_stride,
+                          const PoolArgs &pool) {
     dim3 grid(L.map.total_rows, L.p->num_kv_heads);
     if (grid.x == 0) return INFLLMV2_OK;
     hipLaunchKernelGGL((block_scores_generic<T, D>), grid, dim3(256), 0, L.stream, (const T *)q, kc, L.map,
                        L.p->num_q_heads, L.p->cmp_len, L.p->cmp_stride, L.p->softmax_scale, L.p->dense_threshold,
-                       L.p->lse_mode, s_shared, row_stride);
+                       L.p->lse_mode, s_shared, row_stride, pool);
     return hip_status(hipGetLastError());
 }
 
@@ -173,6 +194,15 @@ struct ScoreArgs {
 };
 
 __device__ inline float s_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// data-parallel-primitive moves of a float: lane i receives the value of another lane without touching LDS
+template <int CTRL>
+__device__ inline float dpp_move(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+constexpr int DPP_QUAD_SWAP1 = 0xB1;   // quad_perm [1,0,3,2]
+constexpr int DPP_QUAD_SWAP2 = 0x4E;   // quad_perm [2,3,0,1]
+constexpr int DPP_WAVE_SHR1 = 0x138;   // lane i <- lane i - 1 (lane 0 <- 0)
 
 template <int NW, int TPW>
 struct ScoreKernel {
@@ -279,6 +309,9 @@ struct ScoreKernel {
         }
     }
 
+    // POOL < 0: one output per compressed key.  POOL = 0 / 1: one output per selection block, the max over the
+    // pooling window [4j - POOL, 4j - POOL + 5) of Eq. 6 (see vec2 below).
+    template <int POOL>
     __device__ static void run(const ScoreArgs &a, int num_tiles) {
         extern __shared__ __attribute__((aligned(16))) _Float16 smem[];     // two tiles (double buffer)
         __shared__ int s_seq, s_tile, s_flag, s_shift[2];
@@ -480,23 +513,61 @@ struct ScoreKernel {
         for (int i = 0; i < TPW; ++i)
 #pragma unroll
             for (int r = 0; r < 4; ++r) nlse[i][r] = -lse2[i][r];
-        auto vec2 = [&](int kt) {
+        // Fused pooling (POOL >= 0).  After the butterfly lane x of the wave holds the group sum of key kbase + x,
+        // so the four keys 4m .. 4m + 3 of the tile sit in one lane quad and their max takes two quad swaps.  The
+        // fifth key of a window lies one lane below the quad (POOL = 1: window = key 4m - 1 and quad m, block
+        // 16 kt + m) or is the first lane of the next quad (POOL = 0: window = quad m - 1 and key 4m, block
+        // 16 kt + m - 1): either way lane 4m combines its own value with one shifted up by a lane, and what
+        // lane 0 needs from the previous tile of the same token is carried in a scalar.
+        float carry[TPW];
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) carry[i] = 0.f;
+        float *const out_w = a.out + ((int64_t)h * a.map.total_rows + row0 + w * TPW) * a.row_stride;
+        auto vec2_body = [&](int kt, auto edge_c) {
+            constexpr bool edge_tile = decltype(edge_c)::value;   // the tile reaches past some token's visible keys
             const int kbase = kt * kBlock;
+            const int jb = kt * (kBlock / 4) + (lane >> 2) - (POOL > 0 ? 0 : 1);     // the block lane 4m completes
+            const bool writer = (lane & 3) == 0 && jb >= 0;
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
                 float s[4];
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt)
                     s[nt] = (s_exp2(acc[i][nt][0]) + s_exp2(acc[i][nt][1])) + (s_exp2(acc[i][nt][2]) + s_exp2(acc[i][nt][3]));
-                // butterfly over the four lane groups: afterwards lane (n16, g) holds n-tile 2*(g&1) + (g>>1)
-                const bool odd = g & 1, up = g & 2;
-                const float a0 = (odd ? s[2] : s[0]) + __shfl_xor(odd ? s[0] : s[2], 16);
-                const float a1 = (odd ? s[3] : s[1]) + __shfl_xor(odd ? s[1] : s[3], 16);
-                const float f = (up ? a1 : a0) + __shfl_xor(up ? a0 : a1, 32);
-                const int key = kbase + (2 * (g & 1) + (g >> 1)) * 16 + n16;
-                if (key < vis[i])
-                    a.out[((int64_t)h * a.map.total_rows + row0 + w * TPW + i) * a.row_stride + key] = f;
+                // butterfly over the four lane groups: afterwards lane (n16, g) holds n-tile g, i.e. key kbase + lane
+                const bool hi = g & 2, odd = g & 1;
+                const float a0 = (hi ? s[2] : s[0]) + __shfl_xor(hi ? s[0] : s[2], 32);
+                const float a1 = (hi ? s[3] : s[1]) + __shfl_xor(hi ? s[1] : s[3], 32);
+                const float f = (odd ? a1 : a0) + __shfl_xor(odd ? a0 : a1, 16);
+                const int key = kbase + lane;
+                if (POOL < 0) {
+                    if (key < vis[i]) out_w[i * a.row_stride + key] = f;
+                } else {
+                    // scores are >= 0, so an invisible key counts as 0
+                    const float fz = edge_tile && key >= vis[i] ? 0.f : f;
+                    float qm = fmaxf(fz, dpp_move<DPP_QUAD_SWAP1>(fz));
+                    qm = fmaxf(qm, dpp_move<DPP_QUAD_SWAP2>(qm));
+                    const float shifted_src = POOL ? fz : qm, own = POOL ? qm : fz;
+                    float below = dpp_move<DPP_WAVE_SHR1>(shifted_src);
+                    if (lane == 0) below = carry[i];
+                    carry[i] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(shifted_src), 63));
+                    const bool has_visible_key = !edge_tile || max(4 * jb - POOL, 0) < vis[i];
+                    if (writer && has_visible_key) out_w[i * a.row_stride + jb] = fmaxf(below, own);
+                }
             }
+        };
+        auto vec2 = [&](int kt) {
+            // only tiles that reach past the visible prefix of one of the wave's tokens need per-lane checks
+            if (POOL < 0 || kt * kBlock + kBlock > vis_min) vec2_body(kt, std::true_type{});
+            else vec2_body(kt, std::false_type{});
+        };
+        // the block whose window starts in the last tile but would end in the next one
+        auto flush_pool = [&]() {
+            if (POOL < 0) return;
+            const int jb = nkt * (kBlock / 4) - (POOL ? 0 : 1);
+#pragma unroll
+            for (int i = 0; i < TPW; ++i)
+                if (lane == 0 && max(4 * jb - POOL, 0) < vis[i]) out_w[i * a.row_stride + jb] = carry[i];
         };
         load_tile(kcb, 0, nc, tid, pf);
         stage_tile(smem, tid, pf, &s_flag, &s_shift[0], cm, ke);
@@ -509,15 +580,16 @@ struct ScoreKernel {
             else __syncthreads();
         }
         if (late) vec2(nkt - 1);
+        flush_pool();
     }
 };
 
-template <int NW, int TPW>
+template <int NW, int TPW, int POOL>
 __global__ void __launch_bounds__(NW * 64) block_scores_mfma_kernel(ScoreArgs a, int num_tiles) {
-    ScoreKernel<NW, TPW>::run(a, num_tiles);
+    ScoreKernel<NW, TPW>::template run<POOL>(a, num_tiles);
 }
 
-template <int NW, int TPW>
+template <int NW, int TPW, int POOL>
 int launch_scores_mfma(const Launch &L, const ScoreArgs &a, const int32_t *cu_h) {
     constexpr int T = NW * TPW;
     int64_t tiles = 0;
@@ -525,26 +597,30 @@ int launch_scores_mfma(const Launch &L, const ScoreArgs &a, const int32_t *cu_h)
     if (tiles == 0) return INFLLMV2_OK;
     const size_t lds = (size_t)2 * S_TILE * sizeof(_Float16);
     dim3 grid((unsigned)tiles, L.p->num_kv_heads);
-    hipLaunchKernelGGL((block_scores_mfma_kernel<NW, TPW>), grid, dim3(NW * 64), lds, L.stream, a, (int)tiles);
+    hipLaunchKernelGGL((block_scores_mfma_kernel<NW, TPW, POOL>), grid, dim3(NW * 64), lds, L.stream, a, (int)tiles);
     return hip_status(hipGetLastError());
 }
 
 }  // namespace
 
 int launch_block_scores(const Launch &L, const void *q, const float *kc, float *s_shared, int64_t row_stride,
-                        const int32_t *cu_h) {
+                        const int32_t *cu_h, bool pooled) {
     const bool bf = L.p->dtype == INFLLMV2_BF16;
+    const PoolArgs pool{pooled ? 1 : 0, L.p->pool_len, L.p->pool_stride, L.p->pool_pad};
+    // the tiled kernel pools on chip only for the paper's window (l = 5, s = 4), unshifted or shifted by one
+    const bool pool_ok = !pooled || (pool.len == 5 && pool.stride == 4 && (pool.pad == 0 || pool.pad == 1));
     if (bf && cu_h != nullptr && L.map.ctx == nullptr && L.p->head_dim == SD &&
-        L.p->num_q_heads / L.p->num_kv_heads == SG && (((uintptr_t)q | (uintptr_t)kc) & 15) == 0) {
+        L.p->num_q_heads / L.p->num_kv_heads == SG && (((uintptr_t)q | (uintptr_t)kc) & 15) == 0 && pool_ok) {
         ScoreArgs a{(const uint16_t *)q, kc, s_shared, L.map, L.p->num_q_heads, L.p->cmp_len, L.p->cmp_stride,
                     L.p->dense_threshold, L.p->lse_mode, L.p->softmax_scale, row_stride};
-        return launch_scores_mfma<8, 4>(L, a, cu_h);
+        if (!pooled) return launch_scores_mfma<8, 4, -1>(L, a, cu_h);
+        return pool.pad == 0 ? launch_scores_mfma<8, 4, 0>(L, a, cu_h) : launch_scores_mfma<8, 4, 1>(L, a, cu_h);
     }
     if (L.p->head_dim == 128)
-        return bf ? launch_generic<bf16_t, 128>(L, q, kc, s_shared, row_stride)
-                  : launch_generic<float, 128>(L, q, kc, s_shared, row_stride);
-    return bf ? launch_generic<bf16_t, 64>(L, q, kc, s_shared, row_stride)
-              : launch_generic<float, 64>(L, q, kc, s_shared, row_stride);
+        return bf ? launch_generic<bf16_t, 128>(L, q, kc, s_shared, row_stride, pool)
+                  : launch_generic<float, 128>(L, q, kc, s_shared, row_stride, pool);
+    return bf ? launch_generic<bf16_t, 64>(L, q, kc, s_shared, row_stride, pool)
+              : launch_generic<float, 64>(L, q, kc, s_shared, row_stride, pool);
 }
 
 }  // namespace ifv2

@@ -52,6 +52,11 @@ struct RowMap {
     int64_t kc_head_stride;   // decode: elements between (b,h) planes of the kc cache
 };
 
+// Max-pooling of Eq. 6 when it is fused into the score kernels (on == 0: scores per compressed key)
+struct PoolArgs {
+    int on, len, stride, pad;
+};
+
 struct RowLoc {
     int32_t seq, pos, len;    // sequence, position of the query inside it, sequence length
     int64_t kv_base;          // element offset of (token 0, head 0) of that sequence in K / V
@@ -126,9 +131,12 @@ int launch_compress_k_append(const infllmv2_params *p, const void *k, int64_t kv
                              int64_t kv_tok_stride, float *kc, int64_t kc_head_stride, const int32_t *prev_d,
                              const int32_t *ctx_d, int batch, int max_new, hipStream_t stream);
 // cu_h: host cu_seqlens for the tiled kernels' grid (nullptr: single-row / decode form)
-int launch_block_scores(const Launch &L, const void *q, const float *kc, float *s_shared, int64_t row_stride,
-                        const int32_t *cu_h);
-int launch_topk(const Launch &L, const float *s_shared, int64_t row_stride, int32_t *idx);
+// pooled: the output holds one value per selection block (Eq. 6 applied on chip) instead of one per compressed
+// key; entry j of a row is written iff its pooling window has a visible key, max(stride j - pad, 0) < v(t)
+int launch_block_scores(const Launch &L, const void *q, const float *kc, float *s_out, int64_t row_stride,
+                        const int32_t *cu_h, bool pooled);
+// pooled: s_in holds block scores as written by launch_block_scores(pooled = true)
+int launch_topk(const Launch &L, const float *s_in, int64_t row_stride, int32_t *idx, bool pooled);
 // idx == nullptr: dense for every sequence; dense_below: sequences shorter than this are dense anyway
 int launch_attn(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
                 int dense_below, void *out, float *lse, const int32_t *cu_h);

@@ -39,9 +39,19 @@ __device__ inline void descend(const uint32_t (&keys)[NK], int kr, uint32_t &p, 
 // srow: the row's group scores (global or LDS), t: query position, out: topk_total entries.
 // NCH > 0: pooled keys live in NCH registers per lane (blocks j = c*64 + lane, needs nblk <= 64*NCH);
 // NCH == 0: they live in lk[] (LDS, at least 64*ceil(nblk/64) words owned by this wave).
-// FAST: the pooling is the paper's (l = 5, s = 4, no shift) and srow is 16-byte aligned: vector loads.
-template <int NCH, bool FAST = false>
-__device__ inline void topk_row(const float *srow, int t, const TopkArgs &a, int32_t *out, uint32_t *lk, int lane) {
+// MODE: where the pooled scores come from.
+enum : int {
+    TOPK_POOL_ANY = 0,    // srow holds scores per compressed key; any pooling window
+    TOPK_POOL_FAST = 1,   // the same for the paper's window (l = 5, s = 4, no shift), srow 16-byte aligned: vector loads
+    TOPK_POOLED = 2,      // srow already holds one score per block (the score kernel pooled on chip); entry j is
+                          // defined iff its window has a visible key, max(stride j - pad, 0) < v
+};
+// cand: kCandPerWave (key, block) pairs of LDS owned by this wave (used when NCH > kCandChunks).
+constexpr int kCandChunks = 4, kCandPerWave = 64 * kCandChunks;
+constexpr int kBoundBits = 12;          // leading key bits (below the sign) resolved on the lane maxima
+template <int NCH, int MODE = TOPK_POOL_ANY>
+__device__ inline void topk_row(const float *srow, int t, const TopkArgs &a, int32_t *out, uint32_t *lk, uint2 *cand,
+                                int lane) {
     const int bt = t / kBlock, nblk = bt + 1;
     const int v = visible_cmp(t, a.lc, a.sc);
     const int nch = (nblk + 63) >> 6;
@@ -71,6 +81,7 @@ __device__ inline void topk_row(const float *srow, int t, const TopkArgs &a, int
         const bool forced = j < f_init || j >= f_lo;
         if (forced) return 0u;
         const int lo = a.pool_stride * j - a.pool_pad;
+        if (MODE == TOPK_POOLED) return max(lo, 0) < v ? __float_as_uint(srow[j]) : 0u;
         float m = 0.f;
         for (int u = 0; u < a.pool_len; ++u) {
             int i = lo + u;
@@ -78,7 +89,7 @@ __device__ inline void topk_row(const float *srow, int t, const TopkArgs &a, int
         }
         return __float_as_uint(m);
     };
-    if (NCH > 0 && FAST) {
+    if (NCH > 0 && MODE == TOPK_POOL_FAST) {
         // pool window = [4j, 4j+5): one aligned 16-byte load plus one scalar per block, all issued up front
         // with addresses clamped into the visible prefix (so nothing branches and nothing is read out of
         // bounds); invisible or forced entries are masked afterwards.
@@ -106,6 +117,18 @@ __device__ inline void topk_row(const float *srow, int t, const TopkArgs &a, int
                 keys[c] = dead ? 0u : __float_as_uint(m);
             }
         }
+    } else if (NCH > 0 && MODE == TOPK_POOLED) {
+        // all loads first, addresses clamped into the row (entry bt always exists); undefined, forced and
+        // out-of-range entries are masked afterwards
+        float x[NCH > 0 ? NCH : 1];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) x[c] = srow[min(c * 64 + lane, bt)];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int j = c * 64 + lane;
+            const bool dead = j >= nblk || j < f_init || j >= f_lo || !(max(a.pool_stride * j - a.pool_pad, 0) < v);
+            keys[c] = dead ? 0u : __float_as_uint(x[c]);
+        }
     } else if (NCH > 0) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
@@ -116,6 +139,72 @@ __device__ inline void topk_row(const float *srow, int t, const TopkArgs &a, int
     // a lane's slot is "live" if it is a real, non-forced block
     auto live = [&](int j) -> bool { return j < nblk && !(j < f_init || j >= f_lo); };
     auto key_at = [&](int c) -> uint32_t { return NCH > 0 ? keys[c] : lk[c * 64 + lane]; };
+
+    // ---- long rows: shrink the problem to a few hundred candidates first.
+    // Each lane's largest key is one element of the row, so the kr-th largest of the 64 lane maxima is a lower
+    // bound of the kr-th largest key (kr <= 64).  Its leading bits, found by a descent over that single register,
+    // give a bound L that typically leaves 100-250 keys >= L out of thousands.  Those are compacted, in
+    // ascending block order, into LDS; threshold search and emission then run over at most kCandChunks
+    // registers instead of NCH.  Rows where that does not work out (too many candidates, L = 0, kr > 64) take
+    // the general path below.
+    if (NCH > kCandChunks && kr > 0 && kr <= 64 && nch > kCandChunks) {
+        uint32_t lm = 0;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) lm = max(lm, keys[c]);
+        uint32_t L = 0;
+        for (int b = 30; b > 30 - kBoundBits; --b) {
+            const uint32_t c2 = L | (1u << b);
+            if (__popcll(__ballot(lm >= c2)) >= kr) L = c2;
+        }
+        if (L != 0) {
+            const uint64_t below = (1ull << lane) - 1ull;
+            int total = 0;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const bool in = keys[c] >= L;                    // dead slots hold 0 < L
+                const uint64_t bal = __ballot(in);
+                const int pos = total + __popcll(bal & below);
+                if (in && pos < kCandPerWave) cand[pos] = make_uint2(keys[c], (uint32_t)(c * 64 + lane));
+                total += __popcll(bal);
+            }
+            if (total <= kCandPerWave) {
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                uint32_t ck[kCandChunks], cj[kCandChunks];
+#pragma unroll
+                for (int u = 0; u < kCandChunks; ++u) {
+                    const uint2 e = u * 64 + lane < total ? cand[u * 64 + lane] : make_uint2(0u, 0u);
+                    ck[u] = e.x;
+                    cj[u] = e.y;
+                }
+                // total >= kr keys are >= L, so the kr-th largest key of the row is among the candidates
+                uint32_t p = 0;
+                bool exact = false;
+                int gt = 0;
+                if (total <= 128) descend<2>(ck, kr, p, exact, gt);
+                else descend<kCandChunks>(ck, kr, p, exact, gt);
+                const uint32_t above = exact ? p - 1 : p;        // keys > above are in
+                const int need_eq = exact ? 0 : kr - gt;         // plus the first need_eq keys == p
+                // forced initial blocks, the selected candidates (ascending), forced local blocks
+                for (int j = lane; j < f_init; j += 64) out[j] = j;
+                int written = f_init, eq_seen = 0;
+#pragma unroll
+                for (int u = 0; u < kCandChunks; ++u) {
+                    const bool is_eq = need_eq > 0 && ck[u] == p;   // padding holds 0 < L <= p
+                    const uint64_t eqb = __ballot(is_eq);
+                    const bool sel = ck[u] > above || (is_eq && eq_seen + __popcll(eqb & below) < need_eq);
+                    const uint64_t sb = __ballot(sel);
+                    if (sel) out[written + __popcll(sb & below)] = (int32_t)cj[u];
+                    written += __popcll(sb);
+                    eq_seen += __popcll(eqb);
+                }
+                for (int j = f_lo + lane; j <= bt; j += 64) out[written + j - f_lo] = j;
+                written += bt - f_lo + 1;
+                for (int j = written + lane; j < a.topk_total; j += 64) out[j] = -1;
+                return;
+            }
+        }
+    }
 
     // ---- k-th largest by bit descent (kr >= 0; kr == 0 keeps only the forced blocks).
     // Dead slots (forced blocks, blocks past the query) hold key 0 and every candidate is >= 1, so they are

@@ -105,3 +105,23 @@ def test_validation_errors_before_launch(m):
                                         ctx.ctypes.data_as(ctypes.c_void_p), ctypes.c_void_p(256), 2, None,
                                         ctypes.c_void_p(256), None, ctypes.c_void_p(256), 1 << 30, None)
     assert st == INVALID
+
+
+def test_pooled_entry_points_validate_on_the_host(m):
+    """The fused-pooling forms of stages 2 and 3: row stride counted in selection blocks, null pointers,
+    empty batches -- all decided before anything is launched."""
+    INVALID = -1
+    L = m.lib()
+    p = m.Params.make("bf16", 32, 2, 128)
+    cu = np.array([0, 1000], dtype=np.int32)                         # 16 blocks
+    cu_p, one = cu.ctypes.data_as(ctypes.c_void_p), ctypes.c_void_p(256)
+    assert L.infllmv2_block_scores_pooled(ctypes.byref(p), one, one, 61, cu_p, one, one, 1, one, 15, None) == INVALID
+    assert L.infllmv2_block_scores_pooled(ctypes.byref(p), None, one, 61, cu_p, one, one, 1, one, 16, None) == INVALID
+    assert L.infllmv2_block_scores_pooled(ctypes.byref(p), one, one, 61, cu_p, one, one, 1, None, 16, None) == INVALID
+    assert L.infllmv2_topk_pooled(ctypes.byref(p), one, 15, cu_p, one, 1, one, None) == INVALID
+    assert L.infllmv2_topk_pooled(ctypes.byref(p), None, 16, cu_p, one, 1, one, None) == INVALID
+    empty = np.array([0, 0], dtype=np.int32).ctypes.data_as(ctypes.c_void_p)
+    assert L.infllmv2_block_scores_pooled(ctypes.byref(p), None, None, 0, empty, one, None, 1, None, 0, None) == 0
+    assert L.infllmv2_topk_pooled(ctypes.byref(p), None, 0, empty, one, 1, None, None) == 0
+    bad = m.Params.make("bf16", 32, 2, 128, pool_stride=0)
+    assert L.infllmv2_block_scores_pooled(ctypes.byref(bad), one, one, 61, cu_p, one, one, 1, one, 16, None) == INVALID

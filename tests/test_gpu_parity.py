@@ -438,3 +438,124 @@ def test_determinism(m, oracle):
     torch.cuda.synchronize()
     for key in ("out", "lse", "block_idx", "kc"):
         assert torch.equal(a[key], b[key]), key
+
+
+# ------------------------------------------------------------------------ max-pooling fused into the score kernel
+def _check_fused_pool(m, oracle, w, gp, op, dtype):
+    """The pooled entry points against (a) the two-stage GPU path, bit for bit, and (b) the oracle's Eq. 6."""
+    cu = w["cu_seqlens"]
+    T, hq, d = w["q"].shape
+    hkv = w["k"].shape[0]
+    G = hq // hkv
+    q, k, v = (to_dev(w[x], dtype) for x in ("q", "k", "v"))
+    two = m.sparse_prefill(gp, q, k, v, cu)
+    # poison the pooled buffer: entries the kernel must not define stay NaN and must not influence the selection
+    si = m.SeqInfo(cu)
+    kc, cu_c = two["kc"], two["cu_seqlens_c"]
+    max_len = int(np.diff(cu).max()) if len(cu) > 1 else 0
+    nb = max(1, -(-max_len // 64))
+    s_cmp = torch.full((hkv, T, nb + 3), float("nan"), dtype=torch.float32, device="cuda")
+    m.block_scores_pooled(gp, q, kc, si, cu_c, out=s_cmp)
+    idx_f = m.topk_pooled(gp, s_cmp, si)
+    torch.cuda.synchronize()
+    sh_g, sc_g = to_np(two["s_shared"]), to_np(s_cmp)
+    for s in range(len(cu) - 1):
+        a, b = int(cu[s]), int(cu[s + 1])
+        if b - a < op.dense_threshold or b == a:
+            assert np.all(np.isnan(sc_g[:, a:b]))
+            continue
+        pos = np.arange(b - a, dtype=np.int32)
+        for h in range(hkv):
+            kc_o = oracle.compress_k(w["k"][h, a:b], op)
+            sh_o = oracle.block_scores(w["q"][a:b, h * G:(h + 1) * G], pos, kc_o, op,
+                                       kc2=oracle.compress_k(w["k"][h, a:b], op, level=2) if op.lse_mode else None)
+            _, cmp_o = oracle.topk_blocks(sh_o, pos, op, return_cmp=True)
+            for t in range(b - a):
+                vis = oracle.visible_cmp(t, op)
+                row = sc_g[h, a + t]
+                defined = np.array([j <= t // 64 and max(op.pool_stride * j - op.pool_pad, 0) < vis
+                                    for j in range(row.shape[0])])
+                assert np.all(np.isnan(row[~defined])), (s, h, t)
+                js = np.nonzero(defined)[0]
+                if len(js) == 0:
+                    continue
+                # (a) exactly the max over the window of the scores the unfused kernel stores
+                want = np.array([sh_g[h, a + t, max(op.pool_stride * j - op.pool_pad, 0):
+                                      min(op.pool_stride * j - op.pool_pad + op.pool_len, vis)].max() for j in js])
+                np.testing.assert_array_equal(row[js], want)
+                # (b) the oracle's pooled scores
+                np.testing.assert_allclose(row[js], cmp_o[t, js], rtol=5e-4, atol=1e-7)
+    np.testing.assert_array_equal(to_np(idx_f), to_np(two["block_idx"]))
+
+
+@pytest.mark.parametrize("pool_pad", [0, 1])
+@pytest.mark.parametrize("lse_mode", [0, 1])
+def test_fused_pooling_paper_head_shape(m, oracle, pool_pad, lse_mode):
+    """Matrix-core score kernel with Eq. 6 fused: several key tiles, ragged tails, lengths at tile boundaries
+    (1055 = 64 visible keys + 31, 2079 = 128 + 31 for the last token), a length below the first window."""
+    lens = [1055, 20, 2079, 700, 1500]
+    w = synth.make_varlen(lens, 32, 2, 128, seed=4242 + pool_pad + 2 * lse_mode, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=2, topk_total=7, pool_pad=pool_pad, lse_mode=lse_mode)
+    _check_fused_pool(m, oracle, w, gp, op, "bf16")
+
+
+@pytest.mark.parametrize("pool", [(5, 4, 0), (5, 4, 1), (3, 2, 0), (8, 4, 2), (1, 1, 0)])
+def test_fused_pooling_generic_kernel(m, oracle, pool):
+    """fp32 / small heads take the one-row-per-workgroup kernel, which accepts any pooling window."""
+    pl, ps, pad = pool
+    w = synth.make_varlen([900, 31, 333], 4, 2, 64, seed=977 + pl, dtype="fp32")
+    gp, op = _params(m, oracle, "fp32", 4, 2, 64, n_init=1, n_local=1, topk_total=5, pool_len=pl, pool_stride=ps,
+                     pool_pad=pad)
+    _check_fused_pool(m, oracle, w, gp, op, "fp32")
+
+
+def test_fused_pooling_with_dense_switch_and_full_path(m, oracle):
+    """Sequences below the threshold get no pooled scores and an all -1 list; sparse_prefill(fused_pool=True)
+    returns the same output as the two-stage path."""
+    lens = [300, 1200, 100]
+    w = synth.make_varlen(lens, 32, 2, 128, seed=31, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=2, topk_total=6, dense_threshold=512)
+    _check_fused_pool(m, oracle, w, gp, op, "bf16")
+    q, k, v = (to_dev(w[x], "bf16") for x in ("q", "k", "v"))
+    a = m.sparse_prefill(gp, q, k, v, w["cu_seqlens"])
+    b = m.sparse_prefill(gp, q, k, v, w["cu_seqlens"], fused_pool=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a["block_idx"], b["block_idx"]) and torch.equal(a["out"], b["out"]) and torch.equal(a["lse"], b["lse"])
+
+
+# ------------------------------------------------------------------------------- stage 3 alone on long rows
+@pytest.mark.parametrize("kind", ["continuous", "quantised", "mostly_zero", "one_level"])
+@pytest.mark.parametrize("topk_total", [64, 96, 200])
+def test_topk_long_rows_bit_exact(m, oracle, kind, topk_total):
+    """Rows of more than 256 blocks narrow the search to a candidate set first; rows where that cannot work (mass
+    ties, too few positive scores, more than 64 to pick) take the general path.  Both must give the oracle's list
+    bit for bit, from scores per compressed key and from pooled scores."""
+    n, hkv = 21000, 1
+    rng = np.random.default_rng(500 + len(kind) + topk_total)
+    gp, op = _params(m, oracle, "bf16", 16, hkv, 128, n_init=1, n_local=8 if topk_total != 96 else 32,
+                     topk_total=topk_total)
+    nc = oracle.num_cmp(n, op)
+    rs = (nc + 3) // 4 * 4
+    s = rng.random((hkv, n, rs), dtype=np.float32)
+    if kind == "quantised":
+        s = np.floor(s * 8) / 8
+    elif kind == "mostly_zero":
+        s = np.where(rng.random(s.shape) < 0.004, s, 0).astype(np.float32)
+    elif kind == "one_level":
+        s[:] = 0.25
+    s_d = torch.from_numpy(s).cuda()
+    si = m.SeqInfo([0, n])
+    idx_g = to_np(m.topk_blocks(gp, s_d, si))
+    rows = np.unique(np.concatenate([np.arange(0, n, 97), np.arange(16000, 17000), np.arange(n - 300, n)])).astype(np.int32)
+    idx_o, cmp_o = oracle.topk_blocks(s[0, rows], rows, op, return_cmp=True)
+    np.testing.assert_array_equal(idx_g[0, rows], idx_o)
+    # the same selection from pooled scores: S^cmp as the oracle computes it, NaN where undefined
+    nb = -(-n // 64)
+    sc = np.full((hkv, n, nb), np.nan, dtype=np.float32)
+    for r, t in enumerate(rows):
+        vis = oracle.visible_cmp(int(t), op)
+        for j in range(t // 64 + 1):
+            if max(4 * j, 0) < vis:
+                sc[0, t, j] = cmp_o[r, j]
+    idx_p = to_np(m.topk_pooled(gp, torch.from_numpy(sc).cuda(), si))
+    np.testing.assert_array_equal(idx_p[0, rows], idx_o)
