@@ -434,7 +434,11 @@ struct ScoreKernel {
         const bool late = w >= NW / 2;
 
         // ------------------------------------------------ pass 1: log-sum-exp of every (token, head) row
-        auto vec1 = [&](int kt) {
+        // First attempt without a running reference: sum 2^y as it is.  For ordinary activations |y| stays far
+        // below fp32's exponent range, and the max tracking (a fifth of the vector work of this pass) is saved.
+        // If any row's sum then overflowed, vanished or is NaN, the workgroup repeats the pass with the reference.
+        auto vec1 = [&](int kt, auto tracked_c) {
+            constexpr bool tracked = decltype(tracked_c)::value;
             const int kbase = kt * kBlock;
             const bool edge_tile = kbase + kBlock > vis1_min;
 #pragma unroll
@@ -445,19 +449,21 @@ struct ScoreKernel {
                         if (kbase + nt * 16 + n16 >= vis1[i]) acc[i][nt] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
                 }
                 // The reference moves only when an exponent exceeds S_SLACK; the first tile sets it (up or down).
-                float mx[4];
+                if (tracked) {
+                    float mx[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) mx[r] = fmaxf(fmaxf(acc[i][0][r], acc[i][1][r]), fmaxf(acc[i][2][r], acc[i][3][r]));
-                const float mxall = fmaxf(fmaxf(mx[0], mx[1]), fmaxf(mx[2], mx[3]));
-                if (kt == 0 || __any(mxall > S_SLACK)) {
+                    for (int r = 0; r < 4; ++r) mx[r] = fmaxf(fmaxf(acc[i][0][r], acc[i][1][r]), fmaxf(acc[i][2][r], acc[i][3][r]));
+                    const float mxall = fmaxf(fmaxf(mx[0], mx[1]), fmaxf(mx[2], mx[3]));
+                    if (kt == 0 || __any(mxall > S_SLACK)) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        float d = kt == 0 ? mx[r] : fmaxf(mx[r], 0.f);
-                        if (!(d > -3.0e38f)) d = 0.f;              // nothing visible in this lane's columns yet
-                        l[i][r] *= s_exp2(-d);
-                        nm[i][r] -= d;
+                        for (int r = 0; r < 4; ++r) {
+                            float d = kt == 0 ? mx[r] : fmaxf(mx[r], 0.f);
+                            if (!(d > -3.0e38f)) d = 0.f;              // nothing visible in this lane's columns yet
+                            l[i][r] *= s_exp2(-d);
+                            nm[i][r] -= d;
 #pragma unroll
-                        for (int nt = 0; nt < 4; ++nt) acc[i][nt][r] -= d;
+                            for (int nt = 0; nt < 4; ++nt) acc[i][nt][r] -= d;
+                        }
                     }
                 }
 #pragma unroll
@@ -475,37 +481,50 @@ struct ScoreKernel {
             if (a.lse_mode == 0) load_tile(kcb, kt, nc, tid, pf);
             else load_tile_coarse(kcb, kt, nc2, cstep, tid, pf);
         };
-        if (nkt1 > 0) {
-            load1(0);
-            stage_tile(smem, tid, pf, &s_flag, &s_shift[0], cm, ke);
-        }
-        for (int kt = 0; kt < nkt1; ++kt) {
-            if (kt + 1 < nkt1) load1(kt + 1);
-            if (late && kt > 0) vec1(kt - 1);
-            mma(kt, nm);
-            if (!late) vec1(kt);
-            if (kt + 1 < nkt1) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf, &s_flag, &s_shift[(kt + 1) & 1], cm, ke);
-            else __syncthreads();
-        }
-        if (late && nkt1 > 0) vec1(nkt1 - 1);
-        // merge the 16 key lanes of each lane group; lse2 = log2 of the row's sum of 2^y
         float lse2[TPW][4];
+        auto pass1 = [&](auto tracked_c) -> bool {       // returns true if some row's sum cannot be trusted
 #pragma unroll
-        for (int i = 0; i < TPW; ++i)
+            for (int i = 0; i < TPW; ++i) {
+                nm[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                float mm = -nm[i][r], ll = l[i][r];
-#pragma unroll
-                for (int o = 1; o < 16; o <<= 1) {
-                    const float mo = __shfl_xor(mm, o), lo = __shfl_xor(ll, o);
-                    const float mn = fmaxf(mm, mo);
-                    ll = ll * s_exp2(mm - mn) + lo * s_exp2(mo - mn);
-                    mm = mn;
-                }
-                // a row that saw no key at all (possible with the coarse keys of the LSE Approximation while
-                // fine keys are already visible) normalises everything to zero
-                lse2[i][r] = ll > 0.f ? mm + __log2f(ll) : INFINITY;
+                for (int r = 0; r < 4; ++r) l[i][r] = 0.f;
             }
+            if (nkt1 > 0) {
+                load1(0);
+                stage_tile(smem, tid, pf, &s_flag, &s_shift[0], cm, ke);
+            }
+            for (int kt = 0; kt < nkt1; ++kt) {
+                if (kt + 1 < nkt1) load1(kt + 1);
+                if (late && kt > 0) vec1(kt - 1, tracked_c);
+                mma(kt, nm);
+                if (!late) vec1(kt, tracked_c);
+                if (kt + 1 < nkt1) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf, &s_flag, &s_shift[(kt + 1) & 1], cm, ke);
+                else __syncthreads();
+            }
+            if (late && nkt1 > 0) vec1(nkt1 - 1, tracked_c);
+            // merge the 16 key lanes of each lane group; lse2 = log2 of the row's sum of 2^y
+            bool bad = false;
+#pragma unroll
+            for (int i = 0; i < TPW; ++i)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float mm = -nm[i][r], ll = l[i][r];
+#pragma unroll
+                    for (int o = 1; o < 16; o <<= 1) {
+                        const float mo = __shfl_xor(mm, o), lo = __shfl_xor(ll, o);
+                        const float mn = fmaxf(mm, mo);
+                        ll = ll * s_exp2(mm - mn) + lo * s_exp2(mo - mn);
+                        mm = mn;
+                    }
+                    // a row that saw no key at all (possible with the coarse keys of the LSE Approximation while
+                    // fine keys are already visible) normalises everything to zero
+                    lse2[i][r] = ll > 0.f ? mm + __log2f(ll) : INFINITY;
+                    // untracked sums are trusted only well inside fp32's range (2^-64 .. 3e38)
+                    bad |= vis1[i] > 0 && !(ll >= 5.4e-20f && ll < 3.0e38f);
+                }
+            return bad;
+        };
+        if (__syncthreads_or(pass1(std::false_type{}))) (void)pass1(std::true_type{});
 
         // ------------------------------------------------ pass 2: normalised scores, group sum, store
         f32x4 nlse[TPW];

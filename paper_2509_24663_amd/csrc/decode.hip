@@ -2,8 +2,10 @@
 // t = L-1 of every sequence (the row of Alg. 1 / Eq. 2 / Alg. 2 that a prefill would compute last).
 // The step moves ~100 MB (compressed-key cache once, 64 selected K/V blocks per KV head) and does almost no
 // arithmetic, so the work of one (sequence, KV head) pair is split over many workgroups to fill the chip;
-// the two reductions that need a whole pair are separate small kernels (a kernel boundary is the cheap
-// way to make one workgroup's results visible to another on a multi-die GPU):
+// the two reductions that need a whole pair are separate small kernels.  A kernel boundary is the cheap way to
+// make one workgroup's results visible to another on a multi-die GPU: letting the last attend workgroup of a pair
+// do the merge (device-wide fence + counter) was measured slower than the extra launch, 58.6 vs 53.3 us, because
+// the fences act on whole caches.
 //   scores  : grid (key chunks, pairs)  logits of 128 compressed keys x 16 heads per workgroup, written once
 //             as log2-domain logits, plus per-chunk (max, sum) partials of the softmax normaliser
 //   select  : grid (pairs)              one 1024-thread workgroup per pair merges the partials into the normaliser,
@@ -524,29 +526,31 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     a.nchunk = d.nchunk;
     a.nsplit = d.nsplit;
 
-    hipLaunchKernelGGL(dec_scores_kernel, dim3(d.nchunk, pairs), dim3(256), 0, stream, a);
-    // group sum + max-pool + top-k: one workgroup per pair; the score row lives in LDS
+    // group sum + max-pool + top-k run as one workgroup per pair with the score row in LDS
     const int sh_cap = (d.zs + 3) / 4 * 4;
     const size_t sel_lds = ((size_t)sh_cap + (size_t)sh_cap / 4 + 4) * sizeof(float);
-    if (sel_lds > 128 * 1024) return INFLLMV2_ERR_UNSUPPORTED;
-    {
-        static size_t sel_attr = 0;
-        if (sel_lds > 48 * 1024 && sel_lds > sel_attr) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(dec_select_kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_lds);
-            if (e != hipSuccess) return INFLLMV2_ERR_HIP;
-            sel_attr = sel_lds;
-        }
-        hipLaunchKernelGGL(dec_select_kernel, dim3(pairs), dim3(SEL_THREADS), sel_lds, stream, a, sh_cap);
+    if (sel_lds > 128 * 1024) return INFLLMV2_ERR_UNSUPPORTED;     // before anything is launched
+    // Larger-than-default dynamic LDS has to be enabled once per kernel and device; remembered per device (a
+    // repeated or concurrent call sets the same value again, which is harmless).
+    static size_t sel_attr[64] = {};
+    static bool attn_attr[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return INFLLMV2_ERR_HIP;
+    if (sel_lds > 48 * 1024 && sel_lds > sel_attr[dev]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(dec_select_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_lds);
+        if (e != hipSuccess) return INFLLMV2_ERR_HIP;
+        sel_attr[dev] = sel_lds;
     }
     const size_t attn_lds = (size_t)AW * TILE_ELEMS * sizeof(uint16_t);
-    static bool attr_set = false;
-    if (!attr_set) {
+    if (!attn_attr[dev]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(dec_attn_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds);
         if (e != hipSuccess) return INFLLMV2_ERR_HIP;
-        attr_set = true;
+        attn_attr[dev] = true;
     }
+    hipLaunchKernelGGL(dec_scores_kernel, dim3(d.nchunk, pairs), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(dec_select_kernel, dim3(pairs), dim3(SEL_THREADS), sel_lds, stream, a, sh_cap);
     hipLaunchKernelGGL(dec_attn_kernel, dim3(d.nsplit, pairs), dim3(AW * 64), attn_lds, stream, a);
     hipLaunchKernelGGL(dec_merge_kernel, dim3(pairs), dim3(256), (size_t)d.nsplit * 16 * sizeof(float), stream, a);
     return hip_status(hipGetLastError());
