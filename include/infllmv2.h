@@ -21,12 +21,14 @@
  *     HIP device; pointers named *_h are host memory and are only read during the
  *     call.  The library keeps no state and never synchronises: all work is
  *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
- *     stream).  The two prefill attention calls obtain a V-sized scratch buffer
- *     from the device's stream-ordered memory pool (hipMallocAsync / hipFreeAsync
- *     on `stream`) for bf16 data with 16 query heads per KV head and head_dim 128,
- *     and on first use raise that pool's release threshold so that the buffer is
- *     served from the pool on later calls instead of being returned to the driver
- *     at every synchronisation; nothing else is allocated.  The caller owns every buffer and keeps it alive until the
+ *     stream).  For bf16 data with 16 query heads per KV head and head_dim 128 two
+ *     groups of calls obtain scratch from the device's stream-ordered memory pool
+ *     (hipMallocAsync / hipFreeAsync on `stream`): the two prefill attention calls
+ *     a buffer of the size of V, and infllmv2_block_scores / _pooled one of a quarter
+ *     of the size of K^{C1} (a half-precision copy of the compressed keys).  On first
+ *     use they raise that pool's release threshold so that later calls are served
+ *     from the pool instead of the driver; nothing else is allocated.  The caller
+ *     owns every buffer and keeps it alive until the
  *     stream work has finished.  Calls are thread-safe.
  *   - All indices are 0-based.  Token t of a sequence lies in block t / block_size.
  *     Sequences are packed along the token axis; cu_seqlens has batch+1 int32
@@ -143,6 +145,7 @@ int infllmv2_compress_k_append(const infllmv2_params *p, const void *k_cache_d, 
  *                  written, the rest of each row is left untouched.  row_stride >= max over sequences
  *                  of nc(len) and a multiple of 4.
  *   Per-head score matrices never reach HBM; only the group sums are stored.
+ *   Returns INFLLMV2_ERR_HIP if the scratch buffer (see the general rules) cannot be obtained.
  */
 int infllmv2_block_scores(const infllmv2_params *p, const void *q_d, const float *kc_d, int64_t total_c,
                           const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d,

@@ -356,17 +356,7 @@ int launch_attn_mfma(const Launch &L, const void *q, const void *k, const void *
     int64_t nblk_total = 0;
     for (int s = 0; s < L.map.batch; ++s) nblk_total += (cu_h[s + 1] - cu_h[s] + kBlock - 1) / kBlock;
     if (nblk_total == 0) return INFLLMV2_OK;
-    {   // keep freed scratch in the pool instead of returning it to the driver at every synchronisation
-        static bool pool_set[64] = {};
-        int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && !pool_set[dev]) {
-            hipMemPool_t pool;
-            uint64_t keep = UINT64_MAX;
-            if (hipDeviceGetDefaultMemPool(&pool, dev) == hipSuccess)
-                (void)hipMemPoolSetAttribute(pool, hipMemPoolAttrReleaseThreshold, &keep);
-            pool_set[dev] = true;
-        }
-    }
+    keep_freed_memory_in_pool();
     void *ws = nullptr;
     const size_t ws_bytes = (size_t)nblk_total * L.p->num_kv_heads * VT_TILE_ELEMS * sizeof(uint16_t);
     if (hipMallocAsync(&ws, ws_bytes, L.stream) != hipSuccess) return INFLLMV2_ERR_HIP;

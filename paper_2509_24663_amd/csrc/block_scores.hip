@@ -183,9 +183,19 @@ constexpr float S_LOG2E = 1.4426950408889634f;
 constexpr float S_SLACK = 16.0f;               // pass 1 moves its reference when a logit exceeds it by 2^16
 constexpr float S_FP16_SAFE = 32768.0f;
 
+// fp16 copy of the compressed keys in tiles of 64 rows (written by kc_half_kernel): per KV head `tiles` tiles of
+// 64 x 128 halves, sequences back to back (sequence s starts at tile sum_{s' < s} ceil(nc(s') / 64)), rows past a
+// sequence's last key are zero; tile values are K * cm * 2^-shift with the tile's shift stored beside.
+struct HalfTiles {
+    const _Float16 *data;
+    const int32_t *shift;
+    int32_t tiles;            // per KV head
+};
+
 struct ScoreArgs {
     const uint16_t *q;
     const float *kc;
+    HalfTiles fine, coarse;   // K^{C1}; K^{C2} (only with the LSE Approximation)
     float *out;
     RowMap map;
     int hq, lc, sc, dense_below, lse_mode;
@@ -204,90 +214,104 @@ constexpr int DPP_QUAD_SWAP1 = 0xB1;   // quad_perm [1,0,3,2]
 constexpr int DPP_QUAD_SWAP2 = 0x4E;   // quad_perm [2,3,0,1]
 constexpr int DPP_WAVE_SHR1 = 0x138;   // lane i <- lane i - 1 (lane 0 <- 0)
 
-template <int NW, int TPW>
-struct ScoreKernel {
-    static constexpr int T = NW * TPW;
-    static constexpr int NTHR = NW * 64;
-    static constexpr int NCH = 2048 / NTHR;        // float4 chunks of a 64 x 128 fp32 tile per thread
-
-    __device__ static inline void load_tile(const float *kcb, int kt, int nc, int tid, float4 (&pf)[NCH]) {
-#pragma unroll
-        for (int r = 0; r < NCH; ++r) {
-            const int c = tid + r * NTHR;
-            const int row = kt * kBlock + (c >> 5), col = (c & 31) * 4;
-            pf[r] = row < nc ? *reinterpret_cast<const float4 *>(kcb + (int64_t)row * SD + col)
-                             : make_float4(0.f, 0.f, 0.f, 0.f);
+// Pre-pass of the matrix-core kernel: one workgroup per 64-row key tile.  Converts K^{C1} (or, for tiles
+// >= fine.tiles, the coarse keys of Eq. 7: row i = mean of K^{C1} rows 4i + m l_C1/s_C1, m = 0..3) to fp16,
+// multiplied by cm = the mantissa of softmax_scale * log2(e), and by 2^-shift where shift is the smallest power of
+// two that brings the tile's largest magnitude below 2^15 (0 for any real activations).
+__global__ void __launch_bounds__(256)
+kc_half_kernel(const float *__restrict__ kc, RowMap map, int lc, int sc, int dense_below, float cm,
+               _Float16 *__restrict__ fine, int32_t *__restrict__ sh_fine, int tiles_fine,
+               _Float16 *__restrict__ coarse, int32_t *__restrict__ sh_coarse, int tiles_coarse) {
+    __shared__ int s_seq, s_local;
+    __shared__ float s_red[4];
+    const int tid = threadIdx.x, h = blockIdx.y;
+    const bool is_coarse = (int)blockIdx.x >= tiles_fine;
+    const int tile = is_coarse ? blockIdx.x - tiles_fine : blockIdx.x;
+    const int wl = is_coarse ? 4 * lc : lc, ws = is_coarse ? 4 * sc : sc;
+    if (tid == 0) {
+        int rem = tile, s = 0;
+        for (; s < map.batch; ++s) {
+            const int nt = (num_cmp(map.cu[s + 1] - map.cu[s], wl, ws) + kBlock - 1) / kBlock;
+            if (rem < nt) break;
+            rem -= nt;
         }
+        s_seq = s;
+        s_local = rem;
     }
-    // the same for a tile of coarse keys (Eq. 7): row i = mean of K^{C1} rows 4i, 4i + cstep, .. + 3 cstep
-    __device__ static inline void load_tile_coarse(const float *kcb, int kt, int nc2, int cstep, int tid,
-                                                   float4 (&pf)[NCH]) {
+    __syncthreads();
+    const int seq = s_seq;
+    if (seq >= map.batch) return;
+    const int len = map.cu[seq + 1] - map.cu[seq];
+    if (len < dense_below) return;                    // dense sequences are never scored
+    const int rows = num_cmp(len, wl, ws), cstep = lc / sc;
+    const float *kcb = kc + ((int64_t)h * map.kc_total_c + map.cu_c[seq]) * SD;
+    float4 x[8];
+    float amax = 0.f;
 #pragma unroll
-        for (int r = 0; r < NCH; ++r) {
-            const int c = tid + r * NTHR;
-            const int row = kt * kBlock + (c >> 5), col = (c & 31) * 4;
-            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < nc2) {
+    for (int r = 0; r < 8; ++r) {
+        const int c = tid + r * 256;
+        const int row = s_local * kBlock + (c >> 5), col = (c & 31) * 4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row < rows) {
+            if (!is_coarse) {
+                v = *reinterpret_cast<const float4 *>(kcb + (int64_t)row * SD + col);
+            } else {
                 const float *b = kcb + (int64_t)4 * row * SD + col;
                 const float4 k0 = *reinterpret_cast<const float4 *>(b);
                 const float4 k1 = *reinterpret_cast<const float4 *>(b + (int64_t)cstep * SD);
                 const float4 k2 = *reinterpret_cast<const float4 *>(b + (int64_t)2 * cstep * SD);
                 const float4 k3 = *reinterpret_cast<const float4 *>(b + (int64_t)3 * cstep * SD);
-                x.x = ((k0.x + k1.x) + (k2.x + k3.x)) * 0.25f;
-                x.y = ((k0.y + k1.y) + (k2.y + k3.y)) * 0.25f;
-                x.z = ((k0.z + k1.z) + (k2.z + k3.z)) * 0.25f;
-                x.w = ((k0.w + k1.w) + (k2.w + k3.w)) * 0.25f;
+                v.x = ((k0.x + k1.x) + (k2.x + k3.x)) * 0.25f;
+                v.y = ((k0.y + k1.y) + (k2.y + k3.y)) * 0.25f;
+                v.z = ((k0.z + k1.z) + (k2.z + k3.z)) * 0.25f;
+                v.w = ((k0.w + k1.w) + (k2.w + k3.w)) * 0.25f;
             }
-            pf[r] = x;
         }
+        x[r] = v;
+        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
     }
-    // fp32 -> fp16 (x * cm * 2^e) into the tile; returns true if some scaled magnitude is not fp16-safe
-    __device__ static inline bool store_tile(_Float16 *tile, int tid, const float4 (&pf)[NCH], float cm, int e) {
-        float amax = 0.f;
-        const float sc = __builtin_ldexpf(cm, e);
+    amax = wave_max(amax);
+    if ((tid & 63) == 0) s_red[tid >> 6] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+    if (!(amax < 3.0e38f)) amax = 3.0e38f;            // Inf / NaN inputs: keep going, results are Inf / NaN anyway
+    int ek = 0;
+    if (amax > 0.f) (void)frexpf(amax, &ek);          // amax < 2^ek and cm < 1
+    const int shift = max(0, ek - 15);
+    const float f = __builtin_ldexpf(cm, -shift);
+    _Float16 *dst = (is_coarse ? coarse + ((int64_t)h * tiles_coarse + tile) * (kBlock * SD)
+                               : fine + ((int64_t)h * tiles_fine + tile) * (kBlock * SD));
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const int c = tid + r * 256;
+        typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+        const half4 hv = {(_Float16)(x[r].x * f), (_Float16)(x[r].y * f), (_Float16)(x[r].z * f), (_Float16)(x[r].w * f)};
+        *reinterpret_cast<half4 *>(dst + (c >> 5) * SD + (c & 31) * 4) = hv;
+    }
+    if (tid == 0) (is_coarse ? sh_coarse : sh_fine)[(int64_t)h * (is_coarse ? tiles_coarse : tiles_fine) + tile] = shift;
+}
+
+template <int NW, int TPW>
+struct ScoreKernel {
+    static constexpr int T = NW * TPW;
+    static constexpr int NTHR = NW * 64;
+    static constexpr int NCH = 1024 / NTHR;        // 16-byte chunks of a 64 x 128 fp16 tile per thread
+
+    __device__ static inline void load_tile(const _Float16 *tiles, int kt, int tid, uint4 (&pf)[NCH]) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(tiles) + (int64_t)kt * 1024;
+#pragma unroll
+        for (int r = 0; r < NCH; ++r) pf[r] = src[tid + r * NTHR];
+    }
+    // registers -> LDS (padded rows), then a workgroup barrier: every thread calls it
+    __device__ static inline void stage_tile(_Float16 *tile, int tid, const uint4 (&pf)[NCH]) {
 #pragma unroll
         for (int r = 0; r < NCH; ++r) {
             const int c = tid + r * NTHR;
-            const int row = c >> 5, col = (c & 31) * 4;
-            const float x[4] = {pf[r].x * sc, pf[r].y * sc, pf[r].z * sc, pf[r].w * sc};
-            amax = fmaxf(fmaxf(amax, fmaxf(fabsf(x[0]), fabsf(x[1]))), fmaxf(fabsf(x[2]), fabsf(x[3])));
-            typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-            half4 hv = {(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3]};
-            *reinterpret_cast<half4 *>(tile + row * SKS + col) = hv;
+            *reinterpret_cast<uint4 *>(tile + (c >> 4) * SKS + (c & 15) * 8) = pf[r];
         }
-        return !(amax < S_FP16_SAFE);              // also true for NaN / Inf
-    }
-
-    // Stage the prefetched tile; returns the power-of-two exponent the tile was scaled down by (normally 0).
-    // Contains workgroup barriers: every thread calls it.
-    __device__ static inline void stage_tile(_Float16 *tile, int tid, const float4 (&pf)[NCH], int *s_flag,
-                                             int *s_shift, float cm, int ke) {
-        const bool bad = store_tile(tile, tid, pf, cm, ke);
-        if (bad) *s_flag = 1;
-        if (tid == 0 && *s_shift != 0) *s_shift = 0;     // the stage's previous occupant may have been scaled
         __syncthreads();
-        if (*s_flag) {                             // rare: re-stage with the tile's own scale
-            float amax = 0.f;
-#pragma unroll
-            for (int r = 0; r < NCH; ++r)
-                amax = fmaxf(fmaxf(amax, fmaxf(fabsf(pf[r].x), fabsf(pf[r].y))), fmaxf(fabsf(pf[r].z), fabsf(pf[r].w)));
-            if (!(amax < 3.0e38f)) amax = 3.0e38f;  // Inf / NaN inputs: keep going, results are Inf / NaN anyway
-            atomicMax(reinterpret_cast<unsigned *>(s_shift), __float_as_uint(amax));
-            __syncthreads();
-            // smallest shift with amax * cm * 2^(ke - shift) < 2^15 (amax < 2^ek and cm < 1)
-            int ek = 0;
-            (void)frexpf(__uint_as_float(*reinterpret_cast<unsigned *>(s_shift)), &ek);
-            const int shift = max(0, ek + ke - 15);
-            __syncthreads();
-            (void)store_tile(tile, tid, pf, cm, ke - shift);
-            if (tid == 0) { *s_flag = 0; *s_shift = shift; }
-            __syncthreads();
-        }
     }
 
-    // acc[i][nt] = Q_i (16 heads x 128) . kc_tile^T (128 x 16 keys of n-tile nt); each B fragment read from
-    // LDS feeds the TPW tokens of the wave, through a rolling window of 4 fragments
-    // SEEDED: the accumulators start from seed[i] (one value per head row) instead of zero.
     template <bool SEEDED>
     __device__ static inline void tile_mma(const half8 (&qf)[TPW][4], const _Float16 *tile, int lane,
                                            f32x4 (&acc)[TPW][4], const f32x4 (&seed)[TPW]) {
@@ -314,21 +338,24 @@ struct ScoreKernel {
     template <int POOL>
     __device__ static void run(const ScoreArgs &a, int num_tiles) {
         extern __shared__ __attribute__((aligned(16))) _Float16 smem[];     // two tiles (double buffer)
-        __shared__ int s_seq, s_tile, s_flag, s_shift[2];
+        __shared__ int s_seq, s_tile, s_tbase[2];
         const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
         const int h = blockIdx.y;
         const int tile_id = num_tiles - 1 - (int)blockIdx.x;     // longest rows first
         if (tid == 0) {
-            int rem = tile_id, s = 0;
+            int rem = tile_id, s = 0, tb_fine = 0, tb_coarse = 0;      // first key tile of the sequence
             for (; s < a.map.batch; ++s) {
-                const int nt = (a.map.cu[s + 1] - a.map.cu[s] + T - 1) / T;
+                const int slen = a.map.cu[s + 1] - a.map.cu[s];
+                const int nt = (slen + T - 1) / T;
                 if (rem < nt) break;
                 rem -= nt;
+                tb_fine += (num_cmp(slen, a.lc, a.sc) + kBlock - 1) / kBlock;
+                tb_coarse += (num_cmp(slen, 4 * a.lc, 4 * a.sc) + kBlock - 1) / kBlock;
             }
             s_seq = s;
             s_tile = rem;
-            s_flag = 0;
-            s_shift[0] = s_shift[1] = 0;
+            s_tbase[0] = tb_fine;
+            s_tbase[1] = tb_coarse;
         }
         __syncthreads();
         const int seq = s_seq;
@@ -342,7 +369,13 @@ struct ScoreKernel {
         if (vis_last == 0) return;
         const int nkt = (vis_last + kBlock - 1) / kBlock;
         const int row0 = tok0 + t0;
-        const float *kcb = a.kc + ((int64_t)h * a.map.kc_total_c + a.map.cu_c[seq]) * SD;
+        // this sequence's key tiles and their shifts (wave-uniform addresses)
+        const int tb_fine = __builtin_amdgcn_readfirstlane(s_tbase[0]);
+        const int tb_coarse = __builtin_amdgcn_readfirstlane(s_tbase[1]);
+        const _Float16 *kt_fine = a.fine.data + ((int64_t)h * a.fine.tiles + tb_fine) * (kBlock * SD);
+        const int32_t *sh_fine = a.fine.shift + (int64_t)h * a.fine.tiles + tb_fine;
+        const _Float16 *kt_coarse = a.lse_mode ? a.coarse.data + ((int64_t)h * a.coarse.tiles + tb_coarse) * (kBlock * SD) : kt_fine;
+        const int32_t *sh_coarse = a.lse_mode ? a.coarse.shift + (int64_t)h * a.coarse.tiles + tb_coarse : sh_fine;
         const int n16 = lane & 15, g = lane >> 4;
 
         // ---- Q rows of this wave's tokens: bf16 -> fp16, times a power of two (exact).  With
@@ -351,11 +384,11 @@ struct ScoreKernel {
         // A token whose magnitudes would leave fp16's comfortable range that way gets its own exponent instead and
         // takes the slower path that multiplies the accumulator by the difference.
         int ce;
-        const float cm = frexpf(a.scale * S_LOG2E, &ce);
+        (void)frexpf(a.scale * S_LOG2E, &ce);
         half8 qf[TPW][4];
         int vis[TPW];
         // keys of pass 1: the fine ones, or with the LSE Approximation the coarse ones (Eq. 7)
-        const int nc2 = num_cmp(len, 4 * a.lc, 4 * a.sc), cstep = a.lc / a.sc;
+        const int nc2 = num_cmp(len, 4 * a.lc, 4 * a.sc);
         int vis1[TPW];
         int vis1_min = 1 << 30;
         float cq[TPW];                   // 2^(ce - token's exponent): multiplies the accumulator (normally 1)
@@ -397,9 +430,7 @@ struct ScoreKernel {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) qf[i][ks][e] = (_Float16)(x[ks][e] * sc);
         }
-        const int ke = 0;                // a key tile is staged as K^{C1} * cm * 2^(ke - shift)
-
-        float4 pf[NCH];
+        uint4 pf[NCH];
         f32x4 acc[TPW][4];
         f32x4 nm[TPW];                   // per lane and head row: minus the reference (log2 domain)
         float l[TPW][4];                 // ... and the sum of 2^(y - reference)
@@ -411,9 +442,9 @@ struct ScoreKernel {
         }
 
         // Matrix-core step of either pass: acc = y - seed for tile kt (y = the logit in the log2 domain)
-        auto mma = [&](int kt, const f32x4 (&seed)[TPW]) {
+        auto mma = [&](int kt, const int32_t *shifts, const f32x4 (&seed)[TPW]) {
             const _Float16 *tile = smem + (kt & 1) * S_TILE;
-            const int tshift = s_shift[kt & 1];
+            const int tshift = shifts[kt];
             if (q_plain && tshift == 0) {
                 tile_mma<true>(qf, tile, lane, acc, seed);
             } else {
@@ -477,10 +508,6 @@ struct ScoreKernel {
         };
         const int vis1_last = a.lse_mode == 0 ? vis_last : min(visible_cmp(t0 + ntok - 1, 4 * a.lc, 4 * a.sc), nc2);
         const int nkt1 = (vis1_last + kBlock - 1) / kBlock;
-        auto load1 = [&](int kt) {
-            if (a.lse_mode == 0) load_tile(kcb, kt, nc, tid, pf);
-            else load_tile_coarse(kcb, kt, nc2, cstep, tid, pf);
-        };
         float lse2[TPW][4];
         auto pass1 = [&](auto tracked_c) -> bool {       // returns true if some row's sum cannot be trusted
 #pragma unroll
@@ -490,15 +517,15 @@ struct ScoreKernel {
                 for (int r = 0; r < 4; ++r) l[i][r] = 0.f;
             }
             if (nkt1 > 0) {
-                load1(0);
-                stage_tile(smem, tid, pf, &s_flag, &s_shift[0], cm, ke);
+                load_tile(kt_coarse, 0, tid, pf);
+                stage_tile(smem, tid, pf);
             }
             for (int kt = 0; kt < nkt1; ++kt) {
-                if (kt + 1 < nkt1) load1(kt + 1);
+                if (kt + 1 < nkt1) load_tile(kt_coarse, kt + 1, tid, pf);
                 if (late && kt > 0) vec1(kt - 1, tracked_c);
-                mma(kt, nm);
+                mma(kt, sh_coarse, nm);
                 if (!late) vec1(kt, tracked_c);
-                if (kt + 1 < nkt1) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf, &s_flag, &s_shift[(kt + 1) & 1], cm, ke);
+                if (kt + 1 < nkt1) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf);
                 else __syncthreads();
             }
             if (late && nkt1 > 0) vec1(nkt1 - 1, tracked_c);
@@ -588,14 +615,14 @@ struct ScoreKernel {
             for (int i = 0; i < TPW; ++i)
                 if (lane == 0 && max(4 * jb - POOL, 0) < vis[i]) out_w[i * a.row_stride + jb] = carry[i];
         };
-        load_tile(kcb, 0, nc, tid, pf);
-        stage_tile(smem, tid, pf, &s_flag, &s_shift[0], cm, ke);
+        load_tile(kt_fine, 0, tid, pf);
+        stage_tile(smem, tid, pf);
         for (int kt = 0; kt < nkt; ++kt) {
-            if (kt + 1 < nkt) load_tile(kcb, kt + 1, nc, tid, pf);
+            if (kt + 1 < nkt) load_tile(kt_fine, kt + 1, tid, pf);
             if (late && kt > 0) vec2(kt - 1);
-            mma(kt, nlse);
+            mma(kt, sh_fine, nlse);
             if (!late) vec2(kt);
-            if (kt + 1 < nkt) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf, &s_flag, &s_shift[(kt + 1) & 1], cm, ke);
+            if (kt + 1 < nkt) stage_tile(smem + ((kt + 1) & 1) * S_TILE, tid, pf);
             else __syncthreads();
         }
         if (late) vec2(nkt - 1);
@@ -609,15 +636,39 @@ __global__ void __launch_bounds__(NW * 64) block_scores_mfma_kernel(ScoreArgs a,
 }
 
 template <int NW, int TPW, int POOL>
-int launch_scores_mfma(const Launch &L, const ScoreArgs &a, const int32_t *cu_h) {
+int launch_scores_mfma(const Launch &L, ScoreArgs a, const int32_t *cu_h) {
     constexpr int T = NW * TPW;
-    int64_t tiles = 0;
-    for (int s = 0; s < L.map.batch; ++s) tiles += (cu_h[s + 1] - cu_h[s] + T - 1) / T;
-    if (tiles == 0) return INFLLMV2_OK;
+    int64_t tiles = 0, kt_fine = 0, kt_coarse = 0;
+    for (int s = 0; s < L.map.batch; ++s) {
+        const int len = cu_h[s + 1] - cu_h[s];
+        tiles += (len + T - 1) / T;
+        kt_fine += (num_cmp(len, a.lc, a.sc) + kBlock - 1) / kBlock;
+        if (a.lse_mode) kt_coarse += (num_cmp(len, 4 * a.lc, 4 * a.sc) + kBlock - 1) / kBlock;
+    }
+    if (tiles == 0 || kt_fine == 0) return INFLLMV2_OK;      // no token sees a compressed key
+    if (kt_fine + kt_coarse > 0x7fffffff) return INFLLMV2_ERR_UNSUPPORTED;
+    // fp16 key tiles + one shift per tile: stream-ordered scratch, returned to the device's pool after the launch
+    const int hkv = L.p->num_kv_heads;
+    const size_t tile_bytes = (size_t)kBlock * SD * sizeof(_Float16);
+    const size_t data_bytes = (size_t)hkv * (kt_fine + kt_coarse) * tile_bytes;
+    const size_t ws_bytes = data_bytes + (size_t)hkv * (kt_fine + kt_coarse) * sizeof(int32_t);
+    keep_freed_memory_in_pool();
+    void *ws = nullptr;
+    if (hipMallocAsync(&ws, ws_bytes, L.stream) != hipSuccess) return INFLLMV2_ERR_HIP;
+    _Float16 *fine = (_Float16 *)ws, *coarse = fine + (size_t)hkv * kt_fine * kBlock * SD;
+    int32_t *sh_fine = (int32_t *)((char *)ws + data_bytes), *sh_coarse = sh_fine + (size_t)hkv * kt_fine;
+    int ce;
+    const float cm = frexpf(a.scale * S_LOG2E, &ce);
+    hipLaunchKernelGGL(kc_half_kernel, dim3((unsigned)(kt_fine + kt_coarse), hkv), dim3(256), 0, L.stream, a.kc, L.map,
+                       a.lc, a.sc, a.dense_below, cm, fine, sh_fine, (int)kt_fine, coarse, sh_coarse, (int)kt_coarse);
+    a.fine = HalfTiles{fine, sh_fine, (int32_t)kt_fine};
+    a.coarse = HalfTiles{coarse, sh_coarse, (int32_t)kt_coarse};
     const size_t lds = (size_t)2 * S_TILE * sizeof(_Float16);
-    dim3 grid((unsigned)tiles, L.p->num_kv_heads);
+    dim3 grid((unsigned)tiles, hkv);
     hipLaunchKernelGGL((block_scores_mfma_kernel<NW, TPW, POOL>), grid, dim3(NW * 64), lds, L.stream, a, (int)tiles);
-    return hip_status(hipGetLastError());
+    const hipError_t e = hipGetLastError();
+    (void)hipFreeAsync(ws, L.stream);
+    return hip_status(e);
 }
 
 }  // namespace
@@ -630,7 +681,7 @@ int launch_block_scores(const Launch &L, const void *q, const float *kc, float *
     const bool pool_ok = !pooled || (pool.len == 5 && pool.stride == 4 && (pool.pad == 0 || pool.pad == 1));
     if (bf && cu_h != nullptr && L.map.ctx == nullptr && L.p->head_dim == SD &&
         L.p->num_q_heads / L.p->num_kv_heads == SG && (((uintptr_t)q | (uintptr_t)kc) & 15) == 0 && pool_ok) {
-        ScoreArgs a{(const uint16_t *)q, kc, s_shared, L.map, L.p->num_q_heads, L.p->cmp_len, L.p->cmp_stride,
+        ScoreArgs a{(const uint16_t *)q, kc, HalfTiles{}, HalfTiles{}, s_shared, L.map, L.p->num_q_heads, L.p->cmp_len, L.p->cmp_stride,
                     L.p->dense_threshold, L.p->lse_mode, L.p->softmax_scale, row_stride};
         if (!pooled) return launch_scores_mfma<8, 4, -1>(L, a, cu_h);
         return pool.pad == 0 ? launch_scores_mfma<8, 4, 0>(L, a, cu_h) : launch_scores_mfma<8, 4, 1>(L, a, cu_h);

@@ -143,4 +143,19 @@ int launch_attn(const Launch &L, const void *q, const void *k, const void *v, co
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? INFLLMV2_OK : INFLLMV2_ERR_HIP; }
 
+// Stream-ordered scratch (hipMallocAsync / hipFreeAsync) comes from the current device's default memory pool.  By
+// default the pool hands freed memory back to the driver at every synchronisation; a release threshold of
+// "never" makes the second and later calls allocation-free in effect.  Set once per device.
+inline void keep_freed_memory_in_pool() {
+    static bool pool_set[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && !pool_set[dev]) {
+        hipMemPool_t pool;
+        uint64_t keep = UINT64_MAX;
+        if (hipDeviceGetDefaultMemPool(&pool, dev) == hipSuccess)
+            (void)hipMemPoolSetAttribute(pool, hipMemPoolAttrReleaseThreshold, &keep);
+        pool_set[dev] = true;
+    }
+}
+
 }  // namespace ifv2
