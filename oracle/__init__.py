@@ -54,6 +54,8 @@ def _load():
         lib.oracle_sparse_attn.argtypes = [P, P, i32, i32, i32, P, P, i32, i32, P, i32, f64, P, P]
         lib.oracle_dense_attn.restype = None
         lib.oracle_dense_attn.argtypes = [P, P, i32, i32, i32, P, P, i32, f64, P, P]
+        lib.oracle_attn_bwd.restype = None
+        lib.oracle_attn_bwd.argtypes = [P, P, i32, i32, i32, P, P, i32, i32, P, i32, f64, P, P, P, P]
         _lib = lib
     return _lib
 
@@ -175,6 +177,23 @@ def dense_attn(Q, pos, K, V, p: Params):
     _load().oracle_dense_attn(_p(Q), _p(pos), nr, G, d, _p(K), _p(V), K.shape[0], float(p.softmax_scale),
                               _p(O), _p(lse))
     return O, lse
+
+
+def attn_bwd(Q, pos, K, V, idx, dO, p: Params):
+    """Gradients of stage 4 for a fixed selection (idx None: dense causal attention, Eq. 1) from the definition
+    of softmax attention, in float64.  Q, dO [rows, G, d]; K, V [n, d] -> dQ [rows, G, d], dK, dV [n, d]."""
+    Q, pos, K, V, dO = _f32(Q), _i32(pos), _f32(K), _f32(V), _f32(dO)
+    nr, G, d = Q.shape
+    n = K.shape[0]
+    dQ = np.zeros((nr, G, d), dtype=np.float64)
+    dK = np.zeros((n, d), dtype=np.float64)
+    dV = np.zeros((n, d), dtype=np.float64)
+    if idx is not None:
+        idx = _i32(idx)
+    _load().oracle_attn_bwd(_p(Q), _p(pos), nr, G, d, _p(K), _p(V), n, p.block_size, _p(idx),
+                            idx.shape[1] if idx is not None else 0, float(p.softmax_scale), _p(dO), _p(dQ), _p(dK),
+                            _p(dV))
+    return dQ, dK, dV
 
 
 # --------------------------------------------------------------------------- compositions

@@ -33,7 +33,9 @@
  * Parity pins (tests/test_oracle_*.py): closed forms for the mean pooling,
  * softmax rows summing to G, brute-force masked dense attention, sparse == dense
  * when every block is kept, library softmax / SDPA cross-checks, a full-sort
- * brute-force top-k, decode == last prefill row.  The choice of which compressed
+ * brute-force top-k, decode == last prefill row; for the gradients of stage 4
+ * (oracle_attn_bwd): automatic differentiation of textbook masked attention in
+ * float64, central differences, and the column sums of dV.  The choice of which compressed
  * keys are visible and the pooling-window alignment are fixed by this file, not
  * by any printed value in the paper: for those two conventions parity is
  * unpinned by the paper itself.
@@ -286,3 +288,74 @@ void oracle_dense_attn(const float *Q, const int32_t *pos, int nr, int G, int d,
         free(o);
     }
 }
+
+/* Gradient of stage 4 (Appendix Alg. 2, or Eq. 1 when idx == NULL) with respect to Q, K and V for a given
+ * selection; the selection itself (stages 1-3) is piecewise constant and carries no gradient (Sec. 3.3: the
+ * compressed scores only pick blocks).  Written from the definition O = softmax(z) V, z_a = scale <q, k_a>:
+ *   p = softmax(z),  dp_a = <dO, v_a>,  D = sum_a p_a dp_a,  dz_a = p_a (dp_a - D),
+ *   dq = scale sum_a dz_a k_a,   dk_a += scale dz_a q,   dv_a += p_a dO
+ * per query row and head, everything in double.  dO [nr][G][d]; dQ [nr][G][d]; dK, dV [n][d] are ACCUMULATED
+ * into (the caller zeroes them), so that several row subsets can be summed. */
+void oracle_attn_bwd(const float *Q, const int32_t *pos, int nr, int G, int d, const float *K, const float *V,
+                     int n, int B, const int32_t *idx, int topk_total, double scale, const float *dO,
+                     double *dQ, double *dK, double *dV) {
+    int cap = idx ? topk_total * B : (n > 0 ? n : 1);
+    int *keys = (int *)malloc(sizeof(int) * (size_t)cap);
+    double *p = (double *)malloc(sizeof(double) * (size_t)cap);
+    for (int r = 0; r < nr; ++r) {
+        int t = pos[r];
+        int nk = 0;
+        if (idx) {
+            for (int s = 0; s < topk_total; ++s) {
+                int j = idx[(size_t)r * topk_total + s];
+                if (j < 0) continue;
+                for (int u = j * B; u < (j + 1) * B && u <= t && u < n; ++u) keys[nk++] = u;
+            }
+        } else {
+            for (int u = 0; u <= t && u < n; ++u) keys[nk++] = u;
+        }
+        for (int g = 0; g < G; ++g) {
+            const float *q = Q + ((size_t)r * G + g) * d;
+            const float *go = dO + ((size_t)r * G + g) * d;
+            double *gq = dQ + ((size_t)r * G + g) * d;
+            double zmax = -INFINITY;
+            for (int a = 0; a < nk; ++a) {
+                const float *kr = K + (size_t)keys[a] * d;
+                double dot = 0.0;
+                for (int c = 0; c < d; ++c) dot += (double)q[c] * (double)kr[c];
+                p[a] = scale * dot;
+                if (p[a] > zmax) zmax = p[a];
+            }
+            double den = 0.0;
+            for (int a = 0; a < nk; ++a) {
+                p[a] = exp(p[a] - zmax);
+                den += p[a];
+            }
+            double D = 0.0;
+            for (int a = 0; a < nk; ++a) {
+                p[a] /= den;
+                const float *vr = V + (size_t)keys[a] * d;
+                double dp = 0.0;
+                for (int c = 0; c < d; ++c) dp += (double)go[c] * (double)vr[c];
+                D += p[a] * dp;
+            }
+            for (int c = 0; c < d; ++c) gq[c] = 0.0;
+            for (int a = 0; a < nk; ++a) {
+                const float *kr = K + (size_t)keys[a] * d;
+                const float *vr = V + (size_t)keys[a] * d;
+                double dp = 0.0;
+                for (int c = 0; c < d; ++c) dp += (double)go[c] * (double)vr[c];
+                const double dz = p[a] * (dp - D);
+                double *gk = dK + (size_t)keys[a] * d, *gv = dV + (size_t)keys[a] * d;
+                for (int c = 0; c < d; ++c) {
+                    gq[c] += scale * dz * (double)kr[c];
+                    gk[c] += scale * dz * (double)q[c];
+                    gv[c] += p[a] * (double)go[c];
+                }
+            }
+        }
+    }
+    free(keys);
+    free(p);
+}
+

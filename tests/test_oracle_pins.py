@@ -350,6 +350,85 @@ def test_attention_closed_forms(oracle):
     assert abs(lse[t, 1] - np.log(np.exp(z).sum())) < 1e-5
 
 
+def _selection_mask(idx, n):
+    mask = np.zeros((n, n), dtype=bool)
+    for t in range(n):
+        for j in idx[t]:
+            if j >= 0:
+                mask[t, j * 64:(j + 1) * 64] = True
+        mask[t, t + 1:] = False
+    return mask
+
+
+def test_attention_gradients_match_library_autograd(oracle):
+    """The backward formulas against automatic differentiation (a library routine) of textbook masked softmax
+    attention in float64: sparse selection and dense, GQA group of 3, loss = <O, dO>."""
+    w = _small(n=200, hq=6, hkv=2, d=16, seed=41)
+    p = oracle.Params(n_init=1, n_local=1, topk_total=2, softmax_scale=0.3)
+    n, G = 200, 3
+    pos = np.arange(n, dtype=np.int32)
+    rng = np.random.default_rng(5)
+    for h in range(2):
+        Qh, Kh, Vh = w["q"][:, h * G:(h + 1) * G], w["k"][h], w["v"][h]
+        dO = rng.standard_normal(Qh.shape).astype(np.float32)
+        idx = oracle.select_blocks(Qh, pos, Kh, p)
+        for sel in (idx, None):
+            mask = _selection_mask(idx, n) if sel is not None else np.tril(np.ones((n, n), dtype=bool))
+            q = torch.from_numpy(Qh).double().requires_grad_()
+            k = torch.from_numpy(Kh).double().requires_grad_()
+            v = torch.from_numpy(Vh).double().requires_grad_()
+            z = torch.einsum("tgd,ud->gtu", q, k) * 0.3
+            z = z.masked_fill(~torch.from_numpy(mask)[None], float("-inf"))
+            o = torch.einsum("gtu,ud->tgd", torch.softmax(z, dim=-1), v)
+            (o * torch.from_numpy(dO).double()).sum().backward()
+            dQ, dK, dV = oracle.attn_bwd(Qh, pos, Kh, Vh, sel, dO, p)
+            np.testing.assert_allclose(dQ, q.grad.numpy(), atol=1e-12)
+            np.testing.assert_allclose(dK, k.grad.numpy(), atol=1e-12)
+            np.testing.assert_allclose(dV, v.grad.numpy(), atol=1e-12)
+
+
+def test_attention_gradients_match_finite_differences_and_invariants(oracle):
+    """Central differences of the oracle's own forward on sampled coordinates, and what the mathematics fixes:
+    softmax rows sum to 1 => the columns of dV sum to the columns of dO; a constant V => O does not depend on Q or K;
+    rows that are not given contribute nothing."""
+    w = _small(n=150, hq=2, hkv=1, d=8, seed=42)
+    p = oracle.Params(n_init=1, n_local=1, topk_total=2, softmax_scale=0.5)
+    n = 150
+    pos = np.arange(n, dtype=np.int32)
+    Q, K, V = w["q"].astype(np.float64), w["k"][0].astype(np.float64), w["v"][0].astype(np.float64)
+    idx = oracle.select_blocks(w["q"], pos, w["k"][0], p)
+    mask = _selection_mask(idx, n)
+    rng = np.random.default_rng(6)
+    dO = rng.standard_normal(Q.shape).astype(np.float32)
+
+    def loss(Q_, K_, V_):
+        z = np.einsum("tgd,ud->gtu", Q_, K_) * 0.5
+        z = np.where(mask[None], z, -np.inf)
+        pr = np.exp(z - z.max(-1, keepdims=True))
+        pr /= pr.sum(-1, keepdims=True)
+        return float((np.einsum("gtu,ud->tgd", pr, V_) * dO).sum())
+
+    dQ, dK, dV = oracle.attn_bwd(w["q"], pos, w["k"][0], w["v"][0], idx, dO, p)
+    h = 1e-5
+    for arr, grad, which in ((Q, dQ, 0), (K, dK, 1), (V, dV, 2)):
+        for _ in range(12):
+            i = tuple(rng.integers(0, s) for s in arr.shape)
+            args = [Q.copy(), K.copy(), V.copy()]
+            args[which][i] += h
+            up = loss(*args)
+            args[which][i] -= 2 * h
+            fd = (up - loss(*args)) / (2 * h)
+            assert abs(fd - grad[i]) < 1e-6 * max(1.0, abs(fd)), (which, i, fd, grad[i])
+    np.testing.assert_allclose(dV.sum(0), dO.astype(np.float64).sum((0, 1)), atol=1e-10)
+    dQc, dKc, _ = oracle.attn_bwd(w["q"], pos, w["k"][0], np.full_like(w["v"][0], 0.7), idx, dO, p)
+    assert np.abs(dQc).max() < 1e-12 and np.abs(dKc).max() < 1e-12
+    # a subset of rows: gradients add up over disjoint row sets
+    a, b = np.arange(0, 70), np.arange(70, n)
+    parts = [oracle.attn_bwd(w["q"][r], pos[r], w["k"][0], w["v"][0], idx[r], dO[r], p) for r in (a, b)]
+    np.testing.assert_allclose(parts[0][1] + parts[1][1], dK, atol=1e-12)
+    np.testing.assert_allclose(np.concatenate([parts[0][0], parts[1][0]]), dQ, atol=1e-12)
+
+
 def test_softmax_scale_reaches_both_stages(oracle):
     """A dropped or doubled scale in either stage changes these numbers (d=16: scale 0.25 vs 1)."""
     w = _small(n=200, hq=2, hkv=1, d=16, seed=30)
