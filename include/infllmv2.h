@@ -201,6 +201,28 @@ int infllmv2_sparse_attn_fwd(const infllmv2_params *p, const void *q_d, const vo
                              const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
                              void *out_d, float *lse_d, void *stream);
 
+/*
+ * Gradients of stage 4 with respect to Q, K and V for a given selection.  The paper trains through this
+ * attention (Sec. 3.2; Alg. 2 returns the log-sum-exp for that purpose) but prints no backward algorithm: this is
+ * the chain rule on O = softmax(scale * q K^T) V over the keys stage 4 attends to.  The selection only picks
+ * blocks (Sec. 3.3), so nothing flows back into stages 1-3.
+ *   block_idx_d    as for infllmv2_sparse_attn_fwd, or NULL: every sequence attends densely (Eq. 1)
+ *   out_d, lse_d   device, what the forward call produced from the same inputs
+ *   dout_d         device, dtype [total_tokens, num_q_heads, head_dim]: gradient of the loss w.r.t. out
+ *   dq_d           device out, dtype [total_tokens, num_q_heads, head_dim]
+ *   dk_d, dv_d     device out, float32 [num_kv_heads, total_tokens, head_dim], 16-byte aligned; overwritten
+ *                  (each row sums the contributions of the num_q_heads / num_kv_heads heads of its group and of
+ *                  every query row that attends to it; added up with float atomics, so the last bits may differ
+ *                  between runs)
+ * Every head shape and dtype runs fp32 arithmetic on the vector units (no matrix-core path yet).  Obtains a
+ * [num_q_heads, total_tokens] float32 scratch from the stream-ordered pool (see the general rules).
+ */
+int infllmv2_sparse_attn_bwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
+                             int64_t kv_tok_stride, int64_t kv_head_stride, const int32_t *block_idx_d,
+                             const void *out_d, const float *lse_d, const void *dout_d,
+                             const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
+                             void *dq_d, float *dk_d, float *dv_d, void *stream);
+
 /* Dense causal GQA attention -- Eq. 1 (tile schedule of Appendix Alg. 3).  Arguments as above. */
 int infllmv2_dense_attn_fwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
                             int64_t kv_tok_stride, int64_t kv_head_stride,

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     dense_attn_fwd,
     lib,
     num_cmp,
+    sparse_attn_bwd,
     sparse_attn_fwd,
     sparse_decode,
     sparse_prefill,

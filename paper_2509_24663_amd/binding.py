@@ -71,6 +71,7 @@ _SIGNATURES = {
     "infllmv2_topk_pooled": (ctypes.c_int, [_PP, _P, _I64, _P, _P, _I32, _P, _P]),
     "infllmv2_sparse_attn_fwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _P, _I32, _P, _P, _P]),
     "infllmv2_dense_attn_fwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _I32, _P, _P, _P]),
+    "infllmv2_sparse_attn_bwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _P, _P, _P, _P, _I32, _P, _P, _P, _P]),
     "infllmv2_sparse_decode": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _I64, _P, _I64, _P, _P, _I32, _P, _P, _P,
                                               _P, _SZ, _P]),
     "infllmv2_decode_workspace_bytes": (_SZ, [_PP, _I32, _I32]),
@@ -260,6 +261,25 @@ def dense_attn_fwd(p: Params, q, k, v, cu_seqlens, out=None, lse=None):
                                        batch, _ptr(out), _ptr(lse), _stream())
     _check(st, "infllmv2_dense_attn_fwd")
     return out, lse
+
+
+def sparse_attn_bwd(p: Params, q, k, v, block_idx, out, lse, dout, cu_seqlens, dq=None, dk=None, dv=None):
+    """Gradients of stage 4 for a given selection (block_idx None: dense).  Returns (dq like q, dk, dv float32
+    [hkv, T, d])."""
+    cu_h, cu_d = _cu_pair(cu_seqlens)
+    batch = cu_h.numel() - 1
+    ts, hs = _kv_strides(k)
+    assert _kv_strides(v) == (ts, hs)
+    T = q.shape[0]
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty((p.num_kv_heads, T, p.head_dim), dtype=torch.float32, device=q.device) if dk is None else dk
+    dv = torch.empty((p.num_kv_heads, T, p.head_dim), dtype=torch.float32, device=q.device) if dv is None else dv
+    assert dout.is_contiguous() and out.is_contiguous() and dq.is_contiguous() and dk.is_contiguous() and dv.is_contiguous()
+    st = lib().infllmv2_sparse_attn_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), ts, hs, _ptr(block_idx), _ptr(out),
+                                        _ptr(lse), _ptr(dout), _ptr(cu_h), _ptr(cu_d), batch, _ptr(dq), _ptr(dk),
+                                        _ptr(dv), _stream())
+    _check(st, "infllmv2_sparse_attn_bwd")
+    return dq, dk, dv
 
 
 def decode_workspace_bytes(p: Params, batch: int, max_ctx_len: int) -> int:

@@ -251,6 +251,29 @@ int infllmv2_dense_attn_fwd(const infllmv2_params *p, const void *q_d, const voi
                        cu_seqlens_d, batch, out_d, lse_d, stream);
 }
 
+int infllmv2_sparse_attn_bwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
+                             int64_t kv_tok_stride, int64_t kv_head_stride, const int32_t *block_idx_d,
+                             const void *out_d, const float *lse_d, const void *dout_d,
+                             const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
+                             void *dq_d, float *dk_d, float *dv_d, void *stream) {
+    int st = check_params(p);
+    if (st) return st;
+    int64_t total;
+    int32_t max_len;
+    st = check_cu(cu_seqlens_h, cu_seqlens_d, batch, &total, &max_len);
+    if (st) return st;
+    if (total == 0) return INFLLMV2_OK;
+    if (q_d == nullptr || k_d == nullptr || v_d == nullptr || out_d == nullptr || lse_d == nullptr || dout_d == nullptr ||
+        dq_d == nullptr || dk_d == nullptr || dv_d == nullptr)
+        return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if (kv_tok_stride < p->head_dim || kv_head_stride < p->head_dim) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    if ((((uintptr_t)dk_d | (uintptr_t)dv_d) & 15) != 0) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    Launch L{p, prefill_map(p, cu_seqlens_d, nullptr, batch, total, kv_tok_stride, kv_head_stride, 0),
+             (hipStream_t)stream, max_len};
+    return launch_attn_bwd(L, q_d, k_d, v_d, block_idx_d, block_idx_d ? p->dense_threshold : 0, out_d, lse_d, dout_d,
+                           dq_d, dk_d, dv_d, cu_seqlens_h);
+}
+
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 size_t infllmv2_decode_workspace_bytes(const infllmv2_params *p, int32_t batch, int32_t max_ctx_len) {

@@ -141,6 +141,11 @@ int launch_topk(const Launch &L, const float *s_in, int64_t row_stride, int32_t 
 int launch_attn(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
                 int dense_below, void *out, float *lse, const int32_t *cu_h);
 
+// gradients of stage 4 (idx == nullptr: dense for every sequence); dk, dv float32 [hkv, T, d], zeroed inside
+int launch_attn_bwd(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx, int dense_below,
+                    const void *out, const float *lse, const void *dout, void *dq, float *dk, float *dv,
+                    const int32_t *cu_h);
+
 inline int hip_status(hipError_t e) { return e == hipSuccess ? INFLLMV2_OK : INFLLMV2_ERR_HIP; }
 
 // Stream-ordered scratch (hipMallocAsync / hipFreeAsync) comes from the current device's default memory pool.  By

@@ -125,3 +125,24 @@ def test_pooled_entry_points_validate_on_the_host(m):
     assert L.infllmv2_topk_pooled(ctypes.byref(p), None, 0, empty, one, 1, None, None) == 0
     bad = m.Params.make("bf16", 32, 2, 128, pool_stride=0)
     assert L.infllmv2_block_scores_pooled(ctypes.byref(bad), one, one, 61, cu_p, one, one, 1, one, 16, None) == INVALID
+
+
+def test_backward_entry_point_validates_on_the_host(m):
+    INVALID = -1
+    L = m.lib()
+    p = m.Params.make("bf16", 32, 2, 128)
+    cu = np.array([0, 100], dtype=np.int32)
+    cu_p, one = cu.ctypes.data_as(ctypes.c_void_p), ctypes.c_void_p(256)
+
+    def call(**over):
+        a = dict(q=one, k=one, v=one, ts=256, hs=128, idx=one, out=one, lse=one, dout=one, dq=one, dk=one, dv=one)
+        a.update(over)
+        return L.infllmv2_sparse_attn_bwd(ctypes.byref(p), a["q"], a["k"], a["v"], a["ts"], a["hs"], a["idx"], a["out"],
+                                          a["lse"], a["dout"], cu_p, one, 1, a["dq"], a["dk"], a["dv"], None)
+    for name in ("q", "k", "v", "out", "lse", "dout", "dq", "dk", "dv"):
+        assert call(**{name: None}) == INVALID, name
+    assert call(ts=64) == INVALID                                    # token stride < head_dim
+    assert call(dk=ctypes.c_void_p(260)) == INVALID                  # dK not 16-byte aligned
+    empty = np.array([0, 0], dtype=np.int32).ctypes.data_as(ctypes.c_void_p)
+    assert L.infllmv2_sparse_attn_bwd(ctypes.byref(p), None, None, None, 0, 0, None, None, None, None, empty, one, 1,
+                                      None, None, None, None) == 0

@@ -559,3 +559,78 @@ def test_topk_long_rows_bit_exact(m, oracle, kind, topk_total):
                 sc[0, t, j] = cmp_o[r, j]
     idx_p = to_np(m.topk_pooled(gp, torch.from_numpy(sc).cuda(), si))
     np.testing.assert_array_equal(idx_p[0, rows], idx_o)
+
+
+# ----------------------------------------------------------------------------- gradients of stage 4
+def _check_backward(m, oracle, w, gp, op, dtype, dense_all=False):
+    """dQ, dK, dV of the GPU (through the C ABI, from the GPU's own forward outputs and selection) against the
+    oracle's float64 gradients for the same selection.  Errors are measured relative to the largest magnitude of
+    each gradient (at least 0.1; inputs are O(1)): fp32 data max 2e-4 / mean 5e-5 (fast exponentials, float accumulation over up to n rows); bf16 data max 2e-2 /
+    mean 2e-3, the forward bar, because Delta = <dO, O> is formed from the bf16-rounded O and dQ is stored in bf16."""
+    cu = w["cu_seqlens"]
+    T, hq, d = w["q"].shape
+    hkv = w["k"].shape[0]
+    G = hq // hkv
+    q, k, v = (to_dev(w[x], dtype) for x in ("q", "k", "v"))
+    rng = np.random.default_rng(12345 + T)
+    dout_np = synth.round_to_bf16(rng.standard_normal((T, hq, d)).astype(np.float32)) if dtype == "bf16" else \
+        rng.standard_normal((T, hq, d)).astype(np.float32)
+    dout = to_dev(dout_np, dtype)
+    si = m.SeqInfo(cu)
+    if dense_all:
+        out, lse = m.dense_attn_fwd(gp, q, k, v, si)
+        idx_d = None
+    else:
+        res = m.sparse_prefill(gp, q, k, v, si)
+        out, lse, idx_d = res["out"], res["lse"], res["block_idx"]
+    dq, dk, dv = m.sparse_attn_bwd(gp, q, k, v, idx_d, out, lse, dout, si)
+    dq2, dk2, dv2 = m.sparse_attn_bwd(gp, q, k, v, idx_d, out, lse, dout, si)
+    torch.cuda.synchronize()
+    assert torch.equal(dq, dq2)                                  # no atomics on this path
+    dq_g, dk_g, dv_g = to_np(dq), to_np(dk), to_np(dv)
+    idx_g = None if idx_d is None else to_np(idx_d)
+    max_tol, mean_tol = (2e-2, 2e-3) if dtype == "bf16" else (2e-4, 5e-5)
+    worst = 0.0
+    for s in range(len(cu) - 1):
+        a, b = int(cu[s]), int(cu[s + 1])
+        if a == b:
+            continue
+        pos = np.arange(b - a, dtype=np.int32)
+        dense = dense_all or (b - a) < op.dense_threshold
+        for h in range(hkv):
+            sel = None if dense else idx_g[h, a:b]
+            dQ, dK, dV = oracle.attn_bwd(w["q"][a:b, h * G:(h + 1) * G], pos, w["k"][h, a:b], w["v"][h, a:b], sel,
+                                         dout_np[a:b, h * G:(h + 1) * G], op)
+            for name, got, ref in (("dq", dq_g[a:b, h * G:(h + 1) * G], dQ), ("dk", dk_g[h, a:b], dK),
+                                   ("dv", dv_g[h, a:b], dV)):
+                # (a single visible key gives dz = 0 exactly: dQ = dK = 0, so the scale has a floor)
+                scale = max(float(np.abs(ref).max()), 0.1)
+                err = np.abs(got.astype(np.float64) - ref) / scale
+                assert err.max() <= max_tol and err.mean() <= mean_tol, (name, s, h, err.max(), err.mean())
+                worst = max(worst, float(err.max()))
+    # float atomics: a second run may differ in the last bits only
+    np.testing.assert_allclose(to_np(dk2), dk_g, rtol=0, atol=1e-5 * max(1.0, float(np.abs(dk_g).max())))
+    np.testing.assert_allclose(to_np(dv2), dv_g, rtol=0, atol=1e-5 * max(1.0, float(np.abs(dv_g).max())))
+    return worst
+
+
+@pytest.mark.parametrize("n", [1, 65, 200, 700])
+def test_backward_fp32_small_heads(m, oracle, n):
+    w = synth.make_prefill(n, 4, 2, 64, seed=300 + n, dtype="fp32")
+    gp, op = _params(m, oracle, "fp32", 4, 2, 64, n_init=1, n_local=1, topk_total=3)
+    _check_backward(m, oracle, w, gp, op, "fp32")
+
+
+def test_backward_fp32_group_of_16_d128_and_dense(m, oracle):
+    w = synth.make_prefill(330, 16, 1, 128, seed=311, dtype="fp32")
+    gp, op = _params(m, oracle, "fp32", 16, 1, 128, n_init=1, n_local=2, topk_total=4)
+    _check_backward(m, oracle, w, gp, op, "fp32")
+    _check_backward(m, oracle, w, gp, op, "fp32", dense_all=True)
+
+
+def test_backward_bf16_paper_head_shape_varlen_with_switch(m, oracle):
+    """Paper head shape in bf16, packed sequences on both sides of the dense threshold, one crossing a chunk of
+    256 tokens several times."""
+    w = synth.make_varlen([300, 50, 900], 32, 2, 128, seed=312, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=2, topk_total=5, dense_threshold=256)
+    _check_backward(m, oracle, w, gp, op, "bf16")
