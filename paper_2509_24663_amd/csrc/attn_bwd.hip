@@ -5,7 +5,8 @@
 //     p_u  = exp(z_u - lse)                     dp_u = <dO, v_u>             Delta = <dO, O> (= sum_u p_u dp_u)
 //     dz_u = p_u (dp_u - Delta)                 dq   = scale * sum_u dz_u k_u
 //     dk_u += scale * dz_u q                    dv_u += p_u dO               (summed over rows and over the group)
-// fp32 arithmetic on the vector units for any G <= 16, d in {64, 128}, fp32 or bf16 data, in three kernels:
+// This file: fp32 arithmetic on the vector units for any G <= 16, d in {64, 128}, fp32 or bf16 data (the paper's
+// head shape in bf16 takes the matrix-core path of attn_bwd_mfma.hip instead), in three kernels:
 //   delta : Delta per (row, query head)
 //   dq    : one workgroup per (row, KV head), the loop of the forward generic kernel
 //   dkv   : one workgroup per (KV block, chunk of 256 later tokens, KV head): finds the tokens of its chunk that
@@ -299,9 +300,16 @@ int launch_d(const Launch &L, const void *q, const void *k, const void *v, const
 
 }  // namespace
 
+// matrix-core path for the paper's head shape (attn_bwd_mfma.hip); INFLLMV2_ERR_UNSUPPORTED = not covered
+int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
+                         int dense_below, const void *out, const float *lse, const void *dout, void *dq, float *dk,
+                         float *dv, const int32_t *cu_h);
+
 int launch_attn_bwd(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx, int dense_below,
                     const void *out, const float *lse, const void *dout, void *dq, float *dk, float *dv,
                     const int32_t *cu_h) {
+    const int st = launch_attn_bwd_mfma(L, q, k, v, idx, dense_below, out, lse, dout, dq, dk, dv, cu_h);
+    if (st != INFLLMV2_ERR_UNSUPPORTED) return st;
     return L.p->dtype == INFLLMV2_BF16
                ? launch_d<bf16_t>(L, q, k, v, idx, dense_below, out, lse, dout, dq, dk, dv, cu_h)
                : launch_d<float>(L, q, k, v, idx, dense_below, out, lse, dout, dq, dk, dv, cu_h);

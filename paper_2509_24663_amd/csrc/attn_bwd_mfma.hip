@@ -1,0 +1,413 @@
+// Gradients of stage 4 on the matrix cores for the paper's head shape (bf16, 16 query heads per KV head,
+// d_h = 128).  Same mathematics as attn_bwd.hip (chain rule on O = softmax(scale q K^T) V with the stored
+// log-sum-exp; the paper prints no backward algorithm):
+//     P = exp(z - lse),  dP = dO V^T,  dZ = P o (dP - Delta),  dQ = scale dZ K,  dK = scale dZ^T Q,  dV = P^T dO.
+// Every product is an MFMA with the 16 heads of a token as one matrix dimension.  Operands go from global
+// memory (L2) straight into MFMA registers -- no LDS in the main kernels -- which needs three transposed copies
+// made by two pre-passes into stream-ordered scratch:
+//   prep : per (token, KV head) Q^T and dO^T as [128 dims][16 heads]; Delta = <dO, O> and lse * log2(e) per
+//          (token, query head), token-major
+//   kt   : per 64-key block K^T as [128 dims][64 keys]
+//   dq   : one wavefront per (token, KV head), loop over the token's selected blocks.  Per 16 keys:
+//          S^T = K Q^T and dP^T = V dO^T (4 + 4 MFMA 16x16x32: keys x heads), dZ^T in registers with one head per
+//          lane, dQ^T += K^T dZ^T (8 MFMA 16x16x16: dims x heads).
+//   dkv  : one workgroup of 4 wavefronts per (64-key block, chunk of later tokens, KV head); wavefront w owns keys
+//          16 w .. 16 w + 15 with their K and V fragments in registers.  The workgroup lists the tokens of its
+//          chunk that selected the block; per token S = Q K^T and dP = dO V^T (heads x keys), then
+//          dV += P^T dO and dK += dZ^T Q (8 + 8 MFMA 16x16x16: keys x dims, contraction over the 16 heads).
+//          Results are added to the float32 outputs with atomics, one add per element and workgroup.
+#include <algorithm>
+
+#include "common.h"
+
+namespace ifv2 {
+
+namespace {
+
+constexpr int D = 128, G = 16;
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr int DKV_CHUNK = 2048;          // tokens per dkv workgroup
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef short short4v __attribute__((ext_vector_type(4)));
+
+__device__ inline float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ inline short4v to_bf16x4(float a, float b, float c, float d) {
+    short4v r;
+    r[0] = (short)float_to_bf16(a);
+    r[1] = (short)float_to_bf16(b);
+    r[2] = (short)float_to_bf16(c);
+    r[3] = (short)float_to_bf16(d);
+    return r;
+}
+
+struct BwdM {
+    const uint16_t *q, *k, *v, *out, *dout;
+    const float *lse;
+    const int32_t *idx;          // nullptr: dense
+    int topk_total, dense_below, hq;
+    float scale;
+    RowMap map;
+    // scratch
+    uint16_t *qt, *dot;          // [T][hkv][128][16]
+    float *lse2, *delta;         // [T][hq]
+    uint16_t *kt;                // [hkv][blocks][128][64]
+    int64_t nblocks;             // 64-key blocks over all sequences
+    // results
+    uint16_t *dq;
+    float *dk, *dv;
+};
+
+// first 64-key block of sequence seq in the packed block numbering
+__device__ inline int block_base(const RowMap &m, int seq) {
+    int b = 0;
+    for (int s = 0; s < seq; ++s) b += (m.cu[s + 1] - m.cu[s] + kBlock - 1) / kBlock;
+    return b;
+}
+
+// ------------------------------------------------------------------------------------------ pre-passes
+__global__ void __launch_bounds__(256) bwd_prep_kernel(BwdM a) {
+    __shared__ __attribute__((aligned(16))) uint16_t tq[D][G], tg[D][G];
+    const int row = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+    const int head = tid >> 4, d0 = (tid & 15) * 8;
+    const int64_t off = ((int64_t)row * a.hq + h * G + head) * D + d0;
+    const uint4 rq = *reinterpret_cast<const uint4 *>(a.q + off);
+    const uint4 rg = *reinterpret_cast<const uint4 *>(a.dout + off);
+    const uint4 ro = *reinterpret_cast<const uint4 *>(a.out + off);
+    const uint32_t wq[4] = {rq.x, rq.y, rq.z, rq.w}, wg[4] = {rg.x, rg.y, rg.z, rg.w}, wo[4] = {ro.x, ro.y, ro.z, ro.w};
+    float dot = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        tq[d0 + 2 * e][head] = (uint16_t)(wq[e] & 0xffffu);
+        tq[d0 + 2 * e + 1][head] = (uint16_t)(wq[e] >> 16);
+        tg[d0 + 2 * e][head] = (uint16_t)(wg[e] & 0xffffu);
+        tg[d0 + 2 * e + 1][head] = (uint16_t)(wg[e] >> 16);
+        dot += __uint_as_float(wg[e] << 16) * __uint_as_float(wo[e] << 16);
+        dot += __uint_as_float(wg[e] & 0xffff0000u) * __uint_as_float(wo[e] & 0xffff0000u);
+    }
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) dot += __shfl_xor(dot, o);
+    if ((tid & 15) == 0) {
+        const int qh = h * G + head;
+        a.delta[(int64_t)row * a.hq + qh] = dot;
+        a.lse2[(int64_t)row * a.hq + qh] = a.lse[qhead_row(a.map, qh, a.hq, row)] * LOG2E;
+    }
+    __syncthreads();
+    const int64_t tile = ((int64_t)row * a.map.num_kv_heads + h) * (D * G);
+    reinterpret_cast<uint4 *>(a.qt + tile)[tid] = reinterpret_cast<const uint4 *>(&tq[0][0])[tid];
+    reinterpret_cast<uint4 *>(a.dot + tile)[tid] = reinterpret_cast<const uint4 *>(&tg[0][0])[tid];
+}
+
+__global__ void __launch_bounds__(256) bwd_kt_kernel(BwdM a) {
+    constexpr int KS = kBlock + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t tk[D][KS];
+    __shared__ int s_seq, s_j;
+    const int tid = threadIdx.x, h = blockIdx.y;
+    if (tid == 0) {
+        int rem = blockIdx.x, s = 0;
+        for (; s < a.map.batch; ++s) {
+            const int nb = (a.map.cu[s + 1] - a.map.cu[s] + kBlock - 1) / kBlock;
+            if (rem < nb) break;
+            rem -= nb;
+        }
+        s_seq = s;
+        s_j = rem;
+    }
+    __syncthreads();
+    const int seq = s_seq, j = s_j;
+    if (seq >= a.map.batch) return;
+    const int tok0 = a.map.cu[seq], len = a.map.cu[seq + 1] - tok0;
+    const uint16_t *kb = a.k + (int64_t)tok0 * a.map.kv_tok_stride + (int64_t)h * a.map.kv_head_stride;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int c = tid + r * 256, key = c >> 4, d0 = (c & 15) * 8, u = j * kBlock + key;
+        uint4 raw = make_uint4(0, 0, 0, 0);
+        if (u < len) raw = *reinterpret_cast<const uint4 *>(kb + (int64_t)u * a.map.kv_tok_stride + d0);
+        const uint32_t wd[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            tk[d0 + 2 * e][key] = (uint16_t)(wd[e] & 0xffffu);
+            tk[d0 + 2 * e + 1][key] = (uint16_t)(wd[e] >> 16);
+        }
+    }
+    __syncthreads();
+    uint16_t *dst = a.kt + ((int64_t)h * a.nblocks + blockIdx.x) * (D * kBlock);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int c = tid + r * 256, d = c >> 3, k0 = (c & 7) * 8;
+        *reinterpret_cast<uint4 *>(dst + d * kBlock + k0) = *reinterpret_cast<const uint4 *>(&tk[d][k0]);
+    }
+}
+
+__global__ void __launch_bounds__(256) bwd_fill_zero_kernel(float4 *p, int64_t n4) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256)
+        p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// ------------------------------------------------------------------------------------------ dQ
+__global__ void __launch_bounds__(256) bwd_dq_mfma_kernel(BwdM a) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int row = blockIdx.x * 4 + w, h = blockIdx.y;
+    if (row >= a.map.total_rows) return;
+    const RowLoc loc = locate(a.map, row);
+    const int t = loc.pos, bt = t / kBlock;
+    const bool dense = a.idx == nullptr || loc.len < a.dense_below;
+    const int32_t *my_idx = dense ? nullptr : a.idx + head_row(a.map, h, row) * a.topk_total;
+    const int nsteps = dense ? bt + 1 : a.topk_total;
+    const int n16 = lane & 15, g = lane >> 4;
+    const int qh = h * G + n16;                                   // this lane's head
+    // Q and dO rows of head n16 as B operands (k = 8 dims at 32 ks + 8 g)
+    bf16x8 qf[4], gf[4];
+    {
+        const uint16_t *qp = a.q + ((int64_t)row * a.hq + qh) * D + g * 8;
+        const uint16_t *gp = a.dout + ((int64_t)row * a.hq + qh) * D + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(qp + ks * 32));
+            gf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(gp + ks * 32));
+        }
+    }
+    const float nlse2 = -a.lse2[(int64_t)row * a.hq + qh], delta = a.delta[(int64_t)row * a.hq + qh];
+    const float c = a.scale * LOG2E;
+    const uint16_t *kb = a.k + loc.kv_base + (int64_t)h * a.map.kv_head_stride;
+    const uint16_t *vb = a.v + loc.kv_base + (int64_t)h * a.map.kv_head_stride;
+    const uint16_t *ktb = a.kt + ((int64_t)h * a.nblocks + block_base(a.map, loc.seq)) * (D * kBlock);
+    f32x4 acc[8];                                                 // dQ^T: dims 16 dt + 4 g + r, head n16
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int s = 0; s < nsteps; ++s) {
+        const int j = dense ? s : my_idx[s];
+        if (j < 0 || j > bt) continue;
+        const uint16_t *ktj = ktb + (int64_t)j * (D * kBlock);
+        const int key_limit = j == bt ? t - j * kBlock : kBlock;    // keys of the block this token may see: 0 .. limit
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+            if (16 * kt > key_limit) break;                          // wave-uniform: nothing visible in this tile
+            // A operands: K and V rows of key 16 kt + n16 (clamped into the sequence; masked below)
+            const int u = min(j * kBlock + 16 * kt + n16, loc.len - 1);
+            const uint16_t *kr = kb + (int64_t)u * a.map.kv_tok_stride + g * 8;
+            const uint16_t *vr = vb + (int64_t)u * a.map.kv_tok_stride + g * 8;
+            f32x4 st = f32x4{0.f, 0.f, 0.f, 0.f}, dpt = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(kr + ks * 32));
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(vr + ks * 32));
+                st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], st, 0, 0, 0);
+                dpt = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, gf[ks], dpt, 0, 0, 0);
+            }
+            // element r: key 16 kt + 4 g + r, head n16
+            float dz[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float p = 16 * kt + 4 * g + r <= key_limit ? exp2_fast(__builtin_fmaf(st[r], c, nlse2)) : 0.f;
+                dz[r] = p * (dpt[r] - delta);
+            }
+            const short4v dzb = to_bf16x4(dz[0], dz[1], dz[2], dz[3]);
+            // dQ^T (dims x heads) += K^T (dims x keys) dZ^T (keys x heads); A: row 16 dt + n16 of K^T, keys 16 kt + 4 g ..
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                const short4v ka = *reinterpret_cast<const short4v *>(ktj + (16 * dt + n16) * kBlock + 16 * kt + 4 * g);
+                acc[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ka, dzb, acc[dt], 0, 0, 0);
+            }
+        }
+    }
+    uint16_t *dq = a.dq + ((int64_t)row * a.hq + qh) * D + 4 * g;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+        uint2 pk;
+        pk.x = (uint32_t)float_to_bf16(acc[dt][0] * a.scale) | ((uint32_t)float_to_bf16(acc[dt][1] * a.scale) << 16);
+        pk.y = (uint32_t)float_to_bf16(acc[dt][2] * a.scale) | ((uint32_t)float_to_bf16(acc[dt][3] * a.scale) << 16);
+        *reinterpret_cast<uint2 *>(dq + 16 * dt) = pk;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ dK, dV
+// is block j in the ascending, -1 padded list e[0 .. n)?
+__device__ inline bool list_has(const int32_t *e, int n, int j) {
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        const int x = e[mid];
+        if (x >= 0 && x < j) lo = mid + 1; else hi = mid;
+    }
+    return lo < n && e[lo] == j;
+}
+
+__global__ void __launch_bounds__(256) bwd_dkv_mfma_kernel(BwdM a) {
+    __shared__ int s_seq, s_j, s_list[DKV_CHUNK], s_wave_cnt[4];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int h = blockIdx.z;
+    if (tid == 0) {
+        int rem = blockIdx.y, s = 0;
+        for (; s < a.map.batch; ++s) {
+            const int nb = (a.map.cu[s + 1] - a.map.cu[s] + kBlock - 1) / kBlock;
+            if (rem < nb) break;
+            rem -= nb;
+        }
+        s_seq = s;
+        s_j = rem;
+    }
+    __syncthreads();
+    const int seq = s_seq, j = s_j;
+    if (seq >= a.map.batch) return;
+    const int tok0 = a.map.cu[seq], len = a.map.cu[seq + 1] - tok0;
+    const int c0 = blockIdx.x * DKV_CHUNK, c1 = min(c0 + DKV_CHUNK, len);
+    if (c1 <= j * kBlock || c0 >= len) return;
+    const bool dense = a.idx == nullptr || len < a.dense_below;
+
+    // ---- tokens of the chunk that selected the block, in token order (rounds of 256)
+    int total = 0;
+    for (int r0 = c0; r0 < c1; r0 += 256) {
+        const int t_mine = r0 + tid;
+        bool sel = t_mine < c1 && t_mine >= j * kBlock;
+        if (sel && !dense) sel = list_has(a.idx + head_row(a.map, h, tok0 + t_mine) * a.topk_total, a.topk_total, j);
+        const uint64_t bal = __ballot(sel);
+        if (lane == 0) s_wave_cnt[w] = __popcll(bal);
+        __syncthreads();
+        int base = total;
+        for (int x = 0; x < 4; ++x) {
+            if (x < w) base += s_wave_cnt[x];
+            total += s_wave_cnt[x];
+        }
+        if (sel) s_list[base + __popcll(bal & ((1ull << lane) - 1ull))] = t_mine;
+        __syncthreads();
+    }
+    if (total == 0) return;
+
+    const int n16 = lane & 15, g = lane >> 4;
+    // K and V rows of key 16 w + n16 as B operands (k = 8 dims at 32 ks + 8 g); rows past the sequence are never
+    // visible to any token (causal), their contributions are masked to zero
+    const int key = j * kBlock + 16 * w + n16;
+    bf16x8 kf[4], vf[4];
+    {
+        const int64_t base = (int64_t)tok0 * a.map.kv_tok_stride + (int64_t)h * a.map.kv_head_stride +
+                             (int64_t)min(key, len - 1) * a.map.kv_tok_stride + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            kf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(a.k + base + ks * 32));
+            vf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(a.v + base + ks * 32));
+        }
+    }
+    const float c = a.scale * LOG2E;
+    f32x4 acc_k[8], acc_v[8];                  // rows: keys 16 w + 4 g + r; columns: dims 16 dt + n16
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+        acc_k[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc_v[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    for (int it = 0; it < total; ++it) {
+        const int t = s_list[it], row = tok0 + t;
+        // A operands: Q and dO rows of head n16
+        const uint16_t *qp = a.q + ((int64_t)row * a.hq + h * G + n16) * D + g * 8;
+        const uint16_t *gp = a.dout + ((int64_t)row * a.hq + h * G + n16) * D + g * 8;
+        f32x4 sacc = f32x4{0.f, 0.f, 0.f, 0.f}, dpacc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8 qa = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(qp + ks * 32));
+            const bf16x8 ga = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(gp + ks * 32));
+            sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa, kf[ks], sacc, 0, 0, 0);
+            dpacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ga, vf[ks], dpacc, 0, 0, 0);
+        }
+        // element r: head 4 g + r, key n16 of this wave's tile
+        const float4 l2 = *reinterpret_cast<const float4 *>(a.lse2 + (int64_t)row * a.hq + h * G + 4 * g);
+        const float4 dl = *reinterpret_cast<const float4 *>(a.delta + (int64_t)row * a.hq + h * G + 4 * g);
+        const float l2a[4] = {l2.x, l2.y, l2.z, l2.w}, dla[4] = {dl.x, dl.y, dl.z, dl.w};
+        const bool visible = key <= t;
+        float p[4], dz[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            p[r] = visible ? exp2_fast(__builtin_fmaf(sacc[r], c, -l2a[r])) : 0.f;
+            dz[r] = p[r] * (dpacc[r] - dla[r]);
+        }
+        const short4v pb = to_bf16x4(p[0], p[1], p[2], p[3]), dzb = to_bf16x4(dz[0], dz[1], dz[2], dz[3]);
+        // dV (keys x dims) += P^T (keys x heads) dO (heads x dims); B: dO^T row 16 dt + n16, heads 4 g .. 4 g + 3
+        const uint16_t *gt = a.dot + ((int64_t)row * a.map.num_kv_heads + h) * (D * G) + n16 * G + 4 * g;
+        const uint16_t *qt = a.qt + ((int64_t)row * a.map.num_kv_heads + h) * (D * G) + n16 * G + 4 * g;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            const short4v gb = *reinterpret_cast<const short4v *>(gt + dt * 16 * G);
+            const short4v qb = *reinterpret_cast<const short4v *>(qt + dt * 16 * G);
+            acc_v[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, gb, acc_v[dt], 0, 0, 0);
+            acc_k[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(dzb, qb, acc_k[dt], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int u = j * kBlock + 16 * w + 4 * g + r;
+        if (u < len) {
+            float *dk = a.dk + ((int64_t)h * a.map.total_rows + tok0 + u) * D + n16;
+            float *dv = a.dv + ((int64_t)h * a.map.total_rows + tok0 + u) * D + n16;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                atomicAdd(dk + 16 * dt, acc_k[dt][r] * a.scale);
+                atomicAdd(dv + 16 * dt, acc_v[dt][r]);
+            }
+        }
+    }
+}
+
+inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+}  // namespace
+
+// Returns INFLLMV2_ERR_UNSUPPORTED (nothing launched) for shapes this path does not cover.
+int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
+                         int dense_below, const void *out, const float *lse, const void *dout, void *dq, float *dk,
+                         float *dv, const int32_t *cu_h) {
+    const infllmv2_params *p = L.p;
+    if (p->dtype != INFLLMV2_BF16 || p->head_dim != D || p->num_q_heads / p->num_kv_heads != G)
+        return INFLLMV2_ERR_UNSUPPORTED;
+    if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out | (uintptr_t)dout | (uintptr_t)dq) & 15) != 0 ||
+        L.map.kv_tok_stride % 8 != 0 || L.map.kv_head_stride % 8 != 0)
+        return INFLLMV2_ERR_UNSUPPORTED;
+    const int64_t rows = L.map.total_rows;
+    if (rows == 0) return INFLLMV2_OK;
+    int64_t nblocks = 0;
+    for (int s = 0; s < L.map.batch; ++s) nblocks += (cu_h[s + 1] - cu_h[s] + kBlock - 1) / kBlock;
+    const int hkv = p->num_kv_heads, hq = p->num_q_heads;
+    if (nblocks > 65535 || hkv > 65535 || rows > 0x7fffffff / 4) return INFLLMV2_ERR_UNSUPPORTED;
+    const size_t b_t = align256((size_t)rows * hkv * D * G * sizeof(uint16_t));
+    const size_t b_f = align256((size_t)rows * hq * sizeof(float));
+    const size_t b_kt = align256((size_t)hkv * nblocks * D * kBlock * sizeof(uint16_t));
+    keep_freed_memory_in_pool();
+    char *ws = nullptr;
+    if (hipMallocAsync((void **)&ws, 2 * b_t + 2 * b_f + b_kt, L.stream) != hipSuccess) return INFLLMV2_ERR_HIP;
+    BwdM a;
+    a.q = (const uint16_t *)q;
+    a.k = (const uint16_t *)k;
+    a.v = (const uint16_t *)v;
+    a.out = (const uint16_t *)out;
+    a.dout = (const uint16_t *)dout;
+    a.lse = lse;
+    a.idx = idx;
+    a.topk_total = p->topk_total;
+    a.dense_below = dense_below;
+    a.hq = hq;
+    a.scale = p->softmax_scale;
+    a.map = L.map;
+    a.qt = (uint16_t *)ws;
+    a.dot = (uint16_t *)(ws + b_t);
+    a.lse2 = (float *)(ws + 2 * b_t);
+    a.delta = (float *)(ws + 2 * b_t + b_f);
+    a.kt = (uint16_t *)(ws + 2 * b_t + 2 * b_f);
+    a.nblocks = nblocks;
+    a.dq = (uint16_t *)dq;
+    a.dk = dk;
+    a.dv = dv;
+    const int64_t n4 = rows * hkv * D / 4;
+    const unsigned zg = (unsigned)std::min<int64_t>((n4 + 255) / 256, 8192);
+    hipLaunchKernelGGL(bwd_fill_zero_kernel, dim3(zg), dim3(256), 0, L.stream, (float4 *)dk, n4);
+    hipLaunchKernelGGL(bwd_fill_zero_kernel, dim3(zg), dim3(256), 0, L.stream, (float4 *)dv, n4);
+    hipLaunchKernelGGL(bwd_prep_kernel, dim3((unsigned)rows, hkv), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(bwd_kt_kernel, dim3((unsigned)nblocks, hkv), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(bwd_dq_mfma_kernel, dim3((unsigned)((rows + 3) / 4), hkv), dim3(256), 0, L.stream, a);
+    const unsigned chunks = (unsigned)((L.max_len + DKV_CHUNK - 1) / DKV_CHUNK);
+    hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(chunks, (unsigned)nblocks, hkv), dim3(256), 0, L.stream, a);
+    const hipError_t e = hipGetLastError();
+    (void)hipFreeAsync(ws, L.stream);
+    return hip_status(e);
+}
+
+}  // namespace ifv2

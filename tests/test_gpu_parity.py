@@ -634,3 +634,14 @@ def test_backward_bf16_paper_head_shape_varlen_with_switch(m, oracle):
     w = synth.make_varlen([300, 50, 900], 32, 2, 128, seed=312, dtype="bf16")
     gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=2, topk_total=5, dense_threshold=256)
     _check_backward(m, oracle, w, gp, op, "bf16")
+
+
+@pytest.mark.parametrize("n", [1, 63, 64, 129, 2500])
+def test_backward_bf16_matrix_core_path(m, oracle, n):
+    """The matrix-core backward (bf16, 16 heads per KV head, d 128): ragged lengths, a sequence longer than one
+    2048-token chunk of the dK/dV kernel, sparse and dense."""
+    w = synth.make_prefill(n, 32, 2, 128, seed=320 + n, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=2, topk_total=6)
+    _check_backward(m, oracle, w, gp, op, "bf16")
+    if n <= 129:
+        _check_backward(m, oracle, w, gp, op, "bf16", dense_all=True)
