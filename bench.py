@@ -52,6 +52,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C3", choices=["C2", "C3"])
     ap.add_argument("--dense-steps", type=int, default=1, help="timed runs of the dense path at the same shape (0 = skip)")
+    ap.add_argument("--backward-steps", type=int, default=1, help="timed runs of the backward of stage 4 (0 = skip)")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=6144, help="query rows per KV head the oracle is timed on")
@@ -226,6 +227,27 @@ def main() -> int:
                  "speedup_sparse_attn_only": round(dms / stage_ms["sparse_attn_fwd"], 2)}
         del od, ld
 
+    # ------------------------------------------------------------------ gradients of stage 4 for the same selection
+    backward = None
+    if args.backward_steps > 0:
+        dout = torch.randn_like(q)
+        dq, dk, dv = m.sparse_attn_bwd(gp, q, k, v, bufs["block_idx"], bufs["out"], bufs["lse"], dout, si)
+        torch.cuda.synchronize()
+        e0, e1 = _events(torch, 2)
+        e0.record()
+        for _ in range(args.backward_steps):
+            m.sparse_attn_bwd(gp, q, k, v, bufs["block_idx"], bufs["out"], bufs["lse"], dout, si, dq=dq, dk=dk, dv=dv)
+        e1.record()
+        torch.cuda.synchronize()
+        bms = e0.elapsed_time(e1) / args.backward_steps
+        # S and dP are recomputed in both kernels: 3 products for dQ, 4 for dK/dV, against 2 in the forward pass
+        bfl = 3.5 * attn_flops
+        backward = {"ms": round(bms, 2), "tflops": round(bfl / (bms * 1e-3) / 1e12, 1),
+                    "frac_mfma_peak": round(bfl / (bms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),
+                    "ratio_to_forward_attn": round(bms / stage_ms["sparse_attn_fwd"], 1),
+                    "note": "infllmv2_sparse_attn_bwd (dQ, dK, dV for the same selection); not part of the step"}
+        del dout, dq, dk, dv
+
     # ------------------------------------------------------------------ decode workload (config 4)
     decode = None
     if not args.no_decode:
@@ -270,6 +292,7 @@ def main() -> int:
                               "note": "stage 2 with lse_mode 1 (pass 1 over K^C2, Sec. 3.4); the selection it produces "
                                       "differs from the exact one, so the headline keeps lse_mode 0"},
         "dense_same_shape": dense,
+        "backward_same_selection": backward,
         "decode": decode,
         "cpu_baseline": cpu,
         "frac_mfma_peak_whole_step": round(tflops / PEAK_BF16_MFMA_TFLOPS, 4),

@@ -210,12 +210,15 @@ int infllmv2_sparse_attn_fwd(const infllmv2_params *p, const void *q_d, const vo
  *   out_d, lse_d   device, what the forward call produced from the same inputs
  *   dout_d         device, dtype [total_tokens, num_q_heads, head_dim]: gradient of the loss w.r.t. out
  *   dq_d           device out, dtype [total_tokens, num_q_heads, head_dim]
- *   dk_d, dv_d     device out, float32 [num_kv_heads, total_tokens, head_dim], 16-byte aligned; overwritten
- *                  (each row sums the contributions of the num_q_heads / num_kv_heads heads of its group and of
- *                  every query row that attends to it; added up with float atomics, so the last bits may differ
- *                  between runs)
- * Every head shape and dtype runs fp32 arithmetic on the vector units (no matrix-core path yet).  Obtains a
- * [num_q_heads, total_tokens] float32 scratch from the stream-ordered pool (see the general rules).
+ *   dk_d, dv_d     device out, float32 [num_kv_heads, total_tokens, head_dim], 16-byte aligned, ordinary
+ *                  (coarse-grained, hipMalloc-style) device memory; overwritten.  Each row sums the
+ *                  contributions of the num_q_heads / num_kv_heads heads of its group and of every query row
+ *                  that attends to it; they are added up with the L2's float atomics, so the last bits may
+ *                  differ between runs.
+ * bf16 data with 16 query heads per KV head and head_dim 128 runs on the matrix cores and obtains scratch for
+ * transposed copies of Q, dO and K (about 2.1 times the size of Q) from the stream-ordered pool (see the general
+ * rules); every other head shape and dtype runs fp32 arithmetic on the vector units with a
+ * [num_q_heads, total_tokens] float32 scratch.
  */
 int infllmv2_sparse_attn_bwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
                              int64_t kv_tok_stride, int64_t kv_head_stride, const int32_t *block_idx_d,
