@@ -215,10 +215,9 @@ int infllmv2_sparse_attn_fwd(const infllmv2_params *p, const void *q_d, const vo
  *                  contributions of the num_q_heads / num_kv_heads heads of its group and of every query row
  *                  that attends to it; they are added up with the L2's float atomics, so the last bits may
  *                  differ between runs.
- * bf16 data with 16 query heads per KV head and head_dim 128 runs on the matrix cores and obtains scratch for
- * transposed copies of Q, dO and K (about 2.1 times the size of Q) from the stream-ordered pool (see the general
- * rules); every other head shape and dtype runs fp32 arithmetic on the vector units with a
- * [num_q_heads, total_tokens] float32 scratch.
+ * bf16 data with 16 query heads per KV head and head_dim 128 runs on the matrix cores and obtains scratch for a
+ * transposed copy of K and two [num_q_heads, total_tokens] float32 arrays from the stream-ordered pool (see the
+ * general rules); every other head shape and dtype runs fp32 arithmetic on the vector units with one such array.
  */
 int infllmv2_sparse_attn_bwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
                              int64_t kv_tok_stride, int64_t kv_head_stride, const int32_t *block_idx_d,

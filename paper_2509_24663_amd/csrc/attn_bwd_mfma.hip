@@ -3,10 +3,8 @@
 // log-sum-exp; the paper prints no backward algorithm):
 //     P = exp(z - lse),  dP = dO V^T,  dZ = P o (dP - Delta),  dQ = scale dZ K,  dK = scale dZ^T Q,  dV = P^T dO.
 // Every product is an MFMA with the 16 heads of a token as one matrix dimension.  Operands go from global
-// memory (L2) into MFMA registers (dq) or through a small LDS stage (dkv), which needs three transposed copies
-// made by two pre-passes into stream-ordered scratch:
-//   prep : per (token, KV head) Q^T and dO^T as [128 dims][16 heads]; Delta = <dO, O> and lse * log2(e) per
-//          (token, query head), token-major
+// memory through LDS stages into MFMA registers.  Two small pre-passes write into stream-ordered scratch:
+//   prep : Delta = <dO, O> and lse * log2(e) per (token, query head), token-major
 //   kt   : per 64-key block K^T as [128 dims][64 keys]
 //   dq   : one wavefront per (token, KV head), a workgroup of consecutive tokens walking the union of their
 //          block lists with each block's K, V, K^T staged once in LDS.  Per 16 keys:
@@ -15,14 +13,14 @@
 //   dkv  : one workgroup of 4 wavefronts per (64-key block, chunk of later tokens, KV head); wavefront w owns keys
 //          16 w .. 16 w + 15 with their K and V fragments in registers.  The workgroup lists the tokens of its
 //          chunk that selected the block; per token S = Q K^T and dP = dO V^T (heads x keys), then
-//          dV += P^T dO and dK += dZ^T Q (8 + 8 MFMA 16x16x16: keys x dims, contraction over the 16 heads).
-//          Per token the four wavefronts share Q, dO, Q^T, dO^T through a double-buffered 16 KB LDS stage (next
-//          token in flight in registers, one barrier per token).  Results are added to the float32 outputs with
+//          dV += P^T dO and dK += dZ^T Q (8 + 8 MFMA 16x16x16: keys x dims, contraction over the 16 heads; the
+//          B operands, heads x dims, are read from the same row-major tiles with the transposing LDS read).
+//          The four wavefronts share each token's Q and dO rows (8 KB) through a double-buffered LDS stage,
+//          two tokens per barrier, the next two in flight in registers.  Results are added to the float32 outputs with
 //          the L2's float atomics, one add per element and workgroup.
-// Measured at 131072 tokens, 64 selected blocks: dq 128 ms, dkv 156 ms (the forward attention kernel: 12.6 ms).
-// Both are bound by operand traffic, not by the matrix cores: dq re-reads 48 KB of K, V, K^T per (token, block)
-// from L2 with no sharing between neighbouring tokens (the forward kernel shares them through LDS), dkv reads
-// 16 KB of per-token operands per (token, block) from HBM with one token in flight per workgroup.
+// Measured at 131072 tokens, 64 selected blocks: dq 37 ms, dkv 71 ms (the forward attention kernel: 12.6 ms; 3.5x
+// its flops).  dkv is bound by the 8 KB of Q and dO rows it fetches per (token, block) -- tokens that selected a
+// given block are scattered, so nothing is shared between blocks -- and dq by LDS traffic and barriers.
 #include <algorithm>
 
 #include "common.h"
@@ -57,7 +55,6 @@ struct BwdM {
     float scale;
     RowMap map;
     // scratch
-    uint16_t *qt, *dot;          // [T][hkv][128][16]
     float *lse2, *delta;         // [T][hq]
     uint16_t *kt;                // [hkv][blocks][128][64]
     int64_t nblocks;             // 64-key blocks over all sequences
@@ -75,21 +72,16 @@ __device__ inline int block_base(const RowMap &m, int seq) {
 
 // ------------------------------------------------------------------------------------------ pre-passes
 __global__ void __launch_bounds__(256) bwd_prep_kernel(BwdM a) {
-    __shared__ __attribute__((aligned(16))) uint16_t tq[D][G], tg[D][G];
+    // 16 threads per (token, query head): Delta = <dO, O>, and lse in the log2 domain, both token-major
     const int row = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
     const int head = tid >> 4, d0 = (tid & 15) * 8;
     const int64_t off = ((int64_t)row * a.hq + h * G + head) * D + d0;
-    const uint4 rq = *reinterpret_cast<const uint4 *>(a.q + off);
     const uint4 rg = *reinterpret_cast<const uint4 *>(a.dout + off);
     const uint4 ro = *reinterpret_cast<const uint4 *>(a.out + off);
-    const uint32_t wq[4] = {rq.x, rq.y, rq.z, rq.w}, wg[4] = {rg.x, rg.y, rg.z, rg.w}, wo[4] = {ro.x, ro.y, ro.z, ro.w};
+    const uint32_t wg[4] = {rg.x, rg.y, rg.z, rg.w}, wo[4] = {ro.x, ro.y, ro.z, ro.w};
     float dot = 0.f;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        tq[d0 + 2 * e][head] = (uint16_t)(wq[e] & 0xffffu);
-        tq[d0 + 2 * e + 1][head] = (uint16_t)(wq[e] >> 16);
-        tg[d0 + 2 * e][head] = (uint16_t)(wg[e] & 0xffffu);
-        tg[d0 + 2 * e + 1][head] = (uint16_t)(wg[e] >> 16);
         dot += __uint_as_float(wg[e] << 16) * __uint_as_float(wo[e] << 16);
         dot += __uint_as_float(wg[e] & 0xffff0000u) * __uint_as_float(wo[e] & 0xffff0000u);
     }
@@ -100,10 +92,6 @@ __global__ void __launch_bounds__(256) bwd_prep_kernel(BwdM a) {
         a.delta[(int64_t)row * a.hq + qh] = dot;
         a.lse2[(int64_t)row * a.hq + qh] = a.lse[qhead_row(a.map, qh, a.hq, row)] * LOG2E;
     }
-    __syncthreads();
-    const int64_t tile = ((int64_t)row * a.map.num_kv_heads + h) * (D * G);
-    reinterpret_cast<uint4 *>(a.qt + tile)[tid] = reinterpret_cast<const uint4 *>(&tq[0][0])[tid];
-    reinterpret_cast<uint4 *>(a.dot + tile)[tid] = reinterpret_cast<const uint4 *>(&tg[0][0])[tid];
 }
 
 __global__ void __launch_bounds__(256) bwd_kt_kernel(BwdM a) {
@@ -322,11 +310,14 @@ __device__ inline bool list_has(const int32_t *e, int n, int j) {
     return lo < n && e[lo] == j;
 }
 
+constexpr int DKV_QS = D + 8;                                   // padded row of the row-major Q / dO tiles
+constexpr int DKV_TOK_ELEMS = 2 * G * DKV_QS;                   // Q and dO rows of one token
+constexpr int DKV_TB = 2;                                       // tokens per barrier (and per prefetch)
+
 __global__ void __launch_bounds__(256) bwd_dkv_mfma_kernel(BwdM a) {
-    constexpr int QS = D + 8;                               // padded row of the row-major Q / dO tiles
-    constexpr int TOK_ELEMS = 2 * G * QS + 2 * D * G;       // Q, dO, Q^T, dO^T of one token
-    __shared__ __attribute__((aligned(16))) uint16_t tok_s[2 * TOK_ELEMS];
-    __shared__ __attribute__((aligned(16))) float f_s[2][32];      // lse * log2(e) and Delta of the 16 heads
+    constexpr int QS = DKV_QS, TOK_ELEMS = DKV_TOK_ELEMS, TB = DKV_TB;
+    __shared__ __attribute__((aligned(16))) uint16_t tok_s[2 * TB * TOK_ELEMS];     // [2 buffers][TB tokens]
+    __shared__ __attribute__((aligned(16))) float f_s[2][TB][32];  // lse * log2(e) and Delta of the 16 heads
     __shared__ int s_seq, s_j, s_list[DKV_CHUNK], s_wave_cnt[4];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int h = blockIdx.z;
@@ -391,64 +382,77 @@ __global__ void __launch_bounds__(256) bwd_dkv_mfma_kernel(BwdM a) {
     // The four wavefronts need the same per-token data, so it goes through LDS once: Q and dO rows (row-major,
     // padded: A operands), Q^T and dO^T ([dims][heads]: B operands), Delta and lse.  Double buffered, the next
     // token's 16 KB are in flight in registers while the current token is computed; one barrier per token.
-    struct TokPre { uint4 q, g, qt, gt; float f; };
+    struct TokPre { uint4 q, g; float f; };
     auto gload = [&](int t) -> TokPre {
         TokPre pr;
         const int row = tok0 + t;
         const int64_t off = ((int64_t)row * a.hq + h * G + (tid >> 4)) * D + (tid & 15) * 8;
-        const int64_t tile = ((int64_t)row * a.map.num_kv_heads + h) * (D * G);
         pr.q = *reinterpret_cast<const uint4 *>(a.q + off);
         pr.g = *reinterpret_cast<const uint4 *>(a.dout + off);
-        pr.qt = reinterpret_cast<const uint4 *>(a.qt + tile)[tid];
-        pr.gt = reinterpret_cast<const uint4 *>(a.dot + tile)[tid];
         pr.f = (tid < 16 ? a.lse2 : a.delta)[(int64_t)row * a.hq + h * G + (tid & 15)];    // used by threads 0..31
         return pr;
     };
-    auto lstore = [&](int buf, const TokPre &pr) {
-        uint16_t *b = tok_s + buf * TOK_ELEMS;
+    auto lstore = [&](int buf, int slot, const TokPre &pr) {
+        uint16_t *b = tok_s + (buf * TB + slot) * TOK_ELEMS;
         *reinterpret_cast<uint4 *>(b + (tid >> 4) * QS + (tid & 15) * 8) = pr.q;
         *reinterpret_cast<uint4 *>(b + G * QS + (tid >> 4) * QS + (tid & 15) * 8) = pr.g;
-        reinterpret_cast<uint4 *>(b + 2 * G * QS)[tid] = pr.qt;
-        reinterpret_cast<uint4 *>(b + 2 * G * QS + D * G)[tid] = pr.gt;
-        if (tid < 32) f_s[buf][tid] = pr.f;
+        if (tid < 32) f_s[buf][slot][tid] = pr.f;
     };
-    lstore(0, gload(s_list[0]));
+    // B operands of the two head-contractions come from the same row-major tiles through the transposing LDS
+    // read: in each group of 16 lanes, lane L points at dims 4 (L % 4) .. + 3 of row L / 4 of a 4 x 16 block and
+    // receives column L of it.  Block = heads 4 g .. 4 g + 3, dims 16 dt .. 16 dt + 15.
+    typedef __attribute__((address_space(3))) short4v lds_s4;
+    const int tr_off = (4 * g + (n16 >> 2)) * QS + 4 * (n16 & 3);
+    // batches of TB tokens: batch i = list entries TB i .. TB i + TB - 1 (entries past the end repeat the last one
+    // and are not computed)
+    const int nbatch = (total + TB - 1) / TB;
+    TokPre nxt[TB];
+#pragma unroll
+    for (int sl = 0; sl < TB; ++sl) lstore(0, sl, gload(s_list[min(sl, total - 1)]));
     __syncthreads();
-    for (int it = 0; it < total; ++it) {
-        const int t = s_list[it];
-        const TokPre nxt = gload(s_list[min(it + 1, total - 1)]);      // (the last one is loaded again, unused)
-        const uint16_t *b = tok_s + (it & 1) * TOK_ELEMS;
-        // A operands: Q and dO rows of head n16
-        f32x4 sacc = f32x4{0.f, 0.f, 0.f, 0.f}, dpacc = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int ib = 0; ib < nbatch; ++ib) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const bf16x8 qa = *reinterpret_cast<const bf16x8 *>(b + n16 * QS + g * 8 + ks * 32);
-            const bf16x8 ga = *reinterpret_cast<const bf16x8 *>(b + G * QS + n16 * QS + g * 8 + ks * 32);
-            sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa, kf[ks], sacc, 0, 0, 0);
-            dpacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ga, vf[ks], dpacc, 0, 0, 0);
-        }
-        // element r: head 4 g + r, key n16 of this wave's tile
-        const float4 l2 = *reinterpret_cast<const float4 *>(&f_s[it & 1][4 * g]);
-        const float4 dl = *reinterpret_cast<const float4 *>(&f_s[it & 1][16 + 4 * g]);
-        const float l2a[4] = {l2.x, l2.y, l2.z, l2.w}, dla[4] = {dl.x, dl.y, dl.z, dl.w};
-        const bool visible = key <= t;
-        float p[4], dz[4];
+        for (int sl = 0; sl < TB; ++sl) nxt[sl] = gload(s_list[min((ib + 1) * TB + sl, total - 1)]);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            p[r] = visible ? exp2_fast(__builtin_fmaf(sacc[r], c, -l2a[r])) : 0.f;
-            dz[r] = p[r] * (dpacc[r] - dla[r]);
-        }
-        const short4v pb = to_bf16x4(p[0], p[1], p[2], p[3]), dzb = to_bf16x4(dz[0], dz[1], dz[2], dz[3]);
-        // dV (keys x dims) += P^T (keys x heads) dO (heads x dims); B: dO^T row 16 dt + n16, heads 4 g .. 4 g + 3
-        const uint16_t *qt = b + 2 * G * QS + n16 * G + 4 * g, *gt = qt + D * G;
+        for (int sl = 0; sl < TB; ++sl) {
+            const int it = ib * TB + sl;
+            if (it >= total) break;                                  // uniform
+            const int t = s_list[it];
+            const uint16_t *b = tok_s + ((ib & 1) * TB + sl) * TOK_ELEMS;
+            // A operands: Q and dO rows of head n16
+            f32x4 sacc = f32x4{0.f, 0.f, 0.f, 0.f}, dpacc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-            const short4v gb = *reinterpret_cast<const short4v *>(gt + dt * 16 * G);
-            const short4v qb = *reinterpret_cast<const short4v *>(qt + dt * 16 * G);
-            acc_v[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, gb, acc_v[dt], 0, 0, 0);
-            acc_k[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(dzb, qb, acc_k[dt], 0, 0, 0);
+            for (int ks = 0; ks < 4; ++ks) {
+                const bf16x8 qa = *reinterpret_cast<const bf16x8 *>(b + n16 * QS + g * 8 + ks * 32);
+                const bf16x8 ga = *reinterpret_cast<const bf16x8 *>(b + G * QS + n16 * QS + g * 8 + ks * 32);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa, kf[ks], sacc, 0, 0, 0);
+                dpacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ga, vf[ks], dpacc, 0, 0, 0);
+            }
+            // element r: head 4 g + r, key n16 of this wave's tile
+            const float4 l2 = *reinterpret_cast<const float4 *>(&f_s[ib & 1][sl][4 * g]);
+            const float4 dl = *reinterpret_cast<const float4 *>(&f_s[ib & 1][sl][16 + 4 * g]);
+            const float l2a[4] = {l2.x, l2.y, l2.z, l2.w}, dla[4] = {dl.x, dl.y, dl.z, dl.w};
+            const bool visible = key <= t;
+            float p[4], dz[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                p[r] = visible ? exp2_fast(__builtin_fmaf(sacc[r], c, -l2a[r])) : 0.f;
+                dz[r] = p[r] * (dpacc[r] - dla[r]);
+            }
+            const short4v pb = to_bf16x4(p[0], p[1], p[2], p[3]), dzb = to_bf16x4(dz[0], dz[1], dz[2], dz[3]);
+            // dV (keys x dims) += P^T (keys x heads) dO (heads x dims); B: dim 16 dt + n16, heads 4 g .. 4 g + 3
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                const short4v qb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)(b + tr_off + 16 * dt));
+                const short4v gb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)(b + G * QS + tr_off + 16 * dt));
+                acc_v[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, gb, acc_v[dt], 0, 0, 0);
+                acc_k[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(dzb, qb, acc_k[dt], 0, 0, 0);
+            }
         }
-        if (it + 1 < total) lstore((it + 1) & 1, nxt);
+        if (ib + 1 < nbatch) {
+#pragma unroll
+            for (int sl = 0; sl < TB; ++sl) lstore((ib + 1) & 1, sl, nxt[sl]);
+        }
         __syncthreads();
     }
 #pragma unroll
@@ -487,12 +491,11 @@ int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const vo
     const int hkv = p->num_kv_heads, hq = p->num_q_heads;
     if (nblocks > 65535 || hkv > 65535 || rows > 0x7fffffff / 4) return INFLLMV2_ERR_UNSUPPORTED;
     if ((L.max_len + kBlock - 1) / kBlock > DQ_MAX_BLOCKS) return INFLLMV2_ERR_UNSUPPORTED;
-    const size_t b_t = align256((size_t)rows * hkv * D * G * sizeof(uint16_t));
     const size_t b_f = align256((size_t)rows * hq * sizeof(float));
     const size_t b_kt = align256((size_t)hkv * nblocks * D * kBlock * sizeof(uint16_t));
     keep_freed_memory_in_pool();
     char *ws = nullptr;
-    if (hipMallocAsync((void **)&ws, 2 * b_t + 2 * b_f + b_kt, L.stream) != hipSuccess) return INFLLMV2_ERR_HIP;
+    if (hipMallocAsync((void **)&ws, 2 * b_f + b_kt, L.stream) != hipSuccess) return INFLLMV2_ERR_HIP;
     BwdM a;
     a.q = (const uint16_t *)q;
     a.k = (const uint16_t *)k;
@@ -506,11 +509,9 @@ int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const vo
     a.hq = hq;
     a.scale = p->softmax_scale;
     a.map = L.map;
-    a.qt = (uint16_t *)ws;
-    a.dot = (uint16_t *)(ws + b_t);
-    a.lse2 = (float *)(ws + 2 * b_t);
-    a.delta = (float *)(ws + 2 * b_t + b_f);
-    a.kt = (uint16_t *)(ws + 2 * b_t + 2 * b_f);
+    a.lse2 = (float *)ws;
+    a.delta = (float *)(ws + b_f);
+    a.kt = (uint16_t *)(ws + 2 * b_f);
     a.nblocks = nblocks;
     a.dq = (uint16_t *)dq;
     a.dk = dk;
