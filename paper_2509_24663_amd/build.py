@@ -20,6 +20,13 @@ FLAGS = [
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 
+# Per-file additions.  The backward kernels keep 64 accumulator registers plus short-lived ones; with the default
+# split of the register file the compiler parks accumulators in AGPRs and then shuffles them through VGPRs around
+# every temporary MFMA (a hundred v_accvgpr moves per token).  Keeping MFMA results in VGPRs avoids that.
+EXTRA_FLAGS = {
+    "attn_bwd_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+}
+
 
 def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
@@ -31,7 +38,7 @@ def _compile(src: str, force: bool) -> str:
         os.path.join(CSRC, h) for h in os.listdir(CSRC) if h.endswith(".h")]
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     # the host pass warns that it does not know the packed-fp32 target feature: harmless
     out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)

@@ -38,13 +38,11 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef short short4v __attribute__((ext_vector_type(4)));
 
 __device__ inline float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+// four floats -> four bf16 (round to nearest even, the hardware conversion)
 __device__ inline short4v to_bf16x4(float a, float b, float c, float d) {
-    short4v r;
-    r[0] = (short)float_to_bf16(a);
-    r[1] = (short)float_to_bf16(b);
-    r[2] = (short)float_to_bf16(c);
-    r[3] = (short)float_to_bf16(d);
-    return r;
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+    const bf16x4 r = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+    return __builtin_bit_cast(short4v, r);
 }
 
 struct BwdM {
