@@ -18,7 +18,7 @@
 //          The four wavefronts share each token's Q and dO rows (8 KB) through a double-buffered LDS stage,
 //          two tokens per barrier, the next two in flight in registers.  Results are added to the float32 outputs with
 //          the L2's float atomics, one add per element and workgroup.
-// Measured at 131072 tokens, 64 selected blocks: dq 37 ms, dkv 71 ms (the forward attention kernel: 12.6 ms; 3.5x
+// Measured at 131072 tokens, 64 selected blocks: dq 31 ms, dkv 45 ms (the forward attention kernel: 12.6 ms; 3.5x
 // its flops).  dkv is bound by the 8 KB of Q and dO rows it fetches per (token, block) -- tokens that selected a
 // given block are scattered, so nothing is shared between blocks -- and dq by LDS traffic and barriers.
 #include <algorithm>
