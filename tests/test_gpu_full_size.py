@@ -93,3 +93,44 @@ def test_decode_context_of_400k_tokens(m, oracle):
     gp = m.Params.make("bf16", 32, 2, 128, n_init=1, n_local=8, topk_total=64)
     op = oracle.Params(n_init=1, n_local=8, topk_total=64, softmax_scale=float(gp.softmax_scale))
     assert _check_decode(m, oracle, w, ctx, gp, op, "bf16") == 4
+
+
+def test_c2_32k_backward_sampled(m, oracle):
+    """Gradients of stage 4 at config 2's full size.  dQ of a row depends on that row alone, so it is checked on a
+    sample of rows; dK / dV of a key block sum over every row that selected the block, so one block is checked
+    with the oracle run on exactly those rows (taken from the GPU's selection)."""
+    cfg = synth.CONFIGS["C2"]
+    w = synth.make_config(cfg)
+    gp, op = m.Params.from_config(cfg), oracle.Params.from_config(cfg)
+    n, G, hkv = cfg.seq_len, cfg.group, cfg.num_kv_heads
+    q, k, v = (to_dev(w[x], "bf16") for x in ("q", "k", "v"))
+    rng = np.random.default_rng(77)
+    dout_np = synth.round_to_bf16(rng.standard_normal(w["q"].shape).astype(np.float32))
+    dout = to_dev(dout_np, "bf16")
+    res = m.sparse_prefill(gp, q, k, v, [0, n], fused_pool=True)
+    dq, dk, dv = m.sparse_attn_bwd(gp, q, k, v, res["block_idx"], res["out"], res["lse"], dout, [0, n])
+    torch.cuda.synchronize()
+    idx_g = to_np(res["block_idx"])
+    print("C2 backward: GPU done, oracle on sampled rows and one key block ...", flush=True)
+
+    def rel(got, ref):
+        scale = max(float(np.abs(ref).max()), 0.1)
+        err = np.abs(got.astype(np.float64) - ref) / scale
+        return float(err.max()), float(err.mean())
+
+    rows = np.unique(np.concatenate([[0, 63, 64, n - 1], rng.integers(0, n, 28)])).astype(np.int32)
+    dq_g = to_np(dq[torch.from_numpy(rows.astype(np.int64)).cuda()])
+    h = 1
+    dQ, _, _ = oracle.attn_bwd(w["q"][rows, h * G:(h + 1) * G], rows, w["k"][h], w["v"][h], idx_g[h, rows],
+                               dout_np[rows, h * G:(h + 1) * G], op)
+    mx, mean = rel(dq_g[:, h * G:(h + 1) * G], dQ)
+    assert mx <= 2e-2 and mean <= 2e-3, ("dq", mx, mean)
+    dk_g, dv_g = to_np(dk[h]), to_np(dv[h])
+    for j in (401,):                                       # a block outside the forced ranges of most rows
+        users = np.nonzero((idx_g[h] == j).any(-1))[0].astype(np.int32)
+        assert 64 < len(users) < 6000
+        _, dK, dV = oracle.attn_bwd(w["q"][users, h * G:(h + 1) * G], users, w["k"][h], w["v"][h], idx_g[h, users],
+                                    dout_np[users, h * G:(h + 1) * G], op)
+        for name, got, ref in (("dk", dk_g, dK), ("dv", dv_g, dV)):
+            mx, mean = rel(got[j * 64:(j + 1) * 64], ref[j * 64:(j + 1) * 64])
+            assert mx <= 2e-2 and mean <= 2e-3, (name, j, len(users), mx, mean)
