@@ -189,6 +189,19 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
         for (int j = tid; j < a.tk.topk_total; j += SEL_THREADS) out[j] = j < nblk ? j : -1;
         return;
     }
+    // The logits this thread will normalise (up to ZPT keys x 16 heads) are requested first, so that their trip to
+    // memory overlaps the merge of the normaliser below.
+    constexpr int ZPT = 4;                               // covers 4096 compressed keys = 65K tokens of context
+    float zr[ZPT][G];
+    {
+        const float *zb0 = a.z + (int64_t)pair * G * a.zs;
+#pragma unroll
+        for (int u = 0; u < ZPT; ++u) {
+            const int i = min(tid + u * SEL_THREADS, max(v - 1, 0));
+#pragma unroll
+            for (int gq = 0; gq < G; ++gq) zr[u][gq] = zb0[(int64_t)gq * a.zs + i];
+        }
+    }
     // ---- log2 of sum_i 2^z per head: 64 thread groups per head over the chunk partials, then 64 -> 1
     {
         const int head = tid & 15, pg = tid >> 4;
@@ -215,7 +228,17 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
         __syncthreads();
     }
     // ---- S^shared[i] = sum over the 16 heads of 2^(z[g][i] - lse2[g]), kept in LDS
-    for (int i = tid; i < v; i += SEL_THREADS) {
+#pragma unroll
+    for (int u = 0; u < ZPT; ++u) {
+        const int i = tid + u * SEL_THREADS;
+        if (i < v) {
+            float sum = 0.f;
+#pragma unroll
+            for (int gq = 0; gq < G; ++gq) sum += fast_exp2(zr[u][gq] - lse2[gq]);
+            sh[i] = sum;
+        }
+    }
+    for (int i = tid + ZPT * SEL_THREADS; i < v; i += SEL_THREADS) {      // longer contexts: the rest, unprefetched
         const float *zb = a.z + (int64_t)pair * G * a.zs + i;
         float sum = 0.f;
 #pragma unroll
@@ -395,44 +418,47 @@ __global__ void __launch_bounds__(AW * 64) dec_attn_kernel(DecArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------ merge
+// Thread (head, group of 8 dims) combines the splits' partial results by itself, eight splits at a time with all of
+// their loads issued before the first use: no LDS, no barrier, one round trip to memory for the usual 8 splits.
 __global__ void __launch_bounds__(256) dec_merge_kernel(DecArgs a) {
-    extern __shared__ float wgt[];                     // [nsplit][16] weights of the splits
-    __shared__ float mtot[16], ltot[16];
     const int pair = blockIdx.x;
     const int b = pair / a.hkv, h = pair - b * a.hkv;
     const int tid = threadIdx.x;
-    const float c = a.scale * LOG2E;
-    const float *ml = a.mlpart + (int64_t)pair * a.nsplit * 32;
-    if (tid < 16) {
-        float mm = -INFINITY;
-        for (int s = 0; s < a.nsplit; ++s) mm = fmaxf(mm, ml[s * 32 + tid * 2]);
-        mtot[tid] = mm;
-    }
-    __syncthreads();
-    for (int i = tid; i < a.nsplit * 16; i += 256) {
-        const int s = i >> 4, head = i & 15;
-        const float ms = ml[s * 32 + head * 2];
-        wgt[i] = ms == -INFINITY ? 0.f : fast_exp2((ms - mtot[head]) * c);
-    }
-    __syncthreads();
-    if (tid < 16) {
-        float ll = 0.f;
-        for (int s = 0; s < a.nsplit; ++s) ll += ml[s * 32 + tid * 2 + 1] * wgt[s * 16 + tid];
-        ltot[tid] = ll;
-    }
-    __syncthreads();
     const int head = tid & 15, dg = tid >> 4;          // 16 heads x 16 groups of 8 dims
-    float o[8];
+    const float c = a.scale * LOG2E;
+    const float *ml = a.mlpart + (int64_t)pair * a.nsplit * 32 + head * 2;
+    const float *opb = a.opart + (int64_t)pair * a.nsplit * OPART + (dg * 8) * G + head;
+    float mm = -INFINITY, ll = 0.f, o[8];
 #pragma unroll
     for (int e2 = 0; e2 < 8; ++e2) o[e2] = 0.f;
-    const float *opb = a.opart + (int64_t)pair * a.nsplit * OPART + (dg * 8) * G + head;
-#pragma unroll 4
-    for (int s = 0; s < a.nsplit; ++s) {
-        const float wg = wgt[s * 16 + head];
+    for (int s0 = 0; s0 < a.nsplit; s0 += 8) {
+        float ms[8], ls[8], ov[8][8];
 #pragma unroll
-        for (int e2 = 0; e2 < 8; ++e2) o[e2] += opb[(int64_t)s * OPART + e2 * G] * wg;
+        for (int u = 0; u < 8; ++u) {
+            const int s = min(s0 + u, a.nsplit - 1);        // past the end: re-read the last split, weight 0 below
+            ms[u] = ml[s * 32];
+            ls[u] = ml[s * 32 + 1];
+#pragma unroll
+            for (int e2 = 0; e2 < 8; ++e2) ov[u][e2] = opb[(int64_t)s * OPART + e2 * G];
+        }
+        float cm = mm;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s0 + u < a.nsplit) cm = fmaxf(cm, ms[u]);
+        if (cm == -INFINITY) continue;                      // nothing attended to in these splits
+        const float resc = mm == -INFINITY ? 0.f : fast_exp2((mm - cm) * c);
+        ll *= resc;
+#pragma unroll
+        for (int e2 = 0; e2 < 8; ++e2) o[e2] *= resc;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float wg = s0 + u < a.nsplit && ms[u] != -INFINITY ? fast_exp2((ms[u] - cm) * c) : 0.f;
+            ll += ls[u] * wg;
+#pragma unroll
+            for (int e2 = 0; e2 < 8; ++e2) o[e2] += ov[u][e2] * wg;
+        }
+        mm = cm;
     }
-    const float ll = ltot[head];
     const float inv = ll > 0.f ? 1.f / ll : 0.f;
     uint4 pk;
     pk.x = (uint32_t)float_to_bf16(o[0] * inv) | ((uint32_t)float_to_bf16(o[1] * inv) << 16);
@@ -440,7 +466,7 @@ __global__ void __launch_bounds__(256) dec_merge_kernel(DecArgs a) {
     pk.z = (uint32_t)float_to_bf16(o[4] * inv) | ((uint32_t)float_to_bf16(o[5] * inv) << 16);
     pk.w = (uint32_t)float_to_bf16(o[6] * inv) | ((uint32_t)float_to_bf16(o[7] * inv) << 16);
     *reinterpret_cast<uint4 *>(a.out + ((int64_t)b * a.hq + h * G + head) * D + dg * 8) = pk;
-    if (a.lse != nullptr && dg == 0) a.lse[(int64_t)b * a.hq + h * G + head] = mtot[head] * a.scale + __logf(ll);
+    if (a.lse != nullptr && dg == 0) a.lse[(int64_t)b * a.hq + h * G + head] = mm * a.scale + __logf(ll);
 }
 
 inline size_t align_up(size_t x, size_t al) { return (x + al - 1) / al * al; }
@@ -552,7 +578,7 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     hipLaunchKernelGGL(dec_scores_kernel, dim3(d.nchunk, pairs), dim3(256), 0, stream, a);
     hipLaunchKernelGGL(dec_select_kernel, dim3(pairs), dim3(SEL_THREADS), sel_lds, stream, a, sh_cap);
     hipLaunchKernelGGL(dec_attn_kernel, dim3(d.nsplit, pairs), dim3(AW * 64), attn_lds, stream, a);
-    hipLaunchKernelGGL(dec_merge_kernel, dim3(pairs), dim3(256), (size_t)d.nsplit * 16 * sizeof(float), stream, a);
+    hipLaunchKernelGGL(dec_merge_kernel, dim3(pairs), dim3(256), 0, stream, a);
     return hip_status(hipGetLastError());
 }
 
