@@ -314,7 +314,7 @@ int infllmv2_sparse_decode(const infllmv2_params *p, const void *q_d, const void
                            (uintptr_t)out_d) & 15) == 0 &&
                          kv_tok_stride % 8 == 0 && kv_head_stride % 8 == 0 && kv_batch_stride % 8 == 0 &&
                          kc_head_stride % 4 == 0;
-    if (decode_mfma_supported(p) && aligned && p->lse_mode == 0) {   // the split decode kernels are exact-lse only
+    if (decode_mfma_supported(p) && aligned) {
         const int rc = launch_decode_mfma(p, q_d, k_cache_d, v_cache_d, kv_batch_stride, kv_head_stride, kv_tok_stride,
                                           kc_cache_d, kc_head_stride, ctx_lens_h, ctx_lens_d, batch, block_idx_out_d,
                                           out_d, lse_d, workspace_d, (hipStream_t)stream);

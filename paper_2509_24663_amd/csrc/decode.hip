@@ -8,7 +8,8 @@
 // the fences act on whole caches.
 //   scores  : grid (key chunks, pairs)  logits of 128 compressed keys x 16 heads per workgroup, written once
 //             as log2-domain logits, plus per-chunk (max, sum) partials of the softmax normaliser
-//   select  : grid (pairs)              one 1024-thread workgroup per pair merges the partials into the normaliser,
+//   select  : grid (pairs)              one 1024-thread workgroup per pair merges the partials into the normaliser
+//             (with the LSE Approximation: forms it from means of four logits, the coarse keys' logits),
 //             sums the normalised scores of the 16 heads (Eq. 5) into LDS, max-pools them to blocks (Eq. 6) and
 //             selects (Eq. 2) with a workgroup-wide radix select: a single wavefront per row, as in prefill, would
 //             leave the chip empty and spend ~16 us on latency here.  The score row of a pair must fit in LDS
@@ -47,6 +48,7 @@ struct DecArgs {
     uint16_t *out;     // [batch][hq][d]
     float *lse;        // [batch][hq] or nullptr
     int zs, nchunk, nsplit;
+    int lse_mode;      // 1: normalise with the log-sum-exp over the four times coarser keys (LSE Approximation, Sec. 3.4)
 };
 
 // ------------------------------------------------------------------------------------------ scores
@@ -203,7 +205,7 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
         }
     }
     // ---- log2 of sum_i 2^z per head: 64 thread groups per head over the chunk partials, then 64 -> 1
-    {
+    if (a.lse_mode == 0) {
         const int head = tid & 15, pg = tid >> 4;
         const float *pp = a.part + (int64_t)pair * a.nchunk * 32 + head * 2;
         float mm = -INFINITY, ll = 0.f;
@@ -216,6 +218,25 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
         }
         red[pg][head][0] = mm;
         red[pg][head][1] = ll;
+    } else {
+        // LSE Approximation (Eq. 7): the normaliser runs over the coarse keys.  K^{C2}_i is the mean of the four
+        // disjoint K^{C1} windows 4i + m l/s, m = 0..3, and the logit is linear in the key, so the coarse logit is
+        // the mean of four logits already in z -- no second product.  Thread groups as above, over coarse keys.
+        const int head = tid & 15, pg = tid >> 4;
+        const int cstep = a.tk.lc / a.tk.sc;
+        const int v2 = min(visible_cmp(t, 4 * a.tk.lc, 4 * a.tk.sc), num_cmp(L, 4 * a.tk.lc, 4 * a.tk.sc));
+        const float *zh = a.z + ((int64_t)pair * G + head) * a.zs;
+        float mm = -INFINITY, ll = 0.f;
+        for (int i2 = pg; i2 < v2; i2 += 64) {
+            const float zc = 0.25f * ((zh[4 * i2] + zh[4 * i2 + cstep]) + (zh[4 * i2 + 2 * cstep] + zh[4 * i2 + 3 * cstep]));
+            const float mn = fmaxf(mm, zc);
+            ll = ll * fast_exp2(mm - mn) + fast_exp2(zc - mn);
+            mm = mn;
+        }
+        red[pg][head][0] = mm;
+        red[pg][head][1] = ll;
+    }
+    {
         __syncthreads();
         if (tid < 16) {
             float m2 = -INFINITY;
@@ -223,7 +244,8 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
             float l2 = 0.f;
             for (int k = 0; k < 64; ++k)
                 if (red[k][tid][0] != -INFINITY) l2 += red[k][tid][1] * fast_exp2(red[k][tid][0] - m2);
-            lse2[tid] = m2 + __log2f(l2);
+            // no coarse key visible yet (LSE Approximation only): every score is zero
+            lse2[tid] = l2 > 0.f ? m2 + __log2f(l2) : INFINITY;
         }
         __syncthreads();
     }
@@ -551,6 +573,7 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     a.zs = d.zs;
     a.nchunk = d.nchunk;
     a.nsplit = d.nsplit;
+    a.lse_mode = p->lse_mode;
 
     // group sum + max-pool + top-k run as one workgroup per pair with the score row in LDS
     const int sh_cap = (d.zs + 3) / 4 * 4;

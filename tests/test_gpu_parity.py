@@ -173,7 +173,7 @@ def test_lse_approximation_varlen_and_decode(m, oracle):
     w = synth.make_varlen(lengths, 32, 2, 128, seed=5, dtype="bf16")
     gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=3, topk_total=9, lse_mode=1)
     _run_prefill_case(m, oracle, w, gp, op, "bf16")
-    ctx = [300, 1500, 127, 64]
+    ctx = [300, 1500, 127, 64, 6100]
     dw = synth.make_decode(ctx, 32, 2, 128, seed=6, dtype="bf16")
     _check_decode(m, oracle, dw, ctx, gp, op, "bf16")
 
