@@ -297,17 +297,23 @@ struct ScoreKernel {
     static constexpr int NTHR = NW * 64;
     static constexpr int NCH = 1024 / NTHR;        // 16-byte chunks of a 64 x 128 fp16 tile per thread
 
-    __device__ static inline void load_tile(const _Float16 *tiles, int kt, int tid, uint4 (&pf)[NCH]) {
+    // one thread's share of a tile in flight; passed and returned by value so that it stays in registers
+    struct TilePre {
+        uint4 c[NCH];
+    };
+    __device__ static inline TilePre load_tile(const _Float16 *tiles, int kt, int tid) {
         const uint4 *src = reinterpret_cast<const uint4 *>(tiles) + (int64_t)kt * 1024;
+        TilePre pf;
 #pragma unroll
-        for (int r = 0; r < NCH; ++r) pf[r] = src[tid + r * NTHR];
+        for (int r = 0; r < NCH; ++r) pf.c[r] = src[tid + r * NTHR];
+        return pf;
     }
     // registers -> LDS (padded rows), then a workgroup barrier: every thread calls it
-    __device__ static inline void stage_tile(_Float16 *tile, int tid, const uint4 (&pf)[NCH]) {
+    __device__ static inline void stage_tile(_Float16 *tile, int tid, const TilePre pf) {
 #pragma unroll
         for (int r = 0; r < NCH; ++r) {
             const int c = tid + r * NTHR;
-            *reinterpret_cast<uint4 *>(tile + (c >> 4) * SKS + (c & 15) * 8) = pf[r];
+            *reinterpret_cast<uint4 *>(tile + (c >> 4) * SKS + (c & 15) * 8) = pf.c[r];
         }
         __syncthreads();
     }
@@ -430,7 +436,6 @@ struct ScoreKernel {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) qf[i][ks][e] = (_Float16)(x[ks][e] * sc);
         }
-        uint4 pf[NCH];
         f32x4 acc[TPW][4];
         f32x4 nm[TPW];                   // per lane and head row: minus the reference (log2 domain)
         float l[TPW][4];                 // ... and the sum of 2^(y - reference)
@@ -516,12 +521,10 @@ struct ScoreKernel {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) l[i][r] = 0.f;
             }
-            if (nkt1 > 0) {
-                load_tile(kt_coarse, 0, tid, pf);
-                stage_tile(smem, tid, pf);
-            }
+            TilePre pf = {};
+            if (nkt1 > 0) stage_tile(smem, tid, load_tile(kt_coarse, 0, tid));
             for (int kt = 0; kt < nkt1; ++kt) {
-                if (kt + 1 < nkt1) load_tile(kt_coarse, kt + 1, tid, pf);
+                if (kt + 1 < nkt1) pf = load_tile(kt_coarse, kt + 1, tid);
                 if (late && kt > 0) vec1(kt - 1, tracked_c);
                 mma(kt, sh_coarse, nm);
                 if (!late) vec1(kt, tracked_c);
@@ -615,10 +618,10 @@ struct ScoreKernel {
             for (int i = 0; i < TPW; ++i)
                 if (lane == 0 && max(4 * jb - POOL, 0) < vis[i]) out_w[i * a.row_stride + jb] = carry[i];
         };
-        load_tile(kt_fine, 0, tid, pf);
+        TilePre pf = load_tile(kt_fine, 0, tid);
         stage_tile(smem, tid, pf);
         for (int kt = 0; kt < nkt; ++kt) {
-            if (kt + 1 < nkt) load_tile(kt_fine, kt + 1, tid, pf);
+            if (kt + 1 < nkt) pf = load_tile(kt_fine, kt + 1, tid);
             if (late && kt > 0) vec2(kt - 1);
             mma(kt, sh_fine, nlse);
             if (!late) vec2(kt);
