@@ -291,6 +291,16 @@ kc_half_kernel(const float *__restrict__ kc, RowMap map, int lc, int sc, int den
     if (tid == 0) (is_coarse ? sh_coarse : sh_fine)[(int64_t)h * (is_coarse ? tiles_coarse : tiles_fine) + tile] = shift;
 }
 
+// W = 32: lanes 0..31 get x[lane] + x[lane + 32], lanes 32..63 get y[lane - 32] + y[lane].
+// W = 16 (rows of 16 lanes): rows 0 and 2 get x's rows 0+1 and 2+3, rows 1 and 3 get y's rows 0+1 and 2+3.
+template <int W>
+__device__ inline float swap_add(float x, float y) {
+    const unsigned ux = __float_as_uint(x), uy = __float_as_uint(y);
+    const auto r = W == 32 ? __builtin_amdgcn_permlane32_swap(ux, uy, false, false)
+                           : __builtin_amdgcn_permlane16_swap(ux, uy, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 template <int NW, int TPW>
 struct ScoreKernel {
     static constexpr int T = NW * TPW;
@@ -584,10 +594,10 @@ struct ScoreKernel {
                 for (int nt = 0; nt < 4; ++nt)
                     s[nt] = (s_exp2(acc[i][nt][0]) + s_exp2(acc[i][nt][1])) + (s_exp2(acc[i][nt][2]) + s_exp2(acc[i][nt][3]));
                 // butterfly over the four lane groups: afterwards lane (n16, g) holds n-tile g, i.e. key kbase + lane
-                const bool hi = g & 2, odd = g & 1;
-                const float a0 = (hi ? s[2] : s[0]) + __shfl_xor(hi ? s[0] : s[2], 32);
-                const float a1 = (hi ? s[3] : s[1]) + __shfl_xor(hi ? s[1] : s[3], 32);
-                const float f = (odd ? a1 : a0) + __shfl_xor(odd ? a0 : a1, 16);
+                // (a half swap of (s0, s2) and of (s1, s3), then a row swap of the two sums: no LDS round trip)
+                const float a0 = swap_add<32>(s[0], s[2]);
+                const float a1 = swap_add<32>(s[1], s[3]);
+                const float f = swap_add<16>(a0, a1);
                 const int key = kbase + lane;
                 if (POOL < 0) {
                     if (key < vis[i]) out_w[i * a.row_stride + key] = f;
