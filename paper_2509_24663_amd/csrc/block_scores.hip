@@ -205,10 +205,10 @@ struct ScoreArgs {
 
 __device__ inline float s_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// data-parallel-primitive moves of a float: lane i receives the value of another lane without touching LDS
+// data-parallel-primitive moves of a 32-bit value: lane i receives the value of another lane without touching LDS
 template <int CTRL>
-__device__ inline float dpp_move(float x) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+__device__ inline unsigned dpp_move(unsigned x) {
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, true);
 }
 constexpr int DPP_QUAD_SWAP1 = 0xB1;   // quad_perm [1,0,3,2]
 constexpr int DPP_QUAD_SWAP2 = 0x4E;   // quad_perm [2,3,0,1]
@@ -578,9 +578,9 @@ struct ScoreKernel {
         // 16 kt + m) or is the first lane of the next quad (POOL = 0: window = quad m - 1 and key 4m, block
         // 16 kt + m - 1): either way lane 4m combines its own value with one shifted up by a lane, and what
         // lane 0 needs from the previous tile of the same token is carried in a scalar.
-        float carry[TPW];
+        unsigned carry[TPW];                 // bit patterns of non-negative floats
 #pragma unroll
-        for (int i = 0; i < TPW; ++i) carry[i] = 0.f;
+        for (int i = 0; i < TPW; ++i) carry[i] = 0u;
         float *const out_w = a.out + ((int64_t)h * a.map.total_rows + row0 + w * TPW) * a.row_stride;
         auto vec2_body = [&](int kt, auto edge_c) {
             constexpr bool edge_tile = decltype(edge_c)::value;   // the tile reaches past some token's visible keys
@@ -602,16 +602,17 @@ struct ScoreKernel {
                 if (POOL < 0) {
                     if (key < vis[i]) out_w[i * a.row_stride + key] = f;
                 } else {
-                    // scores are >= 0, so an invisible key counts as 0
-                    const float fz = edge_tile && key >= vis[i] ? 0.f : f;
-                    float qm = fmaxf(fz, dpp_move<DPP_QUAD_SWAP1>(fz));
-                    qm = fmaxf(qm, dpp_move<DPP_QUAD_SWAP2>(qm));
-                    const float shifted_src = POOL ? fz : qm, own = POOL ? qm : fz;
-                    float below = dpp_move<DPP_WAVE_SHR1>(shifted_src);
+                    // scores are >= 0: an invisible key counts as 0, and the maxima are taken on the bit patterns
+                    // (same order as the floats; an integer max folds the lane move into itself)
+                    const unsigned fz = edge_tile && key >= vis[i] ? 0u : __float_as_uint(f);
+                    unsigned qm = max(fz, dpp_move<DPP_QUAD_SWAP1>(fz));
+                    qm = max(qm, dpp_move<DPP_QUAD_SWAP2>(qm));
+                    const unsigned shifted_src = POOL ? fz : qm, own = POOL ? qm : fz;
+                    unsigned below = dpp_move<DPP_WAVE_SHR1>(shifted_src);
                     if (lane == 0) below = carry[i];
-                    carry[i] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(shifted_src), 63));
+                    carry[i] = __builtin_amdgcn_readlane(shifted_src, 63);
                     const bool has_visible_key = !edge_tile || max(4 * jb - POOL, 0) < vis[i];
-                    if (writer && has_visible_key) out_w[i * a.row_stride + jb] = fmaxf(below, own);
+                    if (writer && has_visible_key) out_w[i * a.row_stride + jb] = __uint_as_float(max(below, own));
                 }
             }
         };
@@ -626,7 +627,7 @@ struct ScoreKernel {
             const int jb = nkt * (kBlock / 4) - (POOL ? 0 : 1);
 #pragma unroll
             for (int i = 0; i < TPW; ++i)
-                if (lane == 0 && max(4 * jb - POOL, 0) < vis[i]) out_w[i * a.row_stride + jb] = carry[i];
+                if (lane == 0 && max(4 * jb - POOL, 0) < vis[i]) out_w[i * a.row_stride + jb] = __uint_as_float(carry[i]);
         };
         TilePre pf = load_tile(kt_fine, 0, tid);
         stage_tile(smem, tid, pf);
