@@ -1,7 +1,9 @@
 """Build libinfllmv2.so (HIP kernels + C ABI) for gfx950, in-tree, with hipcc."""
 from __future__ import annotations
 
+import json
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -28,6 +30,17 @@ EXTRA_FLAGS = {
 }
 
 
+def kernel_resources() -> dict:
+    """Resource usage of every kernel of the last build: {source file: {mangled kernel name: {...}}}."""
+    res = {}
+    for src in sources():
+        path = os.path.join(OBJ, src[:-4] + ".resources.json")
+        if os.path.exists(path):
+            with open(path) as f:
+                res[src] = json.load(f)
+    return res
+
+
 def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
@@ -38,15 +51,57 @@ def _compile(src: str, force: bool) -> str:
         os.path.join(CSRC, h) for h in os.listdir(CSRC) if h.endswith(".h")]
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
-    cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-Rpass-analysis=kernel-resource-usage",
+           "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    usage, rest = _split_resource_remarks(r.stdout)
     # the host pass warns that it does not know the packed-fp32 target feature: harmless
-    out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
+    out = "\n".join(l for l in rest if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{out}")
     if out.strip():
         sys.stderr.write(out + "\n")
+    with open(obj[:-2] + ".resources.json", "w") as f:
+        json.dump(usage, f, indent=1)
+    for name, u in usage.items():
+        if u.get("ScratchSize", 0) or u.get("VGPRs Spill", 0):
+            sys.stderr.write(f"note: {src}: kernel {name} uses {u.get('ScratchSize', 0)} B/lane of private-segment memory "
+                             f"({u.get('VGPRs Spill', 0)} spilled VGPRs)\n")
     return obj
+
+
+_REMARK = re.compile(r"remark:\s+(.*?)\s+\[-Rpass-analysis=kernel-resource-usage\]")
+
+
+def _split_resource_remarks(text: str):
+    """Separate the compiler's per-kernel resource remarks from the rest of its output.
+
+    Returns ({mangled kernel name: {"VGPRs": n, "ScratchSize": bytes per lane, "VGPRs Spill": n, ...}}, other lines).
+    A prefetch array that ends up in private-segment memory costs a kernel tens of percent and shows nowhere in the
+    source, so the numbers are kept next to the objects (tests read them) and non-zero scratch is reported.
+    """
+    usage, rest, cur = {}, [], None
+    skip = 0
+    for line in text.splitlines():
+        m = _REMARK.search(line)
+        if m:
+            body = m.group(1)
+            if body.startswith("Function Name:"):
+                cur = body.split(":", 1)[1].strip()
+                usage[cur] = {}
+            elif cur is not None and ":" in body:
+                key, val = body.rsplit(":", 1)
+                key = key.split("[")[0].strip()
+                val = val.strip()
+                usage[cur][key] = int(val) if val.lstrip("-").isdigit() else val
+            skip = 2          # the source line and the caret line that follow a remark
+            continue
+        if skip and (re.match(r"\s*\d+ \|", line) or re.match(r"\s*\|\s*\^", line)):
+            skip -= 1
+            continue
+        skip = 0
+        rest.append(line)
+    return usage, rest
 
 
 def build(force: bool = True, jobs: int = 8) -> str:

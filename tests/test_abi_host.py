@@ -146,3 +146,21 @@ def test_backward_entry_point_validates_on_the_host(m):
     empty = np.array([0, 0], dtype=np.int32).ctypes.data_as(ctypes.c_void_p)
     assert L.infllmv2_sparse_attn_bwd(ctypes.byref(p), None, None, None, 0, 0, None, None, None, None, empty, one, 1,
                                       None, None, None, None) == 0
+
+
+def test_no_kernel_uses_private_segment_memory():
+    """The build records the compiler's per-kernel resource usage.  A register array that the compiler moves to
+    private-segment (scratch) memory costs a hot kernel tens of percent without any sign in the source, so every
+    kernel of the library is required to stay in registers."""
+    from paper_2509_24663_amd import build
+    res = build.kernel_resources()
+    if not res:
+        pytest.skip("no resource records: the library was not built in this tree")
+    assert set(res) == set(build.sources())
+    names = [k for per_file in res.values() for k in per_file]
+    for must in ("block_scores_mfma_kernel", "attn_tile_kernel", "dec_attn_kernel", "topk_blocks_kernel",
+                 "bwd_dq_mfma_kernel", "bwd_dkv_mfma_kernel"):
+        assert any(must in n for n in names), must
+    for src, per_file in res.items():
+        for name, u in per_file.items():
+            assert u["ScratchSize"] == 0 and u["VGPRs Spill"] == 0, (src, name, u)
