@@ -180,7 +180,7 @@ __device__ inline void softmax_pv(TokState &st, f32x4 (&acc)[4], const uint16_t 
 }
 
 // =====================================================================================================
-// Prefill unit: one K/V block (both tiles in one LDS stage) against NT tokens held by this wave.
+// Prefill unit: one K/V block (both tiles in one LDS stage) against the token held by this wave.
 //
 // The vector unit and the matrix core share one issue port per SIMD (4 clocks per instruction, an MFMA keeps
 // the matrix core busy for 16), so every vector instruction in the unit costs matrix-core time unless fewer
@@ -190,20 +190,20 @@ __device__ inline void softmax_pv(TokState &st, f32x4 (&acc)[4], const uint16_t 
 //   * the accumulator of S^T = K Q^T is seeded with minus the running reference of the online softmax,
 // so the MFMA result is already the exponent of 2 and a logit costs one v_exp, one add (row sum) and half a
 // pack instruction.  The reference is lazy: any value shared by the lanes of a head works as long as the
-// exponents stay far from overflow, so it only moves when an exponent exceeds kRefSlack.
+// exponents stay far from overflow, so it only moves when the probabilities show that an exponent was large.
 //
 // LDS bandwidth is the other limit (a one-token unit reads 32 KB for 32 MFMAs), and 8-byte transposing reads run
 // at half the rate of 16-byte reads.  V therefore comes from a transposed copy (V^T, one [128 dims][64 keys]
 // tile per block, made by a small pre-pass), so that both operands are fetched with ds_read_b128:
 //   * K tile  [64 keys][128 dims], 256-byte rows, 16-byte chunk c of row r stored at chunk c ^ f(r),
 //     f(r) = 4 * ((r >> 3) & 3) + (r & 3);
-//   * V^T tile [128 dims][64 keys], 128-byte rows, chunk c of row r stored at chunk c ^ (r & 7).
+//   * V^T tile [128 dims][64 keys], 128-byte rows, chunk c of row r stored at chunk c ^ ((r >> 1) & 7): two rows
+//     span the 64 banks, so the 16 lanes of a group (rows m .. m + 15, same logical chunk) must differ in
+//     (r & 1, position) -- a swizzle by r & 7 would send rows r and r + 8 to the same banks.
 // Row m of the A operand of S^T's key tile kt is key 32 (kt / 2) + 8 (m / 4) + 4 (kt % 2) + (m % 4): with that
 // order the exponents a lane ends up with are exactly the eight consecutive keys 32 s2 + 8 (lane / 16) .. + 7 it
 // must supply as B operand of PV k-step s2, and f(key) = m for every kt, so one address per k-step serves all
 // key tiles through the instruction's immediate offset.
-//
-// With NT = 2 every K and V^T fragment read from LDS feeds two MFMAs (one per token).
 constexpr int VT_TILE_ELEMS = D * kBlock;            // one V^T block: 128 rows x 128 B
 
 struct LaneOffs2 {
@@ -218,7 +218,7 @@ __device__ inline LaneOffs2 lane_offsets2(int lane) {
 #pragma unroll
     for (int s = 0; s < 4; ++s) o.kx[s] = krow * D + (((4 * s + g) ^ m16) << 3);
 #pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2) o.vx[s2] = m16 * kBlock + (((4 * s2 + g) ^ (m16 & 7)) << 3);
+    for (int s2 = 0; s2 < 2; ++s2) o.vx[s2] = m16 * kBlock + (((4 * s2 + g) ^ ((m16 >> 1) & 7)) << 3);
     return o;
 }
 
@@ -231,7 +231,7 @@ __device__ inline void k_piece_src(int q, int lane, int &row, int &chunk) {
 // V^T piece q (rows 8q .. 8q+7 of the tile): lane l fills (row 8q + l / 8, physical chunk l % 8).
 __device__ inline uint32_t vt_piece_src_bytes(int q, int lane) {
     const int row = 8 * q + (lane >> 3);
-    const int chunk = (lane & 7) ^ (row & 7);
+    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
     return (uint32_t)(row * kBlock + chunk * 8) * 2u;
 }
 
@@ -243,7 +243,8 @@ struct Tok {
     bool fresh;        // no block consumed yet (wave-uniform)
 };
 
-constexpr float kRefSlack = 8.0f;
+// a lane's 16 probabilities may sum to this much before the reference moves (each is then < 2^12)
+constexpr float kSumSlack = 4096.0f;
 
 __device__ inline void tok_init(Tok &t) {
 #pragma unroll
@@ -270,8 +271,26 @@ __device__ inline bf16x8 v_frag(const uint16_t *vtile, const LaneOffs2 &lo, int 
     return *reinterpret_cast<const bf16x8 *>(vtile + (i & 7) * 16 * kBlock + lo.vx[i >> 3]);
 }
 
-// Exponents of one token -> probabilities (P^T as B operand of the two PV k-steps: slot i = key 32 s2 + 8g + i),
-// with the causal mask of the token's own block and the lazy reference.
+// 2^exponent for the 16 exponents of a lane, packed as the B operand of the two PV k-steps (slot i = key
+// 32 s2 + 8g + i); returns their sum
+__device__ inline float probs(const f32x4 (&acc)[4], bf16x8 (&pb)[2]) {
+    float ls = 0.f;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float p0 = fast_exp2(acc[2 * s2][r]), p1 = fast_exp2(acc[2 * s2 + 1][r]);
+            ls += p0 + p1;
+            pb[s2][r] = (__bf16)p0;
+            pb[s2][4 + r] = (__bf16)p1;
+        }
+    return ls;
+}
+
+// Exponents of one token -> probabilities, with the causal mask of the token's own block and the lazy reference.
+// The probabilities are computed with the reference as it is; only if a lane's sum of them says that an exponent
+// was large (or this is the token's first block) is the reference moved and the work redone from the exponents,
+// which are still in acc.  The common case then has no maximum to compute at all.
 template <bool OWN>
 __device__ inline void softmax_tok(Tok &t, f32x4 (&acc)[4], bf16x8 (&pb)[2], int g, int key_limit) {
     if (OWN) {
@@ -281,15 +300,16 @@ __device__ inline void softmax_tok(Tok &t, f32x4 (&acc)[4], bf16x8 (&pb)[2], int
             for (int r = 0; r < 4; ++r)
                 if (32 * (kt >> 1) + 8 * g + 4 * (kt & 1) + r > key_limit) acc[kt][r] = -INFINITY;
     }
-    float mx = fmaxf(fmaxf(acc[0][0], acc[0][1]), acc[0][2]);
-    mx = fmaxf(fmaxf(mx, acc[0][3]), acc[1][0]);
-    mx = fmaxf(fmaxf(mx, acc[1][1]), acc[1][2]);
-    mx = fmaxf(fmaxf(mx, acc[1][3]), acc[2][0]);
-    mx = fmaxf(fmaxf(mx, acc[2][1]), acc[2][2]);
-    mx = fmaxf(fmaxf(mx, acc[2][3]), acc[3][0]);
-    mx = fmaxf(fmaxf(mx, acc[3][1]), acc[3][2]);
-    mx = fmaxf(mx, acc[3][3]);
-    if (t.fresh || __any(mx > kRefSlack)) {
+    float ls = probs(acc, pb);
+    if (t.fresh || __any(!(ls < kSumSlack))) {
+        float mx = fmaxf(fmaxf(acc[0][0], acc[0][1]), acc[0][2]);
+        mx = fmaxf(fmaxf(mx, acc[0][3]), acc[1][0]);
+        mx = fmaxf(fmaxf(mx, acc[1][1]), acc[1][2]);
+        mx = fmaxf(fmaxf(mx, acc[1][3]), acc[2][0]);
+        mx = fmaxf(fmaxf(mx, acc[2][1]), acc[2][2]);
+        mx = fmaxf(fmaxf(mx, acc[2][3]), acc[3][0]);
+        mx = fmaxf(fmaxf(mx, acc[3][1]), acc[3][2]);
+        mx = fmaxf(mx, acc[3][3]);
         // move the reference of every head to its current maximum (never down once there is history)
         float delta = rows_max(mx);
         float alpha = 1.0f;
@@ -307,29 +327,18 @@ __device__ inline void softmax_tok(Tok &t, f32x4 (&acc)[4], bf16x8 (&pb)[2], int
         t.l *= alpha;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) t.o[dt] *= alpha;
+        ls = probs(acc, pb);
     }
-    float ls = 0.f;
-#pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float p0 = fast_exp2(acc[2 * s2][r]), p1 = fast_exp2(acc[2 * s2 + 1][r]);
-            ls += p0 + p1;
-            pb[s2][r] = (__bf16)p0;
-            pb[s2][4 + r] = (__bf16)p1;
-        }
     t.l += ls;
 }
 
-// key_limit[n]: last visible key of the block for token n (only used when OWN)
-template <int NT, bool OWN>
-__device__ inline void unit_n(Tok *const (&t)[NT], const uint16_t *stage, const LaneOffs2 &lo, int lane,
-                              const int (&key_limit)[NT]) {
+// One token against one block.  OWN: the block is the token's own and keys past key_limit are masked.
+template <bool OWN>
+__device__ inline void unit(Tok &t, const uint16_t *stage, const LaneOffs2 &lo, int lane, int key_limit) {
     const uint16_t *ktile = stage, *vtile = stage + TILE_ELEMS;
-    const int g = lane >> 4;
-    constexpr int W = 4;               // operand fetches run W MFMA groups ahead
-    f32x4 acc[NT][4];
-    bf16x8 pb[NT][2];
+    constexpr int W = 4;               // operand fetches run W MFMAs ahead
+    f32x4 acc[4];
+    bf16x8 pb[2];
     bf16x8 f[W];
     // ---- exponents: S^T seeded with minus the reference
 #pragma unroll
@@ -337,33 +346,20 @@ __device__ inline void unit_n(Tok *const (&t)[NT], const uint16_t *stage, const 
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int kt = i & 3, s = i >> 2;
-#pragma unroll
-        for (int n = 0; n < NT; ++n)
-            acc[n][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[i % W], t[n]->qf[s], s == 0 ? t[n]->nm : acc[n][kt], 0, 0, 0);
+        acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[i % W], t.qf[s], s == 0 ? t.nm : acc[kt], 0, 0, 0);
         if (i + W < 16) f[i % W] = k_frag(ktile, lo, i + W);
     }
     // V^T fragments of the first k-step are requested before the softmax so that they arrive under it
 #pragma unroll
     for (int i = 0; i < W; ++i) f[i] = v_frag(vtile, lo, i);
-#pragma unroll
-    for (int n = 0; n < NT; ++n) softmax_tok<OWN>(*t[n], acc[n], pb[n], g, key_limit[n]);
+    softmax_tok<OWN>(t, acc, pb, lane >> 4, key_limit);
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int dt = i & 7, s2 = i >> 3;
-#pragma unroll
-        for (int n = 0; n < NT; ++n)
-            t[n]->o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[i % W], pb[n][s2], t[n]->o[dt], 0, 0, 0);
+        t.o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[i % W], pb[s2], t.o[dt], 0, 0, 0);
         if (i + W < 16) f[i % W] = v_frag(vtile, lo, i + W);
     }
-}
-
-// one token against one block; OWN: the block is the token's own, keys past key_limit are masked
-template <bool OWN>
-__device__ inline void unit(Tok &a, const uint16_t *stage, const LaneOffs2 &lo, int lane, int key_limit) {
-    Tok *const t[1] = {&a};
-    const int kl[1] = {key_limit};
-    unit_n<1, OWN>(t, stage, lo, lane, kl);
 }
 
 }  // namespace attn_unit
