@@ -347,10 +347,7 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
 }
 
 // ------------------------------------------------------------------------------------------ attend + merge
-#ifndef IFV2_DEC_AW
-#define IFV2_DEC_AW 8
-#endif
-constexpr int AW = IFV2_DEC_AW;   // waves (= selected blocks) per attend workgroup
+constexpr int AW = 8;              // waves (= selected blocks) per attend workgroup
 
 __global__ void __launch_bounds__(AW * 64) dec_attn_kernel(DecArgs a) {
     extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];     // AW V tiles of 16 KB, one per wave
