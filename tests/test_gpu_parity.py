@@ -645,3 +645,44 @@ def test_backward_bf16_matrix_core_path(m, oracle, n):
     _check_backward(m, oracle, w, gp, op, "bf16")
     if n <= 129:
         _check_backward(m, oracle, w, gp, op, "bf16", dense_all=True)
+
+
+@pytest.mark.parametrize("case", range(10))
+def test_seeded_random_configurations(m, oracle, case):
+    """Randomly drawn (but seeded, hence repeatable) workloads on the matrix-core path: packed lengths on both
+    sides of the switch, selection budgets, pooling shift and the LSE Approximation, every stage against the
+    oracle.  Complements the hand-picked cases above with combinations nobody thought of."""
+    rng = np.random.default_rng(9000 + case)
+    nseq = int(rng.integers(1, 5))
+    lens = [int(x) for x in rng.choice([1, 17, 31, 32, 63, 64, 65, 127, 129, 300, 511, 777, 1200, 1700], size=nseq)]
+    n_init = int(rng.integers(0, 3))
+    n_local = int(rng.integers(1, 5))
+    topk_total = n_init + n_local + int(rng.integers(0, 8))
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=n_init, n_local=n_local, topk_total=topk_total,
+                     dense_threshold=int(rng.choice([0, 64, 400, 1000])), pool_pad=int(rng.integers(0, 2)),
+                     lse_mode=int(rng.integers(0, 2)))
+    w = synth.make_varlen(lens, 32, 2, 128, seed=9100 + case, dtype="bf16")
+    _run_prefill_case(m, oracle, w, gp, op, "bf16")
+    # the fused-pooling form of stages 2-3 selects the same blocks
+    q, k, v = (to_dev(w[x], "bf16") for x in ("q", "k", "v"))
+    two = m.sparse_prefill(gp, q, k, v, w["cu_seqlens"])
+    fused = m.sparse_prefill(gp, q, k, v, w["cu_seqlens"], fused_pool=True)
+    torch.cuda.synchronize()
+    assert torch.equal(two["block_idx"], fused["block_idx"]) and torch.equal(two["out"], fused["out"])
+
+
+@pytest.mark.parametrize("case", range(6))
+def test_seeded_random_decode_configurations(m, oracle, case):
+    """The decode step on randomly drawn (seeded) batches: context lengths around block, window and switch
+    boundaries, selection budgets, pooling shift and the LSE Approximation, against the oracle."""
+    rng = np.random.default_rng(9500 + case)
+    ctx = [int(x) for x in rng.choice([1, 2, 31, 32, 33, 64, 65, 128, 200, 513, 1000, 2047, 2048, 2049, 3333, 5000],
+                                      size=int(rng.integers(1, 7)))]
+    n_init = int(rng.integers(0, 3))
+    n_local = int(rng.integers(1, 5))
+    topk_total = n_init + n_local + int(rng.integers(0, 12))
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=n_init, n_local=n_local, topk_total=topk_total,
+                     dense_threshold=int(rng.choice([0, 100, 1500])), pool_pad=int(rng.integers(0, 2)),
+                     lse_mode=int(rng.integers(0, 2)))
+    w = synth.make_decode(ctx, 32, 2, 128, seed=9600 + case, dtype="bf16", max_len=(max(ctx) + 63) // 64 * 64)
+    _check_decode(m, oracle, w, ctx, gp, op, "bf16")
