@@ -686,3 +686,16 @@ def test_seeded_random_decode_configurations(m, oracle, case):
                      lse_mode=int(rng.integers(0, 2)))
     w = synth.make_decode(ctx, 32, 2, 128, seed=9600 + case, dtype="bf16", max_len=(max(ctx) + 63) // 64 * 64)
     _check_decode(m, oracle, w, ctx, gp, op, "bf16")
+
+
+@pytest.mark.parametrize("case", range(5))
+def test_seeded_random_backward_configurations(m, oracle, case):
+    """Gradients of stage 4 on randomly drawn (seeded) packed workloads, matrix-core path."""
+    rng = np.random.default_rng(9700 + case)
+    lens = [int(x) for x in rng.choice([1, 33, 64, 65, 130, 257, 600, 1100], size=int(rng.integers(1, 4)))]
+    n_init = int(rng.integers(0, 3))
+    n_local = int(rng.integers(1, 4))
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=n_init, n_local=n_local,
+                     topk_total=n_init + n_local + int(rng.integers(0, 6)), dense_threshold=int(rng.choice([0, 100, 500])))
+    w = synth.make_varlen(lens, 32, 2, 128, seed=9800 + case, dtype="bf16")
+    _check_backward(m, oracle, w, gp, op, "bf16")
