@@ -58,12 +58,52 @@ struct TileKernel {
     static_assert(32 % NW == 0, "32 one-KB load instructions are dealt round-robin to the waves");
     static_assert(SLOTS == 1 || SLOTS == 2, "one or two entries per interval");
 
+    // which of the CU's four SIMDs this wave runs on (hardware id register, bits 5:4)
+    __device__ static inline int simd_id() { return (int)__builtin_amdgcn_s_getreg(4 | (4 << 6) | (1 << 11)); }
+
+    // An interval holds two consecutive entries of the union list, and between its barriers a SIMD works through
+    // the units of the waves it hosts, so an interval lasts about as long as its busiest SIMD.  The list (all of
+    // it but the tile's own block, which stays last) is therefore re-paired: each wave takes a contiguous, even
+    // sized range of entries and repeatedly joins its first remaining entry to the one that raises the pair's
+    // busiest SIMD the least.  Partners stay a few entries apart, so the walk remains nearly ascending
+    // (neighbouring tiles then touch the same blocks at about the same time, which the L2 likes).
+    __device__ static inline void pair_entries(int2 *rec, int body, int w, int lane, const uint32_t *simd_waves) {
+        const int pairs = body / 2;
+        const int lo = 2 * (pairs * w / NW), hi = 2 * (pairs * (w + 1) / NW);
+        const int n = hi - lo;
+        if (n < 4 || n > 64) return;                        // nothing to choose / more entries than lanes: left as is
+        bool live = lane < n;
+        const int2 r = live ? rec[lo + lane] : make_int2(NONE, 0);
+        uint32_t loads = 0u;                                // consumers per SIMD, one byte each
+#pragma unroll
+        for (int sd = 0; sd < 4; ++sd) loads |= (uint32_t)__popc((uint32_t)r.y & simd_waves[sd]) << (8 * sd);
+        auto max_byte = [](uint32_t x) -> int {
+            return (int)max(max(x & 0xffu, (x >> 8) & 0xffu), max((x >> 16) & 0xffu, x >> 24));
+        };
+        const int own_max = max_byte(loads);
+        for (int pos = lo; pos < hi; pos += 2) {
+            // first: the live entry with the smallest block number, which keeps the walk close to ascending
+            const int first = __ffsll((long long)__ballot(live)) - 1;
+            const uint32_t lf = (uint32_t)__builtin_amdgcn_readlane((int)loads, first);
+            if (lane == first) { rec[pos] = r; live = false; }
+            // second: the live entry whose company costs the least beyond what it would cost alone
+            const int extra = max_byte(lf + loads) - own_max;
+            int second = 0;
+            for (int c = 0; c <= NW / 4; ++c) {
+                const uint64_t b = __ballot(live && extra == c);
+                if (b) { second = __ffsll((long long)b) - 1; break; }
+            }
+            if (lane == second) { rec[pos + 1] = r; live = false; }
+        }
+    }
+
     __device__ static void run(const AttnArgs &a, int num_tiles) {
         extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
         uint16_t *stages = smem;
         uint32_t *masks = reinterpret_cast<uint32_t *>(smem + NSTAGE * STAGE_ELEMS);
         int2 *rec = reinterpret_cast<int2 *>(masks + a.nb_cap);          // union list: (block, token mask) per entry
         __shared__ int s_seq, s_tile, s_blk0, s_ne, s_ni;
+        __shared__ uint32_t s_simd_waves[4];                             // waves (= tokens) resident on each SIMD
 
         const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
         const int h = blockIdx.y;
@@ -92,8 +132,10 @@ struct TileKernel {
             s_seq = s;
             s_tile = rem;
             s_blk0 = blk0;
+            for (int i = 0; i < 4; ++i) s_simd_waves[i] = 0u;
         }
         __syncthreads();
+        if (SLOTS == 2 && lane == 0) atomicOr(&s_simd_waves[simd_id()], 1u << w);     // read after later barriers
         const int seq = __builtin_amdgcn_readfirstlane(s_seq);
         if (seq >= a.map.batch) return;
         const int tok0 = a.map.cu[seq], len = a.map.cu[seq + 1] - tok0;
@@ -132,6 +174,10 @@ struct TileKernel {
             }
             __syncthreads();
             ni = __builtin_amdgcn_readfirstlane(s_ni);
+            if (SLOTS == 2) {
+                pair_entries(rec, __builtin_amdgcn_readfirstlane(s_ne) - 1, w, lane, s_simd_waves);
+                __syncthreads();
+            }
         } else {
             ni = nblk;
         }
