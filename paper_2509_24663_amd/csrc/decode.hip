@@ -29,7 +29,8 @@ namespace {
 
 using namespace attn_unit;
 
-constexpr int CK = 128;           // compressed keys per scores workgroup (4 waves x 2 tiles of 16)
+constexpr int SC_TILES = 2;               // 16-key tiles per wave of the scores kernel
+constexpr int CK = 4 * SC_TILES * 16;     // compressed keys per scores workgroup (4 waves)
 constexpr int OPART = G * D;      // floats of one partial output
 
 struct DecArgs {
@@ -74,16 +75,27 @@ __global__ void __launch_bounds__(256) dec_scores_kernel(DecArgs a) {
         float m[4], l[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) { m[r] = -INFINITY; l[r] = 0.f; }
+        // every load of the wave is requested before anything is computed: one trip to memory, not one per tile
+        float4 xs[SC_TILES][4][2];
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const int key = chunk * CK + w * 32 + nt * 16 + n16;
-            const bool valid = key < v;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            const float *kr = kcb + (int64_t)(valid ? key : 0) * D + g * 8;
+        for (int nt = 0; nt < SC_TILES; ++nt) {
+            const int key = chunk * CK + w * (SC_TILES * 16) + nt * 16 + n16;
+            const float *kr = kcb + (int64_t)(key < v ? key : 0) * D + g * 8;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const float4 x0 = *reinterpret_cast<const float4 *>(kr + s * 32);
-                const float4 x1 = *reinterpret_cast<const float4 *>(kr + s * 32 + 4);
+                xs[nt][s][0] = *reinterpret_cast<const float4 *>(kr + s * 32);
+                xs[nt][s][1] = *reinterpret_cast<const float4 *>(kr + s * 32 + 4);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int nt = 0; nt < SC_TILES; ++nt) {
+            const int key = chunk * CK + w * (SC_TILES * 16) + nt * 16 + n16;
+            const bool valid = key < v;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const float4 x0 = xs[nt][s][0], x1 = xs[nt][s][1];
                 const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
                 bf16x8 bh, bl;
 #pragma unroll
