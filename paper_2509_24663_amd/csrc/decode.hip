@@ -400,6 +400,9 @@ __global__ void __launch_bounds__(AW * 64) dec_attn_kernel(DecArgs a) {
         const uint16_t *qp = a.q + ((int64_t)b * a.hq + h * G + m16) * D + g * 8;
 #pragma unroll
         for (int s = 0; s < 4; ++s) st.qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(qp + s * 32));
+        // every load of the wave is in flight before the first product (left alone, the scheduler requests the
+        // last third of the K fragments one at a time between the products: a chain of trips to memory)
+        __builtin_amdgcn_sched_barrier(0);
         const LaneOffs lo = lane_offsets(lane);
         f32x4 acc[4];
 #pragma unroll
