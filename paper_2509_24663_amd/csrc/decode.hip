@@ -41,7 +41,7 @@ struct DecArgs {
     int64_t kv_batch_stride, kv_head_stride, kv_tok_stride, kc_head_stride;
     float scale;
     TopkArgs tk;
-    float *z;          // [pairs][16][zs] log2-domain logits c * <q, kc>
+    float *z;          // [pairs][zs keys][16 heads] log2-domain logits c * <q, kc>
     float *part;       // [pairs][nchunk][16][2] (max, sum 2^(z - max)) per chunk
     int32_t *idx;      // [pairs][topk_total]
     float *opart;      // [pairs][nsplit][OPART]  partial O^T ([dim][head]) relative to the split's own max
@@ -51,6 +51,25 @@ struct DecArgs {
     int zs, nchunk, nsplit;
     int lse_mode;      // 1: normalise with the log-sum-exp over the four times coarser keys (LSE Approximation, Sec. 3.4)
 };
+
+// reductions over the 16 lanes of a row (lanes with equal lane / 16), result in every lane, without LDS: swaps inside
+// quads, then the mirror images inside 8 and 16 lanes
+template <int CTRL>
+__device__ inline float row_move(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+__device__ inline float row_all_max(float x) {
+    x = fmaxf(x, row_move<0xB1>(x));      // quad_perm [1,0,3,2]
+    x = fmaxf(x, row_move<0x4E>(x));      // quad_perm [2,3,0,1]
+    x = fmaxf(x, row_move<0x141>(x));     // row_half_mirror
+    return fmaxf(x, row_move<0x140>(x));  // row_mirror
+}
+__device__ inline float row_all_sum(float x) {
+    x += row_move<0xB1>(x);
+    x += row_move<0x4E>(x);
+    x += row_move<0x141>(x);
+    return x + row_move<0x140>(x);
+}
 
 // ------------------------------------------------------------------------------------------ scores
 __global__ void __launch_bounds__(256) dec_scores_kernel(DecArgs a) {
@@ -72,9 +91,6 @@ __global__ void __launch_bounds__(256) dec_scores_kernel(DecArgs a) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(qp + s * 32));
         const float *kcb = a.kc + (int64_t)pair * a.kc_head_stride;
-        float m[4], l[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) { m[r] = -INFINITY; l[r] = 0.f; }
         // every load of the wave is requested before anything is computed: one trip to memory, not one per tile
         float4 xs[SC_TILES][4][2];
 #pragma unroll
@@ -88,6 +104,7 @@ __global__ void __launch_bounds__(256) dec_scores_kernel(DecArgs a) {
             }
         }
         __builtin_amdgcn_sched_barrier(0);
+        float zc[SC_TILES][4];                         // logits of key tile nt, heads 4g .. 4g+3 (-inf: not visible)
 #pragma unroll
         for (int nt = 0; nt < SC_TILES; ++nt) {
             const int key = chunk * CK + w * (SC_TILES * 16) + nt * 16 + n16;
@@ -107,30 +124,27 @@ __global__ void __launch_bounds__(256) dec_scores_kernel(DecArgs a) {
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[s], bh, acc, 0, 0, 0);
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[s], bl, acc, 0, 0, 0);
             }
-            // acc[r] = <q_head(4g+r), kc_key>
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float zc = acc[r] * c;
-                if (valid) {
-                    a.z[((int64_t)pair * G + 4 * g + r) * a.zs + key] = zc;
-                    const float mn = fmaxf(m[r], zc);
-                    l[r] = l[r] * fast_exp2(m[r] - mn) + fast_exp2(zc - mn);
-                    m[r] = mn;
-                }
-            }
+            // acc[r] = <q_head(4g+r), kc_key>: the key's 16 logits are 64 contiguous bytes, this lane writes 16 of them
+            const float4 zv = make_float4(acc[0] * c, acc[1] * c, acc[2] * c, acc[3] * c);
+            if (valid) *reinterpret_cast<float4 *>(a.z + ((int64_t)pair * a.zs + key) * G + 4 * g) = zv;
+            zc[nt][0] = valid ? zv.x : -INFINITY;
+            zc[nt][1] = valid ? zv.y : -INFINITY;
+            zc[nt][2] = valid ? zv.z : -INFINITY;
+            zc[nt][3] = valid ? zv.w : -INFINITY;
         }
-        // merge over the 16 key lanes, then over the 4 waves
+        // per head: max and sum of 2^(z - max) over the wave's keys -- over this lane's tiles, then over the 16 key
+        // lanes with data-parallel moves (no LDS round trips)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            float mm = m[r], ll = l[r];
+            float mm = zc[0][r];
 #pragma unroll
-            for (int o = 1; o < 16; o <<= 1) {
-                const float mo = __shfl_xor(mm, o), lo = __shfl_xor(ll, o);
-                const float mn = fmaxf(mm, mo);
-                const float ms = mn == -INFINITY ? 0.f : mn;
-                ll = ll * fast_exp2(mm - ms) + lo * fast_exp2(mo - ms);
-                mm = mn;
-            }
+            for (int nt = 1; nt < SC_TILES; ++nt) mm = fmaxf(mm, zc[nt][r]);
+            mm = row_all_max(mm);
+            const float ms = mm == -INFINITY ? 0.f : mm;
+            float ll = 0.f;
+#pragma unroll
+            for (int nt = 0; nt < SC_TILES; ++nt) ll += fast_exp2(zc[nt][r] - ms);
+            ll = row_all_sum(ll);
             if (n16 == 0) { red[w][4 * g + r][0] = mm; red[w][4 * g + r][1] = ll; }
         }
         __syncthreads();
@@ -208,12 +222,16 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
     constexpr int ZPT = 4;                               // covers 4096 compressed keys = 65K tokens of context
     float zr[ZPT][G];
     {
-        const float *zb0 = a.z + (int64_t)pair * G * a.zs;
+        const float *zb0 = a.z + (int64_t)pair * a.zs * G;
 #pragma unroll
         for (int u = 0; u < ZPT; ++u) {
             const int i = min(tid + u * SEL_THREADS, max(v - 1, 0));
+            const float4 *zk = reinterpret_cast<const float4 *>(zb0 + (int64_t)i * G);
 #pragma unroll
-            for (int gq = 0; gq < G; ++gq) zr[u][gq] = zb0[(int64_t)gq * a.zs + i];
+            for (int q4 = 0; q4 < G / 4; ++q4) {
+                const float4 t4 = zk[q4];
+                zr[u][4 * q4] = t4.x; zr[u][4 * q4 + 1] = t4.y; zr[u][4 * q4 + 2] = t4.z; zr[u][4 * q4 + 3] = t4.w;
+            }
         }
     }
     // ---- log2 of sum_i 2^z per head: 64 thread groups per head over the chunk partials, then 64 -> 1
@@ -237,10 +255,11 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
         const int head = tid & 15, pg = tid >> 4;
         const int cstep = a.tk.lc / a.tk.sc;
         const int v2 = min(visible_cmp(t, 4 * a.tk.lc, 4 * a.tk.sc), num_cmp(L, 4 * a.tk.lc, 4 * a.tk.sc));
-        const float *zh = a.z + ((int64_t)pair * G + head) * a.zs;
+        const float *zh = a.z + (int64_t)pair * a.zs * G + head;           // logit of key i at zh[i * G]
         float mm = -INFINITY, ll = 0.f;
         for (int i2 = pg; i2 < v2; i2 += 64) {
-            const float zc = 0.25f * ((zh[4 * i2] + zh[4 * i2 + cstep]) + (zh[4 * i2 + 2 * cstep] + zh[4 * i2 + 3 * cstep]));
+            const float zc = 0.25f * ((zh[(4 * i2) * G] + zh[(4 * i2 + cstep) * G]) +
+                                      (zh[(4 * i2 + 2 * cstep) * G] + zh[(4 * i2 + 3 * cstep) * G]));
             const float mn = fmaxf(mm, zc);
             ll = ll * fast_exp2(mm - mn) + fast_exp2(zc - mn);
             mm = mn;
@@ -273,10 +292,10 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
         }
     }
     for (int i = tid + ZPT * SEL_THREADS; i < v; i += SEL_THREADS) {      // longer contexts: the rest, unprefetched
-        const float *zb = a.z + (int64_t)pair * G * a.zs + i;
+        const float *zb = a.z + ((int64_t)pair * a.zs + i) * G;
         float sum = 0.f;
 #pragma unroll
-        for (int gq = 0; gq < G; ++gq) sum += fast_exp2(zb[(int64_t)gq * a.zs] - lse2[gq]);
+        for (int gq = 0; gq < G; ++gq) sum += fast_exp2(zb[gq] - lse2[gq]);
         sh[i] = sum;
     }
     __syncthreads();
