@@ -71,6 +71,16 @@ __device__ inline float row_all_sum(float x) {
     return x + row_move<0x140>(x);
 }
 
+// sum over the four 16-lane rows of a wave (lanes with equal lane % 16), result in every lane
+__device__ inline float rows_sum(float x) {
+    const unsigned u = __float_as_uint(x);
+    const auto p = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const float s1 = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+    const unsigned v = __float_as_uint(s1);
+    const auto q = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
+
 // ------------------------------------------------------------------------------------------ scores
 __global__ void __launch_bounds__(256) dec_scores_kernel(DecArgs a) {
     const int chunk = blockIdx.x, pair = blockIdx.y;
@@ -191,7 +201,7 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
     uint32_t *pk = reinterpret_cast<uint32_t *>(sel_smem + sh_cap);    // [(sh_cap + 3) / 4 + 1] pooled keys per block
     __shared__ float red[64][16][2];
     __shared__ float lse2[16];
-    __shared__ int hist[256];
+    __shared__ int hist[4][256];                 // one histogram per radix pass, all zeroed up front
     __shared__ int wave_tot[SEL_WAVES];
     __shared__ uint32_t s_prefix;
     __shared__ int s_k;
@@ -268,16 +278,14 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
         red[pg][head][1] = ll;
     }
     {
+        // 64 -> 1 per head: wavefront w takes head w, one thread group per lane, merged with lane moves
         __syncthreads();
-        if (tid < 16) {
-            float m2 = -INFINITY;
-            for (int k = 0; k < 64; ++k) m2 = fmaxf(m2, red[k][tid][0]);
-            float l2 = 0.f;
-            for (int k = 0; k < 64; ++k)
-                if (red[k][tid][0] != -INFINITY) l2 += red[k][tid][1] * fast_exp2(red[k][tid][0] - m2);
-            // no coarse key visible yet (LSE Approximation only): every score is zero
-            lse2[tid] = l2 > 0.f ? m2 + __log2f(l2) : INFINITY;
-        }
+        static_assert(SEL_WAVES == G, "one wavefront per head");
+        const float mk = red[lane][w][0], lk = red[lane][w][1];
+        const float m2 = rows_max(row_all_max(mk));
+        const float l2 = rows_sum(row_all_sum(mk == -INFINITY ? 0.f : lk * fast_exp2(mk - m2)));
+        // no coarse key visible yet (LSE Approximation only): every score is zero
+        if (lane == 0) lse2[w] = l2 > 0.f ? m2 + __log2f(l2) : INFINITY;
         __syncthreads();
     }
     // ---- S^shared[i] = sum over the 16 heads of 2^(z[g][i] - lse2[g]), kept in LDS
@@ -313,17 +321,17 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
         pk[j] = __float_as_uint(m);
     }
     if (tid == 0) { s_prefix = 0u; s_k = kr; }
+    (&hist[0][0])[tid] = 0;                      // SEL_THREADS = 4 x 256
     __syncthreads();
     // ---- radix select (4 x 8 bits) of the kr-th largest key among the live blocks
+    static_assert(SEL_THREADS == 4 * 256, "histograms zeroed by one store per thread");
     for (int pass = 3; pass >= 0; --pass) {
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
         const uint32_t prefix = s_prefix;
         const int hi_shift = 8 * (pass + 1);
         for (int j = tid; j < nblk; j += SEL_THREADS) {
             if (!live(j)) continue;
             const uint32_t key = pk[j];
-            if (pass == 3 || (key >> hi_shift) == prefix) atomicAdd(&hist[(key >> (8 * pass)) & 255u], 1);
+            if (pass == 3 || (key >> hi_shift) == prefix) atomicAdd(&hist[pass][(key >> (8 * pass)) & 255u], 1);
         }
         __syncthreads();
         if (w == 0) {
@@ -331,7 +339,7 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
             const int k = s_k;
             int c[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) c[u] = hist[4 * lane + u];
+            for (int u = 0; u < 4; ++u) c[u] = hist[pass][4 * lane + u];
             const int mine = c[0] + c[1] + c[2] + c[3];
             int higher = 0;                              // keys in lanes above this one
             {
