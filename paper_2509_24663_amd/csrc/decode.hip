@@ -44,7 +44,8 @@ struct DecArgs {
     float *z;          // [pairs][zs keys][16 heads] log2-domain logits c * <q, kc>
     float *part;       // [pairs][nchunk][16][2] (max, sum 2^(z - max)) per chunk
     int32_t *idx;      // [pairs][topk_total]
-    float *opart;      // [pairs][nsplit][OPART]  partial O^T ([dim][head]) relative to the split's own max
+    float *opart;      // [pairs][nsplit][OPART]  partial O^T relative to the split's own max, in the attend kernel's
+                       // register order: float4 slot dt * 64 + lane = dims 16 dt + 4 (lane / 16) .. + 3 of head lane % 16
     float *mlpart;     // [pairs][nsplit][16][2]
     uint16_t *out;     // [batch][hq][d]
     float *lse;        // [batch][hq] or nullptr
@@ -447,23 +448,30 @@ __global__ void __launch_bounds__(AW * 64) dec_attn_kernel(DecArgs a) {
     }
     if (g == 0) { wm[w][m16] = st.m; wl[w][m16] = st.l; }
     __syncthreads();                                  // every wave is done with its V tile: reuse as scratch
-    float *scr = reinterpret_cast<float *>(smem);      // [AW waves][dim][head]
+    // Each wave scales its partial to the workgroup's reference of its lane's head and lays it down as it sits in
+    // registers (slot dt * 64 + lane holds dims 16 dt + 4 (lane / 16) .. + 3 of head lane % 16); one thread per slot
+    // then adds the AW partials: 16-byte LDS traffic only, no exponentials in the sum.
+    static_assert(AW * 64 * 4 == OPART, "one 16-byte slot of the partial output per thread");
+    {
+        float mm = wm[0][m16];
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt)
+        for (int k = 1; k < AW; ++k) mm = fmaxf(mm, wm[k][m16]);
+        const float wgt = st.m == -INFINITY ? 0.f : fast_exp2((st.m - mm) * c);
+        float4 *scr4 = reinterpret_cast<float4 *>(smem);           // [AW waves][512 slots]
 #pragma unroll
-        for (int r = 0; r < 4; ++r) scr[w * OPART + (dt * 16 + 4 * g + r) * G + m16] = st.o[dt][r];
+        for (int dt = 0; dt < 8; ++dt)
+            scr4[w * (OPART / 4) + dt * 64 + lane] = make_float4(st.o[dt][0] * wgt, st.o[dt][1] * wgt, st.o[dt][2] * wgt, st.o[dt][3] * wgt);
+    }
     __syncthreads();
-    float *op = a.opart + ((int64_t)pair * a.nsplit + split) * OPART;
-    for (int o = tid; o < OPART; o += AW * 64) {
-        const int head = o & 15;
-        float mm = -INFINITY;
+    {
+        const float4 *scr4 = reinterpret_cast<const float4 *>(smem);
+        float4 acc = scr4[tid];
 #pragma unroll
-        for (int k = 0; k < AW; ++k) mm = fmaxf(mm, wm[k][head]);
-        float acc = 0.f;
-#pragma unroll
-        for (int k = 0; k < AW; ++k)
-            if (wm[k][head] != -INFINITY) acc += scr[k * OPART + o] * fast_exp2((wm[k][head] - mm) * c);
-        op[o] = acc;
+        for (int k = 1; k < AW; ++k) {
+            const float4 x = scr4[k * (OPART / 4) + tid];
+            acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+        }
+        reinterpret_cast<float4 *>(a.opart + ((int64_t)pair * a.nsplit + split) * OPART)[tid] = acc;
     }
     if (tid < 16) {
         float mm = -INFINITY;
@@ -488,7 +496,9 @@ __global__ void __launch_bounds__(256) dec_merge_kernel(DecArgs a) {
     const int head = tid & 15, dg = tid >> 4;          // 16 heads x 16 groups of 8 dims
     const float c = a.scale * LOG2E;
     const float *ml = a.mlpart + (int64_t)pair * a.nsplit * 32 + head * 2;
-    const float *opb = a.opart + (int64_t)pair * a.nsplit * OPART + (dg * 8) * G + head;
+    // dims 8 dg .. + 7 of this head are two 16-byte slots of a partial (see DecArgs::opart)
+    const float4 *opb = reinterpret_cast<const float4 *>(a.opart + (int64_t)pair * a.nsplit * OPART) +
+                        (dg >> 1) * 64 + (dg & 1) * 32 + head;
     float mm = -INFINITY, ll = 0.f, o[8];
 #pragma unroll
     for (int e2 = 0; e2 < 8; ++e2) o[e2] = 0.f;
@@ -499,8 +509,9 @@ __global__ void __launch_bounds__(256) dec_merge_kernel(DecArgs a) {
             const int s = min(s0 + u, a.nsplit - 1);        // past the end: re-read the last split, weight 0 below
             ms[u] = ml[s * 32];
             ls[u] = ml[s * 32 + 1];
-#pragma unroll
-            for (int e2 = 0; e2 < 8; ++e2) ov[u][e2] = opb[(int64_t)s * OPART + e2 * G];
+            const float4 lo4 = opb[(int64_t)s * (OPART / 4)], hi4 = opb[(int64_t)s * (OPART / 4) + 16];
+            ov[u][0] = lo4.x; ov[u][1] = lo4.y; ov[u][2] = lo4.z; ov[u][3] = lo4.w;
+            ov[u][4] = hi4.x; ov[u][5] = hi4.y; ov[u][6] = hi4.z; ov[u][7] = hi4.w;
         }
         float cm = mm;
 #pragma unroll
