@@ -142,14 +142,16 @@ __global__ void __launch_bounds__(256) bwd_fill_zero_kernel(float4 *p, int64_t n
 // A workgroup owns NT consecutive tokens of one sequence and KV head, one wavefront per token.  Neighbouring
 // tokens select mostly the same blocks, so the workgroup walks the union of their lists in ascending order and
 // stages each block's K, V and K^T once in LDS for every wavefront whose token selected it (bitmaps in LDS say
-// who did).  The next block's 48 KB are in flight in registers while the current one is computed.
+// who did).  Two LDS stages: the next block is written to the other stage and the one after it is in flight in
+// registers while the current one is computed.
 constexpr int DQ_MAX_BLOCKS = 4096;      // blocks per sequence the bitmaps cover (262144 tokens)
 
 template <int NT>
 __global__ void __launch_bounds__(NT * 64) bwd_dq_mfma_kernel(BwdM a, int num_tiles) {
     constexpr int NTHR = NT * 64, CH = 1024 / NTHR;          // 16-byte chunks of a 16 KB tile per thread
     constexpr int KS = D + 8, TS = kBlock + 8;                // padded rows of the K / V tiles and of the K^T tile
-    __shared__ __attribute__((aligned(16))) uint16_t k_s[kBlock * KS], v_s[kBlock * KS], kt_s[D * TS];
+    constexpr int STAGE = 2 * kBlock * KS + D * TS;           // K, V, K^T of one block
+    extern __shared__ __attribute__((aligned(16))) uint16_t dq_smem[];      // two stages
     __shared__ uint32_t ubm[DQ_MAX_BLOCKS / 32], wbm[NT][DQ_MAX_BLOCKS / 32];
     __shared__ int s_seq, s_tile;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = blockIdx.y;
@@ -237,22 +239,32 @@ __global__ void __launch_bounds__(NT * 64) bwd_dq_mfma_kernel(BwdM a, int num_ti
         }
         return pr;
     };
-    auto lstore = [&](const BlkPre &pr) {
+    auto lstore = [&](const BlkPre &pr, int buf) {
+        uint16_t *k_d = dq_smem + buf * STAGE, *v_d = k_d + kBlock * KS, *kt_d = v_d + kBlock * KS;
 #pragma unroll
         for (int r = 0; r < CH; ++r) {
             const int cc = tid + r * NTHR;
-            *reinterpret_cast<uint4 *>(k_s + (cc >> 4) * KS + (cc & 15) * 8) = pr.k[r];
-            *reinterpret_cast<uint4 *>(v_s + (cc >> 4) * KS + (cc & 15) * 8) = pr.v[r];
-            *reinterpret_cast<uint4 *>(kt_s + (cc >> 3) * TS + (cc & 7) * 8) = pr.kt[r];
+            *reinterpret_cast<uint4 *>(k_d + (cc >> 4) * KS + (cc & 15) * 8) = pr.k[r];
+            *reinterpret_cast<uint4 *>(v_d + (cc >> 4) * KS + (cc & 15) * 8) = pr.v[r];
+            *reinterpret_cast<uint4 *>(kt_d + (cc >> 3) * TS + (cc & 7) * 8) = pr.kt[r];
         }
     };
+    // Two LDS stages: while block j is consumed from one, block jn (already in registers) is written to the other
+    // and block jnn is requested from memory; one barrier per block.
     int j = next_needed(0);
-    BlkPre cur = gload(max(j, 0));
+    int jn = j >= 0 ? next_needed(j + 1) : -1;
+    int buf = 0;
+    if (j >= 0) lstore(gload(j), 0);
+    BlkPre cur = gload(jn >= 0 ? jn : max(j, 0));
+    __syncthreads();
     while (j >= 0) {
-        lstore(cur);
-        __syncthreads();
-        const int jn = next_needed(j + 1);
-        cur = gload(jn >= 0 ? jn : j);                               // (past the last block: loaded again, unused)
+        const uint16_t *k_s = dq_smem + buf * STAGE, *v_s = k_s + kBlock * KS, *kt_s = v_s + kBlock * KS;
+        int jnn = -1;
+        if (jn >= 0) {
+            lstore(cur, buf ^ 1);                                    // its last readers passed the previous barrier
+            jnn = next_needed(jn + 1);
+            cur = gload(jnn >= 0 ? jnn : jn);                        // (past the last block: loaded again, unused)
+        }
         const bool mine = active && ((wbm[w][j >> 5] >> (j & 31)) & 1u);
         if (mine) {
             const int key_limit = j == bt ? t - j * kBlock : kBlock;    // keys 0 .. limit of the block are visible
@@ -284,6 +296,8 @@ __global__ void __launch_bounds__(NT * 64) bwd_dq_mfma_kernel(BwdM a, int num_ti
         }
         __syncthreads();
         j = jn;
+        jn = jnn;
+        buf ^= 1;
     }
     if (!active) return;
     uint16_t *dq = a.dq + ((int64_t)row * a.hq + qh) * D + 4 * g;
@@ -523,7 +537,13 @@ int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const vo
     constexpr int DQ_NT = 16;
     int64_t dq_tiles = 0;
     for (int s = 0; s < L.map.batch; ++s) dq_tiles += (cu_h[s + 1] - cu_h[s] + DQ_NT - 1) / DQ_NT;
-    hipLaunchKernelGGL(bwd_dq_mfma_kernel<DQ_NT>, dim3((unsigned)dq_tiles, hkv), dim3(DQ_NT * 64), 0, L.stream, a,
+    constexpr size_t dq_lds = 2 * (size_t)(2 * kBlock * (D + 8) + D * (kBlock + 8)) * sizeof(uint16_t);     // two stages
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(bwd_dq_mfma_kernel<DQ_NT>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dq_lds) != hipSuccess) {
+        (void)hipFreeAsync(ws, L.stream);
+        return INFLLMV2_ERR_HIP;
+    }
+    hipLaunchKernelGGL(bwd_dq_mfma_kernel<DQ_NT>, dim3((unsigned)dq_tiles, hkv), dim3(DQ_NT * 64), dq_lds, L.stream, a,
                        (int)dq_tiles);
     const unsigned chunks = (unsigned)((L.max_len + DKV_CHUNK - 1) / DKV_CHUNK);
     hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(chunks, (unsigned)nblocks, hkv), dim3(256), 0, L.stream, a);
