@@ -56,6 +56,8 @@ struct BwdM {
     float *lse2, *delta;         // [T][hq]
     uint16_t *kt;                // [hkv][blocks][128][64]
     int64_t nblocks;             // 64-key blocks over all sequences
+    uint32_t *sel_bits;          // [hkv][sel_words]: per sequence and key block, one bit per token that selected it
+    int64_t sel_words;           //   (block-major, rows of ceil(len / 32) words); nullptr: not built (too large)
     // results
     uint16_t *dq;
     float *dk, *dv;
@@ -89,6 +91,51 @@ __global__ void __launch_bounds__(256) bwd_prep_kernel(BwdM a) {
         const int qh = h * G + head;
         a.delta[(int64_t)row * a.hq + qh] = dot;
         a.lse2[(int64_t)row * a.hq + qh] = a.lse[qhead_row(a.map, qh, a.hq, row)] * LOG2E;
+    }
+}
+
+// words of the selection bitmap before sequence seq
+__device__ inline int64_t sel_base(const RowMap &m, int seq) {
+    int64_t w = 0;
+    for (int s = 0; s < seq; ++s) {
+        const int len = m.cu[s + 1] - m.cu[s];
+        w += (int64_t)((len + kBlock - 1) / kBlock) * ((len + 31) / 32);
+    }
+    return w;
+}
+
+// Inverse of the block lists: bit t of row j says that token t selected key block j.  The dK/dV kernel then gets
+// the tokens of a (block, 2048-token chunk) pair with one 256-byte read instead of searching every token's list.
+// One workgroup per 256 tokens of a sequence; a wavefront reads a token's list with one coalesced load (lane =
+// list entry) and takes its 64 tokens in turn.
+__global__ void __launch_bounds__(256) bwd_sel_bits_kernel(BwdM a) {
+    __shared__ int s_seq, s_tile;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = blockIdx.y;
+    if (tid == 0) {
+        int rem = blockIdx.x, s = 0;
+        for (; s < a.map.batch; ++s) {
+            const int nt = (a.map.cu[s + 1] - a.map.cu[s] + 255) / 256;
+            if (rem < nt) break;
+            rem -= nt;
+        }
+        s_seq = s;
+        s_tile = rem;
+    }
+    __syncthreads();
+    const int seq = s_seq;
+    if (seq >= a.map.batch) return;
+    const int tok0 = a.map.cu[seq], len = a.map.cu[seq + 1] - tok0;
+    if (len < a.dense_below) return;                  // dense sequences need no lists
+    const int words = (len + 31) / 32;
+    uint32_t *rows = a.sel_bits + (int64_t)h * a.sel_words + sel_base(a.map, seq);
+    const int t_first = s_tile * 256 + w * 64, t_end = min(t_first + 64, len);
+    for (int t = t_first; t < t_end; ++t) {
+        const int bt = t / kBlock;
+        const int32_t *e = a.idx + head_row(a.map, h, tok0 + t) * a.topk_total;
+        for (int i = lane; i < a.topk_total; i += 64) {
+            const int j = e[i];
+            if (j >= 0 && j <= bt) atomicOr(rows + (int64_t)j * words + (t >> 5), 1u << (t & 31));
+        }
     }
 }
 
@@ -351,8 +398,33 @@ __global__ void __launch_bounds__(256) bwd_dkv_mfma_kernel(BwdM a) {
     if (c1 <= j * kBlock || c0 >= len) return;
     const bool dense = a.idx == nullptr || len < a.dense_below;
 
-    // ---- tokens of the chunk that selected the block, in token order (rounds of 256)
+    // ---- tokens of the chunk that selected the block, in token order
     int total = 0;
+    if (!dense && a.sel_bits != nullptr) {
+        // from the selection bitmap: the chunk is 64 words of the block's row; thread tid expands byte tid of them
+        static_assert(DKV_CHUNK == 8 * 256, "one byte of the chunk's bits per thread");
+        const int words = (len + 31) / 32;
+        const uint32_t *row = a.sel_bits + (int64_t)h * a.sel_words + sel_base(a.map, seq) + (int64_t)j * words + (c0 >> 5);
+        const int nw = (c1 - c0 + 31) >> 5;
+        const uint32_t wv = (tid >> 2) < nw ? row[tid >> 2] : 0u;
+        const uint32_t bits = (wv >> (8 * (tid & 3))) & 0xffu;
+        const int cnt = __popc(bits);
+        int incl = cnt;                                        // inclusive prefix inside the wave
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o);
+            if (lane >= o) incl += up;
+        }
+        if (lane == 63) s_wave_cnt[w] = incl;
+        __syncthreads();
+        int base = incl - cnt;
+        for (int x = 0; x < 4; ++x) {
+            if (x < w) base += s_wave_cnt[x];
+            total += s_wave_cnt[x];
+        }
+        for (uint32_t rest = bits; rest; rest &= rest - 1) s_list[base++] = c0 + 8 * tid + __ffs(rest) - 1;
+        __syncthreads();
+    } else
     for (int r0 = c0; r0 < c1; r0 += 256) {
         const int t_mine = r0 + tid;
         bool sel = t_mine < c1 && t_mine >= j * kBlock;
@@ -505,9 +577,21 @@ int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const vo
     if ((L.max_len + kBlock - 1) / kBlock > DQ_MAX_BLOCKS) return INFLLMV2_ERR_UNSUPPORTED;
     const size_t b_f = align256((size_t)rows * hq * sizeof(float));
     const size_t b_kt = align256((size_t)hkv * nblocks * D * kBlock * sizeof(uint16_t));
+    // selection bitmap (block-major): only when block lists exist and it stays moderate (it grows with len^2 / 2048
+    // bytes per sequence and KV head: 32 MB at 128K tokens); otherwise the dK/dV kernel searches the lists
+    int64_t sel_words = 0, sel_tiles = 0;
+    if (idx != nullptr)
+        for (int s = 0; s < L.map.batch; ++s) {
+            const int64_t len = cu_h[s + 1] - cu_h[s];
+            sel_words += ((len + kBlock - 1) / kBlock) * ((len + 31) / 32);
+            sel_tiles += (len + 255) / 256;
+        }
+    sel_words = (sel_words + 3) / 4 * 4;                        // zeroed 16 bytes at a time
+    const bool use_bits = idx != nullptr && sel_words > 0 && (size_t)sel_words * hkv * 4 <= ((size_t)512 << 20);
+    const size_t b_sel = use_bits ? align256((size_t)hkv * sel_words * sizeof(uint32_t)) : 0;
     keep_freed_memory_in_pool();
     char *ws = nullptr;
-    if (hipMallocAsync((void **)&ws, 2 * b_f + b_kt, L.stream) != hipSuccess) return INFLLMV2_ERR_HIP;
+    if (hipMallocAsync((void **)&ws, 2 * b_f + b_kt + b_sel, L.stream) != hipSuccess) return INFLLMV2_ERR_HIP;
     BwdM a;
     a.q = (const uint16_t *)q;
     a.k = (const uint16_t *)k;
@@ -525,6 +609,8 @@ int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const vo
     a.delta = (float *)(ws + b_f);
     a.kt = (uint16_t *)(ws + 2 * b_f);
     a.nblocks = nblocks;
+    a.sel_bits = use_bits ? (uint32_t *)(ws + 2 * b_f + b_kt) : nullptr;
+    a.sel_words = sel_words;
     a.dq = (uint16_t *)dq;
     a.dk = dk;
     a.dv = dv;
@@ -532,6 +618,12 @@ int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const vo
     const unsigned zg = (unsigned)std::min<int64_t>((n4 + 255) / 256, 8192);
     hipLaunchKernelGGL(bwd_fill_zero_kernel, dim3(zg), dim3(256), 0, L.stream, (float4 *)dk, n4);
     hipLaunchKernelGGL(bwd_fill_zero_kernel, dim3(zg), dim3(256), 0, L.stream, (float4 *)dv, n4);
+    if (use_bits) {
+        const int64_t s4 = (int64_t)hkv * sel_words / 4;
+        hipLaunchKernelGGL(bwd_fill_zero_kernel, dim3((unsigned)std::min<int64_t>((s4 + 255) / 256, 8192)), dim3(256), 0,
+                           L.stream, (float4 *)a.sel_bits, s4);
+        hipLaunchKernelGGL(bwd_sel_bits_kernel, dim3((unsigned)sel_tiles, hkv), dim3(256), 0, L.stream, a);
+    }
     hipLaunchKernelGGL(bwd_prep_kernel, dim3((unsigned)rows, hkv), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(bwd_kt_kernel, dim3((unsigned)nblocks, hkv), dim3(256), 0, L.stream, a);
     constexpr int DQ_NT = 16;
