@@ -218,7 +218,8 @@ int infllmv2_sparse_attn_fwd(const infllmv2_params *p, const void *q_d, const vo
  * bf16 data with 16 query heads per KV head and head_dim 128 runs on the matrix cores and obtains scratch for a
  * transposed copy of K, two [num_q_heads, total_tokens] float32 arrays and, when block lists are given and it stays
  * below 512 MB, a selection bitmap of num_kv_heads * sum over sequences of ceil(len / 64) * ceil(len / 32) words
- * (32 MB per KV head for one 128K-token sequence) from the stream-ordered pool (see the general rules); every
+ * (32 MB per KV head for one 128K-token sequence; the limit in MB can be set with the environment variable
+ * INFLLMV2_SEL_BITMAP_MAX_MB, 0 = never build it: slower, same results) from the stream-ordered pool (see the general rules); every
  * other head shape and dtype runs fp32 arithmetic on the vector units with one such float32 array.
  */
 int infllmv2_sparse_attn_bwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,

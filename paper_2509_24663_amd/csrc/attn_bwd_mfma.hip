@@ -23,6 +23,7 @@
 // given block are scattered, so nothing is shared between blocks -- and dq by LDS traffic and barriers.
 #include <algorithm>
 
+#include <cstdlib>
 #include "common.h"
 
 namespace ifv2 {
@@ -559,6 +560,14 @@ inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 }  // namespace
 
 // Returns INFLLMV2_ERR_UNSUPPORTED (nothing launched) for shapes this path does not cover.
+// bytes the selection bitmap may take: 512 MB unless INFLLMV2_SEL_BITMAP_MAX_MB says otherwise (0: never built)
+static size_t sel_bitmap_budget() {
+    const char *e = getenv("INFLLMV2_SEL_BITMAP_MAX_MB");
+    if (e == nullptr || *e == '\0') return (size_t)512 << 20;
+    const long mb = strtol(e, nullptr, 10);
+    return mb <= 0 ? 0 : (size_t)mb << 20;
+}
+
 int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
                          int dense_below, const void *out, const float *lse, const void *dout, void *dq, float *dk,
                          float *dv, const int32_t *cu_h) {
@@ -587,7 +596,7 @@ int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const vo
             sel_tiles += (len + 255) / 256;
         }
     sel_words = (sel_words + 3) / 4 * 4;                        // zeroed 16 bytes at a time
-    const bool use_bits = idx != nullptr && sel_words > 0 && (size_t)sel_words * hkv * 4 <= ((size_t)512 << 20);
+    const bool use_bits = idx != nullptr && sel_words > 0 && (size_t)sel_words * hkv * 4 <= sel_bitmap_budget();
     const size_t b_sel = use_bits ? align256((size_t)hkv * sel_words * sizeof(uint32_t)) : 0;
     keep_freed_memory_in_pool();
     char *ws = nullptr;

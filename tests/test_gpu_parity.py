@@ -699,3 +699,12 @@ def test_seeded_random_backward_configurations(m, oracle, case):
                      topk_total=n_init + n_local + int(rng.integers(0, 6)), dense_threshold=int(rng.choice([0, 100, 500])))
     w = synth.make_varlen(lens, 32, 2, 128, seed=9800 + case, dtype="bf16")
     _check_backward(m, oracle, w, gp, op, "bf16")
+
+
+def test_backward_without_selection_bitmap(m, oracle, monkeypatch):
+    """The dK/dV kernel normally reads which tokens selected a block from a bitmap built by a pre-pass; when that
+    would be too large it searches the tokens' lists instead.  Force the second route and check it the same way."""
+    monkeypatch.setenv("INFLLMV2_SEL_BITMAP_MAX_MB", "0")
+    w = synth.make_varlen([300, 50, 2300], 32, 2, 128, seed=331, dtype="bf16")
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=2, topk_total=6, dense_threshold=256)
+    _check_backward(m, oracle, w, gp, op, "bf16")
