@@ -210,6 +210,16 @@ template <int CTRL>
 __device__ inline unsigned dpp_move(unsigned x) {
     return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, true);
 }
+// max (MAX) or sum over the 16 lanes of a row (lanes with equal lane / 16), result in every lane: swaps inside quads,
+// then the mirror images inside 8 and 16 lanes
+template <bool MAX>
+__device__ inline float row16_all(float x) {
+    auto step = [](float v, float o) { return MAX ? fmaxf(v, o) : v + o; };
+    x = step(x, __uint_as_float(dpp_move<0xB1>(__float_as_uint(x))));       // quad_perm [1,0,3,2]
+    x = step(x, __uint_as_float(dpp_move<0x4E>(__float_as_uint(x))));       // quad_perm [2,3,0,1]
+    x = step(x, __uint_as_float(dpp_move<0x141>(__float_as_uint(x))));      // row_half_mirror
+    return step(x, __uint_as_float(dpp_move<0x140>(__float_as_uint(x))));   // row_mirror
+}
 constexpr int DPP_QUAD_SWAP1 = 0xB1;   // quad_perm [1,0,3,2]
 constexpr int DPP_QUAD_SWAP2 = 0x4E;   // quad_perm [2,3,0,1]
 constexpr int DPP_WAVE_SHR1 = 0x138;   // lane i <- lane i - 1 (lane 0 <- 0)
@@ -548,14 +558,11 @@ struct ScoreKernel {
             for (int i = 0; i < TPW; ++i)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
+                    // (lane moves inside the 16-lane row: no LDS round trips)
                     float mm = -nm[i][r], ll = l[i][r];
-#pragma unroll
-                    for (int o = 1; o < 16; o <<= 1) {
-                        const float mo = __shfl_xor(mm, o), lo = __shfl_xor(ll, o);
-                        const float mn = fmaxf(mm, mo);
-                        ll = ll * s_exp2(mm - mn) + lo * s_exp2(mo - mn);
-                        mm = mn;
-                    }
+                    const float mrow = row16_all<true>(mm);
+                    ll = row16_all<false>(ll * s_exp2(mm - mrow));
+                    mm = mrow;
                     // a row that saw no key at all (possible with the coarse keys of the LSE Approximation while
                     // fine keys are already visible) normalises everything to zero
                     lse2[i][r] = ll > 0.f ? mm + __log2f(ll) : INFINITY;
