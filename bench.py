@@ -256,7 +256,7 @@ def main() -> int:
         # to be limited by bandwidth rather than by the latency of four dependent kernels (context, not headline)
         big = bench_decode(torch, m, synth, iters=20, nsets=2, batch=128)
         decode["batch_128_same_distribution"] = {k: big[k] for k in ("ms_per_step", "tokens_per_s", "algorithmic_bytes",
-                                                                     "gbs", "frac_hbm_peak")}
+                                                                     "gbs", "frac_hbm_peak", "hip_graph_replay")}
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample of rows
     cpu = None
@@ -394,6 +394,28 @@ def bench_decode(torch, m, synth, iters: int = 40, nsets: int = 4, batch: int = 
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / iters
+    # the same steps replayed from one HIP graph (what a serving loop would do: the call allocates nothing and
+    # enqueues four kernels, and a graph removes a good part of the launch latency between them)
+    ms_graph = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for s in range(nsets):
+                m.sparse_decode(gp, *sets[s], di, workspace=ws, out=o_, lse=l_, idx=i_)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        reps = max(iters // nsets, 1)
+        e0.record()
+        for _ in range(reps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_graph = e0.elapsed_time(e1) / (reps * nsets)
+    except RuntimeError as ex:                      # capture unavailable: report the stream-launched figure only
+        sys.stderr.write(f"bench: decode graph replay skipped ({ex})\n")
     out, lse, idx = m.sparse_decode(gp, *sets[0], ctx, workspace=ws)
     nsel = (idx >= 0).sum(-1)                                                     # [B, hkv]
     last = torch.as_tensor(ctx, device="cuda")[:, None]
@@ -405,6 +427,10 @@ def bench_decode(torch, m, synth, iters: int = 40, nsets: int = 4, batch: int = 
             "ms_per_step": round(ms, 4), "tokens_per_s": round(B / (ms * 1e-3), 1),
             "algorithmic_bytes": int(byts), "gbs": round(byts / (ms * 1e-3) / 1e9, 1),
             "frac_hbm_peak": round(byts / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "hip_graph_replay": None if ms_graph is None else {
+                "ms_per_step": round(ms_graph, 4), "tokens_per_s": round(B / (ms_graph * 1e-3), 1),
+                "gbs": round(byts / (ms_graph * 1e-3) / 1e9, 1),
+                "frac_hbm_peak": round(byts / (ms_graph * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
             "note": f"attention layer only; rotates over {nsets} distinct cache sets ({nsets * 2 * B * hkv * lmax * d * 2 / 1e9:.1f} GB of K/V)"}
 
 

@@ -708,3 +708,39 @@ def test_backward_without_selection_bitmap(m, oracle, monkeypatch):
     w = synth.make_varlen([300, 50, 2300], 32, 2, 128, seed=331, dtype="bf16")
     gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=2, topk_total=6, dense_threshold=256)
     _check_backward(m, oracle, w, gp, op, "bf16")
+
+
+def test_decode_step_replays_from_a_hip_graph(m, oracle):
+    """The decode call allocates nothing and enqueues only kernels on the caller's stream, so a serving loop can
+    capture it once and replay it.  Replays (with eager work and synchronisations in between, and with the inputs
+    changed in place) must reproduce the eager results bit for bit."""
+    ctx = [3000, 641, 64, 2049]
+    w = synth.make_decode(ctx, 32, 2, 128, seed=41, dtype="bf16", max_len=3008)
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=2, topk_total=8)
+    q, kc_, vc_ = to_dev(w["q"], "bf16"), to_dev(w["k_cache"], "bf16"), to_dev(w["v_cache"], "bf16")
+    B = len(ctx)
+    kcc = torch.zeros((B, 2, oracle.num_cmp(3008, op), 128), dtype=torch.float32, device="cuda")
+    for b, L in enumerate(ctx):
+        kcb, _ = m.compress_k(gp, kc_[b, :, :L], [0, L])
+        kcc[b, :, :kcb.shape[1]] = kcb
+    di = m.DecodeInfo(ctx)
+    ws = torch.empty(m.decode_workspace_bytes(gp, B, di.max_ctx), dtype=torch.uint8, device="cuda")
+    out_e, lse_e, idx_e = m.sparse_decode(gp, q, kc_, vc_, kcc, di, workspace=ws)          # eager (also warms up)
+    torch.cuda.synchronize()
+    q_s = q.clone()
+    out_g, lse_g, idx_g = torch.empty_like(out_e), torch.empty_like(lse_e), torch.empty_like(idx_e)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        m.sparse_decode(gp, q_s, kc_, vc_, kcc, di, workspace=ws, out=out_g, lse=lse_g, idx=idx_g)
+    q2 = (q.float() * 0.5 + 0.25).to(torch.bfloat16)
+    out_e2, lse_e2, idx_e2 = m.sparse_decode(gp, q2, kc_, vc_, kcc, di, workspace=ws.clone())
+    torch.cuda.synchronize()
+    for rep in range(4):
+        src, ref = (q, (out_e, lse_e, idx_e)) if rep % 2 == 0 else (q2, (out_e2, lse_e2, idx_e2))
+        q_s.copy_(src)
+        out_g.zero_(); lse_g.zero_(); idx_g.zero_()
+        junk = torch.randn(1 << 16, device="cuda").sum()                                      # eager work in between
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, ref[0]) and torch.equal(lse_g, ref[1]) and torch.equal(idx_g, ref[2]), rep
+        assert torch.isfinite(junk)
