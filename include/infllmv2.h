@@ -21,15 +21,17 @@
  *     HIP device; pointers named *_h are host memory and are only read during the
  *     call.  The library keeps no state and never synchronises: all work is
  *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
- *     stream).  For bf16 data with 16 query heads per KV head and head_dim 128 two
- *     groups of calls obtain scratch from the device's stream-ordered memory pool
- *     (hipMallocAsync / hipFreeAsync on `stream`): the two prefill attention calls
- *     a buffer of the size of V, and infllmv2_block_scores / _pooled one of a quarter
- *     of the size of K^{C1} (a half-precision copy of the compressed keys).  On first
- *     use they raise that pool's release threshold so that later calls are served
- *     from the pool instead of the driver; nothing else is allocated.  The caller
- *     owns every buffer and keeps it alive until the
- *     stream work has finished.  Calls are thread-safe.
+ *     stream).  The library allocates nothing and reads no environment variable.  The
+ *     caller owns every buffer, including the scratch some calls need, and keeps it
+ *     alive until the stream work has finished.  Calls are thread-safe.
+ *   - Scratch: calls with a (workspace_d, workspace_bytes) pair take device memory,
+ *     256-byte aligned, of at least the size the call needs for its cu_seqlens; its
+ *     contents mean nothing before or after the call.  infllmv2_workspace_bytes
+ *     returns a sufficient size from the batch's totals alone.  A call that needs no
+ *     scratch for its parameters (the query then returns 0) accepts NULL / 0; one
+ *     that does returns INFLLMV2_ERR_INVALID_ARGUMENT for a NULL or misaligned
+ *     pointer and INFLLMV2_ERR_WORKSPACE_TOO_SMALL for too few bytes, before
+ *     anything is launched.  Two calls that run concurrently need separate scratch.
  *   - All indices are 0-based.  Token t of a sequence lies in block t / block_size.
  *     Sequences are packed along the token axis; cu_seqlens has batch+1 int32
  *     entries (cu_seqlens[0] = 0, non-decreasing) and is passed twice: as a host
@@ -102,8 +104,35 @@ int32_t infllmv2_num_cmp(const infllmv2_params *p, int32_t n);
 /* Human-readable text for a status code (static storage, never NULL). */
 const char *infllmv2_status_string(int status);
 
-/* Library version string, e.g. "infllmv2-gfx950 0.1". */
+/* Library version string, e.g. "infllmv2-gfx950 0.2". */
 const char *infllmv2_version(void);
+
+/* The calls, as `op` of infllmv2_workspace_bytes. */
+typedef enum infllmv2_op {
+    INFLLMV2_OP_COMPRESS_K = 0,
+    INFLLMV2_OP_BLOCK_SCORES = 1,
+    INFLLMV2_OP_TOPK_BLOCKS = 2,
+    INFLLMV2_OP_SPARSE_ATTN_FWD = 3,
+    INFLLMV2_OP_DENSE_ATTN_FWD = 4,
+    INFLLMV2_OP_SPARSE_DECODE = 5,
+    INFLLMV2_OP_BLOCK_SCORES_POOLED = 6,
+    INFLLMV2_OP_TOPK_POOLED = 7,
+    INFLLMV2_OP_SPARSE_ATTN_BWD = 8,        /* including the selection bitmap (see infllmv2_sparse_attn_bwd) */
+    INFLLMV2_OP_SPARSE_ATTN_BWD_MIN = 9,    /* without it */
+    INFLLMV2_OP_COMPRESS_K_APPEND = 10
+} infllmv2_op;
+
+/*
+ * Bytes of scratch that call `op` needs at most for any batch of `batch` sequences with total_tokens tokens in
+ * all and none longer than max_seqlen (for INFLLMV2_OP_SPARSE_DECODE: `batch` sequences with contexts of at most
+ * max_seqlen tokens; total_tokens is ignored).  The inputs of Alg. 1 and Appendix Alg. 2 / 3 and their outputs
+ * live in HBM buffers of the caller; so does everything the kernels keep between their launches: a transposed
+ * copy of V for the attention calls, a half-precision copy of the compressed keys for the score calls, K^T and
+ * per-row terms for the backward call, partial results for decode.  Returns 0 for calls that need none, and 0
+ * for parameters that infllmv2_* calls reject.  Host helper, no GPU needed.
+ */
+size_t infllmv2_workspace_bytes(int op, const infllmv2_params *p, int32_t batch, int64_t total_tokens,
+                                int32_t max_seqlen);
 
 /*
  * Stage 1 -- Sec. 3.3, Eq. 3:  K^{C1}_i = Mean(K[i*s_C1 : i*s_C1 + l_C1]) per sequence and KV head.
@@ -144,13 +173,14 @@ int infllmv2_compress_k_append(const infllmv2_params *p, const void *k_cache_d, 
  *   s_shared_d     device out float32 [num_kv_heads, total_tokens, row_stride]; entries i < v(t) are
  *                  written, the rest of each row is left untouched.  row_stride >= max over sequences
  *                  of nc(len) and a multiple of 4.
+ *   workspace_d    device scratch, see the general rules (INFLLMV2_OP_BLOCK_SCORES)
  *   Per-head score matrices never reach HBM; only the group sums are stored.
- *   Returns INFLLMV2_ERR_HIP if the scratch buffer (see the general rules) cannot be obtained.
  */
 int infllmv2_block_scores(const infllmv2_params *p, const void *q_d, const float *kc_d, int64_t total_c,
                           const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d,
                           const int32_t *cu_seqlens_c_d, int32_t batch,
-                          float *s_shared_d, int64_t row_stride, void *stream);
+                          float *s_shared_d, int64_t row_stride, void *workspace_d, size_t workspace_bytes,
+                          void *stream);
 
 /*
  * Stage 3 -- Sec. 3.3 Eq. 6 then Sec. 3.2 Eq. 2, per token t (block b_t = t / B) and KV head:
@@ -175,13 +205,15 @@ int infllmv2_topk_blocks(const infllmv2_params *p, const float *s_shared_d, int6
  *                  i in [s*j - pad, s*j - pad + l) clipped to [0, v(t)) for every block j <= b_t whose clipped
  *                  window is not empty, i.e. max(s*j - pad, 0) < v(t), and leaves the other entries untouched;
  *                  infllmv2_topk_pooled reads exactly those entries and takes the others as 0.
- *   Other arguments as for infllmv2_block_scores / infllmv2_topk_blocks.  Every pooling window is accepted; the
- *   paper's (l = 5, s = 4, pad 0 or 1) with the paper's head shape in bfloat16 runs on the matrix cores.
+ *   Other arguments as for infllmv2_block_scores / infllmv2_topk_blocks (scratch: INFLLMV2_OP_BLOCK_SCORES_POOLED).
+ *   Every pooling window is accepted; the paper's (l = 5, s = 4, pad 0 or 1, with s * s_C1 = B) with the paper's head
+ *   shape in bfloat16 runs on the matrix cores.
  */
 int infllmv2_block_scores_pooled(const infllmv2_params *p, const void *q_d, const float *kc_d, int64_t total_c,
                                  const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d,
                                  const int32_t *cu_seqlens_c_d, int32_t batch,
-                                 float *s_cmp_d, int64_t row_stride, void *stream);
+                                 float *s_cmp_d, int64_t row_stride, void *workspace_d, size_t workspace_bytes,
+                                 void *stream);
 int infllmv2_topk_pooled(const infllmv2_params *p, const float *s_cmp_d, int64_t row_stride,
                          const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
                          int32_t *block_idx_d, void *stream);
@@ -194,12 +226,12 @@ int infllmv2_topk_pooled(const infllmv2_params *p, const float *s_cmp_d, int64_t
  *                  numbers <= b_t or -1; as produced by infllmv2_topk_blocks)
  *   out_d          device out, dtype [total_tokens, num_q_heads, head_dim]
  *   lse_d          device out float32 [num_q_heads, total_tokens]: ln sum_u exp(scale * <q, k_u>); may be NULL
- * Returns INFLLMV2_ERR_HIP if the scratch buffer (see the general rules) cannot be obtained.
+ *   workspace_d    device scratch, see the general rules (INFLLMV2_OP_SPARSE_ATTN_FWD)
  */
 int infllmv2_sparse_attn_fwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
                              int64_t kv_tok_stride, int64_t kv_head_stride, const int32_t *block_idx_d,
                              const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
-                             void *out_d, float *lse_d, void *stream);
+                             void *out_d, float *lse_d, void *workspace_d, size_t workspace_bytes, void *stream);
 
 /*
  * Gradients of stage 4 with respect to Q, K and V for a given selection.  The paper trains through this
@@ -215,24 +247,26 @@ int infllmv2_sparse_attn_fwd(const infllmv2_params *p, const void *q_d, const vo
  *                  contributions of the num_q_heads / num_kv_heads heads of its group and of every query row
  *                  that attends to it; they are added up with the L2's float atomics, so the last bits may
  *                  differ between runs.
- * bf16 data with 16 query heads per KV head and head_dim 128 runs on the matrix cores and obtains scratch for a
- * transposed copy of K, two [num_q_heads, total_tokens] float32 arrays and, when block lists are given and it stays
- * below 512 MB, a selection bitmap of num_kv_heads * sum over sequences of ceil(len / 64) * ceil(len / 32) words
- * (32 MB per KV head for one 128K-token sequence; the limit in MB can be set with the environment variable
- * INFLLMV2_SEL_BITMAP_MAX_MB, 0 = never build it: slower, same results) from the stream-ordered pool (see the general rules); every
- * other head shape and dtype runs fp32 arithmetic on the vector units with one such float32 array.
+ *   workspace_d    device scratch, see the general rules.  INFLLMV2_OP_SPARSE_ATTN_BWD_MIN bytes are required.
+ *                  For bf16 data with 16 query heads per KV head and head_dim 128 (the matrix-core path) a
+ *                  workspace of INFLLMV2_OP_SPARSE_ATTN_BWD bytes also has room for a selection bitmap of
+ *                  num_kv_heads * sum over sequences of ceil(len / 64) * ceil(len / 32) words (32 MB per KV head for
+ *                  one 128K-token sequence), which the call then builds and which makes dK / dV faster; with less it
+ *                  searches the block lists instead: same results.
  */
 int infllmv2_sparse_attn_bwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
                              int64_t kv_tok_stride, int64_t kv_head_stride, const int32_t *block_idx_d,
                              const void *out_d, const float *lse_d, const void *dout_d,
                              const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
-                             void *dq_d, float *dk_d, float *dv_d, void *stream);
+                             void *dq_d, float *dk_d, float *dv_d, void *workspace_d, size_t workspace_bytes,
+                             void *stream);
 
-/* Dense causal GQA attention -- Eq. 1 (tile schedule of Appendix Alg. 3).  Arguments as above. */
+/* Dense causal GQA attention -- Eq. 1 (tile schedule of Appendix Alg. 3).  Arguments as for
+ * infllmv2_sparse_attn_fwd (scratch: INFLLMV2_OP_DENSE_ATTN_FWD). */
 int infllmv2_dense_attn_fwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
                             int64_t kv_tok_stride, int64_t kv_head_stride,
                             const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
-                            void *out_d, float *lse_d, void *stream);
+                            void *out_d, float *lse_d, void *workspace_d, size_t workspace_bytes, void *stream);
 
 /*
  * Decode step -- stages 2-4 for the single query row t = ctx_len-1 of every sequence (the paper
@@ -258,7 +292,8 @@ int infllmv2_sparse_decode(const infllmv2_params *p, const void *q_d, const void
                            int32_t *block_idx_out_d, void *out_d, float *lse_d,
                            void *workspace_d, size_t workspace_bytes, void *stream);
 
-/* Bytes of scratch infllmv2_sparse_decode needs for `batch` sequences of at most max_ctx_len tokens. */
+/* Bytes of scratch infllmv2_sparse_decode needs for `batch` sequences of at most max_ctx_len tokens
+ * (= infllmv2_workspace_bytes(INFLLMV2_OP_SPARSE_DECODE, p, batch, 0, max_ctx_len)). */
 size_t infllmv2_decode_workspace_bytes(const infllmv2_params *p, int32_t batch, int32_t max_ctx_len);
 
 #ifdef __cplusplus

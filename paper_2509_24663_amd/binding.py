@@ -65,13 +65,15 @@ _SIGNATURES = {
     "infllmv2_version": (ctypes.c_char_p, []),
     "infllmv2_compress_k": (ctypes.c_int, [_PP, _P, _I64, _I64, _P, _P, _I32, _P, _P, _I64, _P]),
     "infllmv2_compress_k_append": (ctypes.c_int, [_PP, _P, _I64, _I64, _I64, _P, _I64, _P, _P, _P, _P, _I32, _P]),
-    "infllmv2_block_scores": (ctypes.c_int, [_PP, _P, _P, _I64, _P, _P, _P, _I32, _P, _I64, _P]),
+    "infllmv2_workspace_bytes": (_SZ, [ctypes.c_int, _PP, _I32, _I64, _I32]),
+    "infllmv2_block_scores": (ctypes.c_int, [_PP, _P, _P, _I64, _P, _P, _P, _I32, _P, _I64, _P, _SZ, _P]),
     "infllmv2_topk_blocks": (ctypes.c_int, [_PP, _P, _I64, _P, _P, _I32, _P, _P]),
-    "infllmv2_block_scores_pooled": (ctypes.c_int, [_PP, _P, _P, _I64, _P, _P, _P, _I32, _P, _I64, _P]),
+    "infllmv2_block_scores_pooled": (ctypes.c_int, [_PP, _P, _P, _I64, _P, _P, _P, _I32, _P, _I64, _P, _SZ, _P]),
     "infllmv2_topk_pooled": (ctypes.c_int, [_PP, _P, _I64, _P, _P, _I32, _P, _P]),
-    "infllmv2_sparse_attn_fwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _P, _I32, _P, _P, _P]),
-    "infllmv2_dense_attn_fwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _I32, _P, _P, _P]),
-    "infllmv2_sparse_attn_bwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _P, _P, _P, _P, _I32, _P, _P, _P, _P]),
+    "infllmv2_sparse_attn_fwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _P, _I32, _P, _P, _P, _SZ, _P]),
+    "infllmv2_dense_attn_fwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _I32, _P, _P, _P, _SZ, _P]),
+    "infllmv2_sparse_attn_bwd": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _P, _P, _P, _P, _P, _P, _I32, _P, _P, _P,
+                                                _P, _SZ, _P]),
     "infllmv2_sparse_decode": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _I64, _P, _I64, _P, _P, _I32, _P, _P, _P,
                                               _P, _SZ, _P]),
     "infllmv2_decode_workspace_bytes": (_SZ, [_PP, _I32, _I32]),
@@ -120,6 +122,30 @@ def _ptr(t: Optional[torch.Tensor]):
 
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+# `op` of infllmv2_workspace_bytes (enum infllmv2_op)
+OP_COMPRESS_K, OP_BLOCK_SCORES, OP_TOPK_BLOCKS, OP_SPARSE_ATTN_FWD, OP_DENSE_ATTN_FWD, OP_SPARSE_DECODE = range(6)
+OP_BLOCK_SCORES_POOLED, OP_TOPK_POOLED, OP_SPARSE_ATTN_BWD, OP_SPARSE_ATTN_BWD_MIN, OP_COMPRESS_K_APPEND = range(6, 11)
+
+
+def workspace_bytes(op: int, p: Params, batch: int, total_tokens: int, max_seqlen: int) -> int:
+    """Bytes of scratch call `op` needs at most for such a batch (host helper, no GPU needed)."""
+    return int(lib().infllmv2_workspace_bytes(int(op), ctypes.byref(p), int(batch), int(total_tokens), int(max_seqlen)))
+
+
+def _workspace(op: int, p: Params, cu_h: torch.Tensor, device, given: Optional[torch.Tensor]):
+    """The caller's scratch tensor, or a new one of the size the library asks for (None when it asks for none)."""
+    if given is not None:
+        return given
+    batch = cu_h.numel() - 1
+    max_len = int((cu_h[1:] - cu_h[:-1]).max()) if batch else 0
+    need = workspace_bytes(op, p, batch, int(cu_h[-1]), max_len)
+    return torch.empty(need, dtype=torch.uint8, device=device) if need else None
+
+
+def _ws_args(ws: Optional[torch.Tensor]):
+    return (None, 0) if ws is None else (ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size())
 
 
 class SeqInfo:
@@ -181,16 +207,19 @@ def compress_k_append(p: Params, k_cache: torch.Tensor, kc_cache: torch.Tensor, 
 
 
 def block_scores(p: Params, q: torch.Tensor, kc: torch.Tensor, cu_seqlens, cu_seqlens_c: torch.Tensor,
-                 out: Optional[torch.Tensor] = None):
-    """Stage 2.  q [T, hq, d]; returns S^shared [hkv, T, row_stride] fp32 (entries beyond v(t) unspecified)."""
+                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """Stage 2.  q [T, hq, d]; returns S^shared [hkv, T, row_stride] fp32 (entries beyond v(t) unspecified).
+    workspace: a uint8 device tensor of workspace_bytes(OP_BLOCK_SCORES, ...) bytes to reuse (else made here)."""
+    assert q.is_contiguous() and kc.is_contiguous()
     cu_h, cu_d = _cu_pair(cu_seqlens)
     batch = cu_h.numel() - 1
     max_len = int((cu_h[1:] - cu_h[:-1]).max()) if batch else 0
     rs = max(4, (num_cmp(p, max_len) + 3) // 4 * 4)
     if out is None:
         out = torch.empty((p.num_kv_heads, q.shape[0], rs), dtype=torch.float32, device=q.device)
+    ws = _workspace(OP_BLOCK_SCORES, p, cu_h, q.device, workspace)
     st = lib().infllmv2_block_scores(ctypes.byref(p), _ptr(q), _ptr(kc), kc.shape[1], _ptr(cu_h), _ptr(cu_d),
-                                     _ptr(cu_seqlens_c), batch, _ptr(out), out.shape[2], _stream())
+                                     _ptr(cu_seqlens_c), batch, _ptr(out), out.shape[2], *_ws_args(ws), _stream())
     _check(st, "infllmv2_block_scores")
     return out
 
@@ -208,7 +237,7 @@ def topk_blocks(p: Params, s_shared: torch.Tensor, cu_seqlens, out: Optional[tor
 
 
 def block_scores_pooled(p: Params, q: torch.Tensor, kc: torch.Tensor, cu_seqlens, cu_seqlens_c: torch.Tensor,
-                        out: Optional[torch.Tensor] = None):
+                        out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
     """Stages 2 with the max-pooling fused.  Returns S^cmp [hkv, T, row_stride >= ceil(max len / 64)] fp32; entry j of
     a row is written iff the block's pooling window holds a visible key."""
     cu_h, cu_d = _cu_pair(cu_seqlens)
@@ -217,8 +246,11 @@ def block_scores_pooled(p: Params, q: torch.Tensor, kc: torch.Tensor, cu_seqlens
     if out is None:
         rs = max(1, (max_len + p.block_size - 1) // p.block_size)
         out = torch.empty((p.num_kv_heads, q.shape[0], rs), dtype=torch.float32, device=q.device)
+    assert q.is_contiguous() and kc.is_contiguous()
+    ws = _workspace(OP_BLOCK_SCORES_POOLED, p, cu_h, q.device, workspace)
     st = lib().infllmv2_block_scores_pooled(ctypes.byref(p), _ptr(q), _ptr(kc), kc.shape[1], _ptr(cu_h), _ptr(cu_d),
-                                            _ptr(cu_seqlens_c), batch, _ptr(out), out.shape[2], _stream())
+                                            _ptr(cu_seqlens_c), batch, _ptr(out), out.shape[2], *_ws_args(ws),
+                                            _stream())
     _check(st, "infllmv2_block_scores_pooled")
     return out
 
@@ -235,21 +267,23 @@ def topk_pooled(p: Params, s_cmp: torch.Tensor, cu_seqlens, out: Optional[torch.
     return out
 
 
-def sparse_attn_fwd(p: Params, q, k, v, block_idx, cu_seqlens, out=None, lse=None):
-    """Stage 4.  Returns (out [T, hq, d], lse [hq, T])."""
+def sparse_attn_fwd(p: Params, q, k, v, block_idx, cu_seqlens, out=None, lse=None, workspace=None):
+    """Stage 4.  Returns (out [T, hq, d], lse [hq, T]).  workspace: scratch tensor to reuse (else made here)."""
     cu_h, cu_d = _cu_pair(cu_seqlens)
     batch = cu_h.numel() - 1
     out = torch.empty_like(q) if out is None else out
     lse = torch.empty((p.num_q_heads, q.shape[0]), dtype=torch.float32, device=q.device) if lse is None else lse
     ts, hs = _kv_strides(k)
     assert _kv_strides(v) == (ts, hs)
+    assert q.is_contiguous() and out.is_contiguous() and lse.is_contiguous() and block_idx.is_contiguous()
+    ws = _workspace(OP_SPARSE_ATTN_FWD, p, cu_h, q.device, workspace)
     st = lib().infllmv2_sparse_attn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), ts, hs, _ptr(block_idx),
-                                        _ptr(cu_h), _ptr(cu_d), batch, _ptr(out), _ptr(lse), _stream())
+                                        _ptr(cu_h), _ptr(cu_d), batch, _ptr(out), _ptr(lse), *_ws_args(ws), _stream())
     _check(st, "infllmv2_sparse_attn_fwd")
     return out, lse
 
 
-def dense_attn_fwd(p: Params, q, k, v, cu_seqlens, out=None, lse=None):
+def dense_attn_fwd(p: Params, q, k, v, cu_seqlens, out=None, lse=None, workspace=None):
     """Dense causal GQA attention.  Returns (out [T, hq, d], lse [hq, T])."""
     cu_h, cu_d = _cu_pair(cu_seqlens)
     batch = cu_h.numel() - 1
@@ -257,15 +291,19 @@ def dense_attn_fwd(p: Params, q, k, v, cu_seqlens, out=None, lse=None):
     lse = torch.empty((p.num_q_heads, q.shape[0]), dtype=torch.float32, device=q.device) if lse is None else lse
     ts, hs = _kv_strides(k)
     assert _kv_strides(v) == (ts, hs)
+    assert q.is_contiguous() and out.is_contiguous() and lse.is_contiguous()
+    ws = _workspace(OP_DENSE_ATTN_FWD, p, cu_h, q.device, workspace)
     st = lib().infllmv2_dense_attn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), ts, hs, _ptr(cu_h), _ptr(cu_d),
-                                       batch, _ptr(out), _ptr(lse), _stream())
+                                       batch, _ptr(out), _ptr(lse), *_ws_args(ws), _stream())
     _check(st, "infllmv2_dense_attn_fwd")
     return out, lse
 
 
-def sparse_attn_bwd(p: Params, q, k, v, block_idx, out, lse, dout, cu_seqlens, dq=None, dk=None, dv=None):
+def sparse_attn_bwd(p: Params, q, k, v, block_idx, out, lse, dout, cu_seqlens, dq=None, dk=None, dv=None,
+                    workspace=None, sel_bitmap_max_bytes: int = 512 << 20):
     """Gradients of stage 4 for a given selection (block_idx None: dense).  Returns (dq like q, dk, dv float32
-    [hkv, T, d])."""
+    [hkv, T, d]).  workspace: scratch tensor to reuse; when it is made here it includes room for the selection
+    bitmap unless that would take more than sel_bitmap_max_bytes (0: never)."""
     cu_h, cu_d = _cu_pair(cu_seqlens)
     batch = cu_h.numel() - 1
     ts, hs = _kv_strides(k)
@@ -275,9 +313,16 @@ def sparse_attn_bwd(p: Params, q, k, v, block_idx, out, lse, dout, cu_seqlens, d
     dk = torch.empty((p.num_kv_heads, T, p.head_dim), dtype=torch.float32, device=q.device) if dk is None else dk
     dv = torch.empty((p.num_kv_heads, T, p.head_dim), dtype=torch.float32, device=q.device) if dv is None else dv
     assert dout.is_contiguous() and out.is_contiguous() and dq.is_contiguous() and dk.is_contiguous() and dv.is_contiguous()
+    assert q.is_contiguous() and lse.is_contiguous()
+    if workspace is None:
+        max_len = int((cu_h[1:] - cu_h[:-1]).max()) if batch else 0
+        full = workspace_bytes(OP_SPARSE_ATTN_BWD, p, batch, T, max_len)
+        least = workspace_bytes(OP_SPARSE_ATTN_BWD_MIN, p, batch, T, max_len)
+        need = full if block_idx is not None and full - least <= sel_bitmap_max_bytes else least
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device) if need else None
     st = lib().infllmv2_sparse_attn_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), ts, hs, _ptr(block_idx), _ptr(out),
                                         _ptr(lse), _ptr(dout), _ptr(cu_h), _ptr(cu_d), batch, _ptr(dq), _ptr(dk),
-                                        _ptr(dv), _stream())
+                                        _ptr(dv), *_ws_args(workspace), _stream())
     _check(st, "infllmv2_sparse_attn_bwd")
     return dq, dk, dv
 
@@ -327,13 +372,20 @@ def sparse_prefill(p: Params, q, k, v, cu_seqlens, buffers: Optional[dict] = Non
     b = buffers or {}
     si = cu_seqlens if isinstance(cu_seqlens, SeqInfo) else SeqInfo(cu_seqlens)
     kc, cu_c = compress_k(p, k, si, out=(b["kc"], b["cu_seqlens_c"]) if b else None)
+    ws_scores = b.get("ws_scores")
+    if ws_scores is None:
+        ws_scores = _workspace(OP_BLOCK_SCORES_POOLED if fused_pool else OP_BLOCK_SCORES, p, si.cu_h, q.device, None)
     if fused_pool:
-        sc = block_scores_pooled(p, q, kc, si, cu_c, out=b.get("s_cmp"))
+        sc = block_scores_pooled(p, q, kc, si, cu_c, out=b.get("s_cmp"), workspace=ws_scores)
         idx = topk_pooled(p, sc, si, out=b.get("block_idx"))
         scores = dict(s_cmp=sc)
     else:
-        sh = block_scores(p, q, kc, si, cu_c, out=b.get("s_shared"))
+        sh = block_scores(p, q, kc, si, cu_c, out=b.get("s_shared"), workspace=ws_scores)
         idx = topk_blocks(p, sh, si, out=b.get("block_idx"))
         scores = dict(s_shared=sh)
-    out, lse = sparse_attn_fwd(p, q, k, v, idx, si, out=b.get("out"), lse=b.get("lse"))
-    return dict(out=out, lse=lse, block_idx=idx, kc=kc, cu_seqlens_c=cu_c, **scores)
+    ws_attn = b.get("ws_attn")
+    if ws_attn is None:
+        ws_attn = _workspace(OP_SPARSE_ATTN_FWD, p, si.cu_h, q.device, None)
+    out, lse = sparse_attn_fwd(p, q, k, v, idx, si, out=b.get("out"), lse=b.get("lse"), workspace=ws_attn)
+    return dict(out=out, lse=lse, block_idx=idx, kc=kc, cu_seqlens_c=cu_c, ws_attn=ws_attn, ws_scores=ws_scores,
+                **scores)

@@ -55,6 +55,13 @@ static int check_cu(const int32_t *cu_h, const int32_t *cu_d, int32_t batch, int
     return INFLLMV2_OK;
 }
 
+// workspace arguments: 256-byte aligned when present; need == 0 accepts anything (also NULL)
+static int check_ws(const void *ws, size_t ws_bytes, size_t need) {
+    if (need == 0) return INFLLMV2_OK;
+    if (ws == nullptr || ((uintptr_t)ws & 255) != 0) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    return ws_bytes < need ? INFLLMV2_ERR_WORKSPACE_TOO_SMALL : INFLLMV2_OK;
+}
+
 static RowMap prefill_map(const infllmv2_params *p, const int32_t *cu_d, const int32_t *cu_c_d, int batch,
                           int64_t total, int64_t tok_stride, int64_t head_stride, int64_t kc_total_c) {
     RowMap m;
@@ -90,7 +97,7 @@ const char *infllmv2_status_string(int status) {
     }
 }
 
-const char *infllmv2_version(void) { return "infllmv2-gfx950 0.1"; }
+const char *infllmv2_version(void) { return "infllmv2-gfx950 0.2"; }
 
 int infllmv2_compress_k(const infllmv2_params *p, const void *k_d, int64_t kv_tok_stride, int64_t kv_head_stride,
                         const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
@@ -112,7 +119,7 @@ int infllmv2_compress_k(const infllmv2_params *p, const void *k_d, int64_t kv_to
     st = launch_cu_c(p, cu_seqlens_d, batch, cu_seqlens_c_d, s);
     if (st) return st;
     Launch L{p, prefill_map(p, cu_seqlens_d, cu_seqlens_c_d, batch, total, kv_tok_stride, kv_head_stride, total_c), s,
-             max_len};
+             max_len, nullptr, 0};
     return launch_compress_k(L, k_d, kc_d, need);
 }
 
@@ -144,7 +151,8 @@ int infllmv2_compress_k_append(const infllmv2_params *p, const void *k_cache_d, 
 int infllmv2_block_scores(const infllmv2_params *p, const void *q_d, const float *kc_d, int64_t total_c,
                           const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d,
                           const int32_t *cu_seqlens_c_d, int32_t batch,
-                          float *s_shared_d, int64_t row_stride, void *stream) {
+                          float *s_shared_d, int64_t row_stride, void *workspace_d, size_t workspace_bytes,
+                          void *stream) {
     int st = check_params(p);
     if (st) return st;
     int64_t total;
@@ -156,8 +164,10 @@ int infllmv2_block_scores(const infllmv2_params *p, const void *q_d, const float
         return INFLLMV2_ERR_INVALID_ARGUMENT;
     if (row_stride < num_cmp(max_len, p->cmp_len, p->cmp_stride) || row_stride % 4 != 0 || row_stride < 4)
         return INFLLMV2_ERR_INVALID_ARGUMENT;
+    st = check_ws(workspace_d, workspace_bytes, scores_ws_bytes(p, exact_totals(p, cu_seqlens_h, batch), false));
+    if (st) return st;
     Launch L{p, prefill_map(p, cu_seqlens_d, cu_seqlens_c_d, batch, total, 0, 0, total_c), (hipStream_t)stream,
-             max_len};
+             max_len, workspace_d, workspace_bytes};
     return launch_block_scores(L, q_d, kc_d, s_shared_d, row_stride, cu_seqlens_h, false);
 }
 
@@ -173,7 +183,7 @@ int infllmv2_topk_blocks(const infllmv2_params *p, const float *s_shared_d, int6
     if (total == 0) return INFLLMV2_OK;
     if (s_shared_d == nullptr || block_idx_d == nullptr) return INFLLMV2_ERR_INVALID_ARGUMENT;
     if (row_stride < num_cmp(max_len, p->cmp_len, p->cmp_stride) || row_stride < 4) return INFLLMV2_ERR_INVALID_ARGUMENT;
-    Launch L{p, prefill_map(p, cu_seqlens_d, nullptr, batch, total, 0, 0, 0), (hipStream_t)stream, max_len};
+    Launch L{p, prefill_map(p, cu_seqlens_d, nullptr, batch, total, 0, 0, 0), (hipStream_t)stream, max_len, nullptr, 0};
     return launch_topk(L, s_shared_d, row_stride, block_idx_d, false);
 }
 
@@ -183,7 +193,8 @@ static inline int num_blocks(int n) { return (n + kBlock - 1) / kBlock; }
 int infllmv2_block_scores_pooled(const infllmv2_params *p, const void *q_d, const float *kc_d, int64_t total_c,
                                  const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d,
                                  const int32_t *cu_seqlens_c_d, int32_t batch,
-                                 float *s_cmp_d, int64_t row_stride, void *stream) {
+                                 float *s_cmp_d, int64_t row_stride, void *workspace_d, size_t workspace_bytes,
+                                 void *stream) {
     int st = check_params(p);
     if (st) return st;
     int64_t total;
@@ -194,8 +205,10 @@ int infllmv2_block_scores_pooled(const infllmv2_params *p, const void *q_d, cons
     if (q_d == nullptr || kc_d == nullptr || cu_seqlens_c_d == nullptr || s_cmp_d == nullptr)
         return INFLLMV2_ERR_INVALID_ARGUMENT;
     if (row_stride < num_blocks(max_len)) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    st = check_ws(workspace_d, workspace_bytes, scores_ws_bytes(p, exact_totals(p, cu_seqlens_h, batch), true));
+    if (st) return st;
     Launch L{p, prefill_map(p, cu_seqlens_d, cu_seqlens_c_d, batch, total, 0, 0, total_c), (hipStream_t)stream,
-             max_len};
+             max_len, workspace_d, workspace_bytes};
     return launch_block_scores(L, q_d, kc_d, s_cmp_d, row_stride, cu_seqlens_h, true);
 }
 
@@ -211,14 +224,14 @@ int infllmv2_topk_pooled(const infllmv2_params *p, const float *s_cmp_d, int64_t
     if (total == 0) return INFLLMV2_OK;
     if (s_cmp_d == nullptr || block_idx_d == nullptr) return INFLLMV2_ERR_INVALID_ARGUMENT;
     if (row_stride < num_blocks(max_len)) return INFLLMV2_ERR_INVALID_ARGUMENT;
-    Launch L{p, prefill_map(p, cu_seqlens_d, nullptr, batch, total, 0, 0, 0), (hipStream_t)stream, max_len};
+    Launch L{p, prefill_map(p, cu_seqlens_d, nullptr, batch, total, 0, 0, 0), (hipStream_t)stream, max_len, nullptr, 0};
     return launch_topk(L, s_cmp_d, row_stride, block_idx_d, true);
 }
 
 static int attn_common(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
                        int64_t kv_tok_stride, int64_t kv_head_stride, const int32_t *block_idx_d, bool sparse,
                        const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch, void *out_d,
-                       float *lse_d, void *stream) {
+                       float *lse_d, void *workspace_d, size_t workspace_bytes, void *stream) {
     int st = check_params(p);
     if (st) return st;
     int64_t total;
@@ -229,8 +242,10 @@ static int attn_common(const infllmv2_params *p, const void *q_d, const void *k_
     if (q_d == nullptr || k_d == nullptr || v_d == nullptr || out_d == nullptr) return INFLLMV2_ERR_INVALID_ARGUMENT;
     if (sparse && block_idx_d == nullptr) return INFLLMV2_ERR_INVALID_ARGUMENT;
     if (kv_tok_stride < p->head_dim || kv_head_stride < p->head_dim) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    st = check_ws(workspace_d, workspace_bytes, attn_fwd_ws_bytes(p, exact_totals(p, cu_seqlens_h, batch)));
+    if (st) return st;
     Launch L{p, prefill_map(p, cu_seqlens_d, nullptr, batch, total, kv_tok_stride, kv_head_stride, 0),
-             (hipStream_t)stream, max_len};
+             (hipStream_t)stream, max_len, workspace_d, workspace_bytes};
     return launch_attn(L, q_d, k_d, v_d, sparse ? block_idx_d : nullptr, sparse ? p->dense_threshold : 0, out_d,
                        lse_d, cu_seqlens_h);
 }
@@ -238,24 +253,25 @@ static int attn_common(const infllmv2_params *p, const void *q_d, const void *k_
 int infllmv2_sparse_attn_fwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
                              int64_t kv_tok_stride, int64_t kv_head_stride, const int32_t *block_idx_d,
                              const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
-                             void *out_d, float *lse_d, void *stream) {
+                             void *out_d, float *lse_d, void *workspace_d, size_t workspace_bytes, void *stream) {
     return attn_common(p, q_d, k_d, v_d, kv_tok_stride, kv_head_stride, block_idx_d, true, cu_seqlens_h,
-                       cu_seqlens_d, batch, out_d, lse_d, stream);
+                       cu_seqlens_d, batch, out_d, lse_d, workspace_d, workspace_bytes, stream);
 }
 
 int infllmv2_dense_attn_fwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
                             int64_t kv_tok_stride, int64_t kv_head_stride,
                             const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
-                            void *out_d, float *lse_d, void *stream) {
+                            void *out_d, float *lse_d, void *workspace_d, size_t workspace_bytes, void *stream) {
     return attn_common(p, q_d, k_d, v_d, kv_tok_stride, kv_head_stride, nullptr, false, cu_seqlens_h,
-                       cu_seqlens_d, batch, out_d, lse_d, stream);
+                       cu_seqlens_d, batch, out_d, lse_d, workspace_d, workspace_bytes, stream);
 }
 
 int infllmv2_sparse_attn_bwd(const infllmv2_params *p, const void *q_d, const void *k_d, const void *v_d,
                              int64_t kv_tok_stride, int64_t kv_head_stride, const int32_t *block_idx_d,
                              const void *out_d, const float *lse_d, const void *dout_d,
                              const int32_t *cu_seqlens_h, const int32_t *cu_seqlens_d, int32_t batch,
-                             void *dq_d, float *dk_d, float *dv_d, void *stream) {
+                             void *dq_d, float *dk_d, float *dv_d, void *workspace_d, size_t workspace_bytes,
+                             void *stream) {
     int st = check_params(p);
     if (st) return st;
     int64_t total;
@@ -268,13 +284,32 @@ int infllmv2_sparse_attn_bwd(const infllmv2_params *p, const void *q_d, const vo
         return INFLLMV2_ERR_INVALID_ARGUMENT;
     if (kv_tok_stride < p->head_dim || kv_head_stride < p->head_dim) return INFLLMV2_ERR_INVALID_ARGUMENT;
     if ((((uintptr_t)dk_d | (uintptr_t)dv_d) & 15) != 0) return INFLLMV2_ERR_INVALID_ARGUMENT;
+    st = check_ws(workspace_d, workspace_bytes, attn_bwd_ws_bytes(p, exact_totals(p, cu_seqlens_h, batch), false));
+    if (st) return st;
     Launch L{p, prefill_map(p, cu_seqlens_d, nullptr, batch, total, kv_tok_stride, kv_head_stride, 0),
-             (hipStream_t)stream, max_len};
+             (hipStream_t)stream, max_len, workspace_d, workspace_bytes};
     return launch_attn_bwd(L, q_d, k_d, v_d, block_idx_d, block_idx_d ? p->dense_threshold : 0, out_d, lse_d, dout_d,
                            dq_d, dk_d, dv_d, cu_seqlens_h);
 }
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+size_t infllmv2_workspace_bytes(int op, const infllmv2_params *p, int32_t batch, int64_t total_tokens,
+                                int32_t max_seqlen) {
+    if (check_params(p) != INFLLMV2_OK || batch < 0 || total_tokens < 0 || max_seqlen < 0) return 0;
+    if (op == INFLLMV2_OP_SPARSE_DECODE) return infllmv2_decode_workspace_bytes(p, batch, max_seqlen);
+    if (total_tokens >= (1ll << 31)) return 0;
+    const BatchTotals t = bound_totals(p, batch, total_tokens, max_seqlen);
+    switch (op) {
+        case INFLLMV2_OP_BLOCK_SCORES: return scores_ws_bytes(p, t, false);
+        case INFLLMV2_OP_BLOCK_SCORES_POOLED: return scores_ws_bytes(p, t, true);
+        case INFLLMV2_OP_SPARSE_ATTN_FWD:
+        case INFLLMV2_OP_DENSE_ATTN_FWD: return attn_fwd_ws_bytes(p, t);
+        case INFLLMV2_OP_SPARSE_ATTN_BWD: return attn_bwd_ws_bytes(p, t, true);
+        case INFLLMV2_OP_SPARSE_ATTN_BWD_MIN: return attn_bwd_ws_bytes(p, t, false);
+        default: return 0;      // compress_k, compress_k_append, top-k: no scratch
+    }
+}
 
 size_t infllmv2_decode_workspace_bytes(const infllmv2_params *p, int32_t batch, int32_t max_ctx_len) {
     if (check_params(p) != INFLLMV2_OK || batch < 0 || max_ctx_len < 0) return 0;
@@ -339,7 +374,7 @@ int infllmv2_sparse_decode(const infllmv2_params *p, const void *q_d, const void
     m.kv_batch_stride = kv_batch_stride;
     m.kc_total_c = 0;
     m.kc_head_stride = kc_head_stride;
-    Launch L{p, m, (hipStream_t)stream, max_ctx};
+    Launch L{p, m, (hipStream_t)stream, max_ctx, nullptr, 0};
     st = launch_block_scores(L, q_d, kc_cache_d, scores, (int64_t)rs, nullptr, false);
     if (st) return st;
     st = launch_topk(L, scores, (int64_t)rs, idx, false);
@@ -350,6 +385,31 @@ int infllmv2_sparse_decode(const infllmv2_params *p, const void *q_d, const void
 }  // extern "C"
 
 namespace ifv2 {
+BatchTotals exact_totals(const infllmv2_params *p, const int32_t *cu_h, int batch) {
+    BatchTotals t{0, 0, 0, 0, 0};
+    for (int s = 0; s < batch; ++s) {
+        const int64_t len = cu_h[s + 1] - cu_h[s];
+        t.rows += len;
+        t.blocks += (len + kBlock - 1) / kBlock;
+        t.kt_fine += (num_cmp((int)len, p->cmp_len, p->cmp_stride) + kBlock - 1) / kBlock;
+        t.kt_coarse += (num_cmp((int)len, 4 * p->cmp_len, 4 * p->cmp_stride) + kBlock - 1) / kBlock;
+        t.sel_words += ((len + kBlock - 1) / kBlock) * ((len + 31) / 32);
+    }
+    return t;
+}
+
+// every total of exact_totals is at most this for any batch of `batch` sequences, total_tokens tokens, none
+// longer than max_seqlen (nc(n) <= n / s_C1 because l_C1 >= s_C1)
+BatchTotals bound_totals(const infllmv2_params *p, int batch, int64_t total_tokens, int32_t max_seqlen) {
+    BatchTotals t;
+    t.rows = total_tokens;
+    t.blocks = total_tokens / kBlock + batch;
+    t.kt_fine = total_tokens / ((int64_t)p->cmp_stride * kBlock) + batch;
+    t.kt_coarse = total_tokens / ((int64_t)4 * p->cmp_stride * kBlock) + batch;
+    t.sel_words = t.blocks * ((int64_t)max_seqlen / 32 + 1);
+    return t;
+}
+
 int launch_attn(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
                 int dense_below, void *out, float *lse, const int32_t *cu_h) {
     const bool aligned = (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) == 0 &&

@@ -265,9 +265,8 @@ int launch_t(const Launch &L, BwdArgs<T> a, const int32_t *cu_h) {
     for (int s = 0; s < L.map.batch; ++s) nblocks += (cu_h[s + 1] - cu_h[s] + kBlock - 1) / kBlock;
     const int hkv = L.p->num_kv_heads;
     if (nblocks > 65535 || hkv > 65535) return INFLLMV2_ERR_UNSUPPORTED;      // grid.y / grid.z limits
-    keep_freed_memory_in_pool();
-    void *ws = nullptr;
-    if (hipMallocAsync(&ws, (size_t)rows * a.hq * sizeof(float), L.stream) != hipSuccess) return INFLLMV2_ERR_HIP;
+    void *ws = L.ws;         // <dO, O> per (row, head)
+    if (ws == nullptr || L.ws_bytes < (size_t)rows * a.hq * sizeof(float)) return INFLLMV2_ERR_WORKSPACE_TOO_SMALL;
     a.delta = (float *)ws;
     const int64_t n4 = rows * hkv * D / 4;
     hipLaunchKernelGGL(bwd_zero_kernel, dim3((unsigned)std::min<int64_t>((n4 + 255) / 256, 4096)), dim3(256), 0, L.stream,
@@ -286,7 +285,6 @@ int launch_t(const Launch &L, BwdArgs<T> a, const int32_t *cu_h) {
         hipLaunchKernelGGL(kern, dim3(chunks, (unsigned)nblocks, hkv), dim3(256), lds, L.stream, a, (int)nblocks);
         e = hipGetLastError();
     }
-    (void)hipFreeAsync(ws, L.stream);
     return hip_status(e);
 }
 
@@ -304,6 +302,15 @@ int launch_d(const Launch &L, const void *q, const void *k, const void *v, const
 int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
                          int dense_below, const void *out, const float *lse, const void *dout, void *dq, float *dk,
                          float *dv, const int32_t *cu_h);
+
+bool bwd_mfma_params(const infllmv2_params *p);
+size_t bwd_mfma_ws_bytes(const infllmv2_params *p, const BatchTotals &t, bool with_bitmap);
+
+size_t attn_bwd_ws_bytes(const infllmv2_params *p, const BatchTotals &t, bool with_bitmap) {
+    // (a call whose pointers or strides rule out the matrix-core path needs less: the bound still holds)
+    if (bwd_mfma_params(p)) return bwd_mfma_ws_bytes(p, t, with_bitmap);
+    return align256((size_t)t.rows * p->num_q_heads * sizeof(float));
+}
 
 int launch_attn_bwd(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx, int dense_below,
                     const void *out, const float *lse, const void *dout, void *dq, float *dk, float *dv,

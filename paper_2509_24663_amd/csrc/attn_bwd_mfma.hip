@@ -555,25 +555,27 @@ __global__ void __launch_bounds__(256) bwd_dkv_mfma_kernel(BwdM a) {
     }
 }
 
-inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
-
 }  // namespace
 
-// Returns INFLLMV2_ERR_UNSUPPORTED (nothing launched) for shapes this path does not cover.
-// bytes the selection bitmap may take: 512 MB unless INFLLMV2_SEL_BITMAP_MAX_MB says otherwise (0: never built)
-static size_t sel_bitmap_budget() {
-    const char *e = getenv("INFLLMV2_SEL_BITMAP_MAX_MB");
-    if (e == nullptr || *e == '\0') return (size_t)512 << 20;
-    const long mb = strtol(e, nullptr, 10);
-    return mb <= 0 ? 0 : (size_t)mb << 20;
+bool bwd_mfma_params(const infllmv2_params *p) {
+    return p->dtype == INFLLMV2_BF16 && p->head_dim == D && p->num_q_heads / p->num_kv_heads == G;
 }
 
+// two [hq, rows] float arrays (lse in powers of two, <dO, O>), K^T tiles, and optionally the selection bitmap
+size_t bwd_mfma_ws_bytes(const infllmv2_params *p, const BatchTotals &t, bool with_bitmap) {
+    const size_t b_f = align256((size_t)t.rows * p->num_q_heads * sizeof(float));
+    const size_t b_kt = align256((size_t)p->num_kv_heads * t.blocks * D * kBlock * sizeof(uint16_t));
+    const size_t words = (size_t)(t.sel_words + 3) / 4 * 4;
+    const size_t b_sel = with_bitmap ? align256((size_t)p->num_kv_heads * words * sizeof(uint32_t)) : 0;
+    return 2 * b_f + b_kt + b_sel;
+}
+
+// Returns INFLLMV2_ERR_UNSUPPORTED (nothing launched) for shapes this path does not cover.
 int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
                          int dense_below, const void *out, const float *lse, const void *dout, void *dq, float *dk,
                          float *dv, const int32_t *cu_h) {
     const infllmv2_params *p = L.p;
-    if (p->dtype != INFLLMV2_BF16 || p->head_dim != D || p->num_q_heads / p->num_kv_heads != G)
-        return INFLLMV2_ERR_UNSUPPORTED;
+    if (!bwd_mfma_params(p)) return INFLLMV2_ERR_UNSUPPORTED;
     if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out | (uintptr_t)dout | (uintptr_t)dq) & 15) != 0 ||
         L.map.kv_tok_stride % 8 != 0 || L.map.kv_head_stride % 8 != 0)
         return INFLLMV2_ERR_UNSUPPORTED;
@@ -596,11 +598,11 @@ int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const vo
             sel_tiles += (len + 255) / 256;
         }
     sel_words = (sel_words + 3) / 4 * 4;                        // zeroed 16 bytes at a time
-    const bool use_bits = idx != nullptr && sel_words > 0 && (size_t)sel_words * hkv * 4 <= sel_bitmap_budget();
-    const size_t b_sel = use_bits ? align256((size_t)hkv * sel_words * sizeof(uint32_t)) : 0;
-    keep_freed_memory_in_pool();
-    char *ws = nullptr;
-    if (hipMallocAsync((void **)&ws, 2 * b_f + b_kt + b_sel, L.stream) != hipSuccess) return INFLLMV2_ERR_HIP;
+    // the bitmap is built when the caller's workspace has room for it
+    const size_t b_sel_full = align256((size_t)hkv * sel_words * sizeof(uint32_t));
+    char *ws = (char *)L.ws;
+    if (ws == nullptr || L.ws_bytes < 2 * b_f + b_kt) return INFLLMV2_ERR_WORKSPACE_TOO_SMALL;
+    const bool use_bits = idx != nullptr && sel_words > 0 && L.ws_bytes >= 2 * b_f + b_kt + b_sel_full;
     BwdM a;
     a.q = (const uint16_t *)q;
     a.k = (const uint16_t *)k;
@@ -640,17 +642,13 @@ int launch_attn_bwd_mfma(const Launch &L, const void *q, const void *k, const vo
     for (int s = 0; s < L.map.batch; ++s) dq_tiles += (cu_h[s + 1] - cu_h[s] + DQ_NT - 1) / DQ_NT;
     constexpr size_t dq_lds = 2 * (size_t)(2 * kBlock * (D + 8) + D * (kBlock + 8)) * sizeof(uint16_t);     // two stages
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(bwd_dq_mfma_kernel<DQ_NT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dq_lds) != hipSuccess) {
-        (void)hipFreeAsync(ws, L.stream);
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dq_lds) != hipSuccess)
         return INFLLMV2_ERR_HIP;
-    }
     hipLaunchKernelGGL(bwd_dq_mfma_kernel<DQ_NT>, dim3((unsigned)dq_tiles, hkv), dim3(DQ_NT * 64), dq_lds, L.stream, a,
                        (int)dq_tiles);
     const unsigned chunks = (unsigned)((L.max_len + DKV_CHUNK - 1) / DKV_CHUNK);
     hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(chunks, (unsigned)nblocks, hkv), dim3(256), 0, L.stream, a);
-    const hipError_t e = hipGetLastError();
-    (void)hipFreeAsync(ws, L.stream);
-    return hip_status(e);
+    return hip_status(hipGetLastError());
 }
 
 }  // namespace ifv2

@@ -9,7 +9,7 @@
 // per-token softmax attention of Alg. 2.
 //
 // Data movement: a small pre-pass writes V^T, one [128 dims][64 keys] tile per block (zero-padded past the end
-// of a sequence), into stream-ordered scratch.  K blocks and V^T tiles then go from global memory straight
+// of a sequence), into the caller's workspace.  K blocks and V^T tiles then go from global memory straight
 // into LDS (global_load_lds, 16 bytes per lane, no register staging) with the 16-byte chunks of a row
 // XOR-swizzled so that the 16-byte operand reads below are spread over all banks.
 //
@@ -54,7 +54,7 @@ struct TileKernel {
     static constexpr int NTHR = NW * 64;
     static constexpr int NSTAGE = 2 * SLOTS;        // double buffering of an interval's blocks
     static constexpr int PPW = 32 / NW;             // one-KB load pieces per wave and block
-    static constexpr int NONE = -1;
+    static constexpr int NONE = 0xffff;            // no block (block numbers are kept in 16 bits)
     static_assert(32 % NW == 0, "32 one-KB load instructions are dealt round-robin to the waves");
     static_assert(SLOTS == 1 || SLOTS == 2, "one or two entries per interval");
 
@@ -185,19 +185,24 @@ struct TileKernel {
         // interval covers two consecutive entries of the union, so that a SIMD usually has two or more units to
         // overlap between one pair of barriers; the tile's own block (the last entry) is alone in the last interval.
         const int ne = dense ? nblk : __builtin_amdgcn_readfirstlane(s_ne);
-        auto interval = [&](int i) -> int4 {
-            if (dense) return make_int4(i, (int)full, NONE, 0);
+        // (packed into two words -- block numbers and consumer masks in 16 bits each -- because the record of the next
+        // interval waits in vector registers while a unit runs)
+        auto pack = [](int j0, int mk0, int j1, int mk1) -> int2 {
+            return make_int2((j0 & 0xffff) | (j1 << 16), (mk0 & 0xffff) | (mk1 << 16));
+        };
+        auto interval = [&](int i) -> int2 {
+            if (dense) return pack(i, (int)full, NONE, 0);
             if (SLOTS == 1) {
                 const int2 r = rec[i];
-                return make_int4(r.x, r.y, NONE, 0);
+                return pack(r.x, r.y, NONE, 0);
             }
             if (i == ni - 1) {
                 const int2 r = rec[ne - 1];
-                return make_int4(r.x, r.y, NONE, 0);
+                return pack(r.x, r.y, NONE, 0);
             }
             const int2 r0 = rec[2 * i];
             const int2 r1 = 2 * i + 1 < ne - 1 ? rec[2 * i + 1] : make_int2(NONE, 0);
-            return make_int4(r0.x, r0.y, r1.x, r1.y);
+            return pack(r0.x, r0.y, r1.x, r1.y);
         };
 
         // ---- loads: the 32 one-KB pieces of a block (16 of the K tile, 16 of the V^T tile) are dealt round-robin
@@ -207,18 +212,17 @@ struct TileKernel {
         // V^T copy is zero-padded instead.
         const uint64_t blk_bytes = (uint64_t)a.map.kv_tok_stride * (kBlock * sizeof(uint16_t));
         const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(stages));
-        uint32_t loff[PPW], loff_own[PPW];
+        const int own_rows = len - bt * kBlock;          // rows of the tile's own block that exist (1..64 counts)
+        uint32_t loff[PPW];
 #pragma unroll
         for (int p = 0; p < PPW; ++p) {
             const int qi = w + p * NW;
             if (qi < 16) {
                 int row, chunk;
                 k_piece_src(qi, lane, row, chunk);
-                const int row_own = min(row, len - 1 - bt * kBlock);
                 loff[p] = (uint32_t)(row * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
-                loff_own[p] = (uint32_t)(row_own * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
             } else {
-                loff[p] = loff_own[p] = vt_piece_src_bytes(qi - 16, lane);
+                loff[p] = vt_piece_src_bytes(qi - 16, lane);
             }
         }
         auto issue_block = [&](int j, int stage_idx) {
@@ -228,17 +232,24 @@ struct TileKernel {
                 const char *base = qi < 16 ? reinterpret_cast<const char *>(kb) + (uint64_t)j * blk_bytes
                                            : reinterpret_cast<const char *>(vtb) + (uint64_t)j * (VT_TILE_ELEMS * sizeof(uint16_t));
                 const uint32_t dst = lds0 + (uint32_t)(stage_idx * STAGE_ELEMS + (qi < 16 ? 0 : TILE_ELEMS) + (qi & 15) * 512) * 2u;
-                async_copy16(base, j == bt ? loff_own[p] : loff[p], dst);
+                uint32_t off = loff[p];
+                if (qi < 16 && j == bt && own_rows < kBlock) {        // the sequence's last, partial block
+                    int row, chunk;
+                    k_piece_src(qi, lane, row, chunk);
+                    off = (uint32_t)(min(row, own_rows - 1) * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
+                }
+                async_copy16(base, off, dst);
             }
         };
-        auto issue_interval = [&](int4 r, int buf) {
-            issue_block(__builtin_amdgcn_readfirstlane(r.x), buf * SLOTS);
+        auto issue_interval = [&](int2 r, int buf) {
+            const uint32_t jj = (uint32_t)__builtin_amdgcn_readfirstlane(r.x);
+            issue_block((int)(jj & 0xffffu), buf * SLOTS);
             if (SLOTS == 2) {
-                const int j1 = __builtin_amdgcn_readfirstlane(r.z);
+                const int j1 = (int)(jj >> 16);
                 if (j1 != NONE) issue_block(j1, buf * SLOTS + 1);
             }
         };
-        int4 r_cur = ni > 0 ? interval(0) : make_int4(0, 0, NONE, 0);
+        int2 r_cur = ni > 0 ? interval(0) : make_int2(0, 0);
         if (ni > 0) issue_interval(r_cur, 0);
 
         // ---- this wave's token
@@ -246,36 +257,38 @@ struct TileKernel {
         const int m16 = lane & 15, g = lane >> 4;
         const int ti = w;
         {
-            const float c = a.scale * LOG2E;
+            float cm;
+            int ce;
+            split_scale(a.scale * LOG2E, cm, ce);
             const uint16_t *qp = a.q + ((int64_t)(row0 + ti) * a.hq + h * G + m16) * D + g * 8;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 uint4 raw = ti < ntok ? *reinterpret_cast<const uint4 *>(qp + s * 32) : make_uint4(0, 0, 0, 0);
-                st.qf[s] = scale_q(raw, c);
+                st.qf[s] = scale_q(raw, ce);
             }
-            tok_init(st);
+            tok_init(st, __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, cm))));
         }
-        const LaneOffs2 lo = lane_offsets2(lane);
+        const uint32_t kx = k_lane_bytes(lane), vx = v_lane_bytes(lane);
 
         // Main loop: while interval i is consumed from one buffer, the blocks of interval i + 1 land in the other
         // (every wave left that buffer before the barrier that ended interval i - 1).  The interval records are
         // read one iteration ahead, so their LDS latency hides behind the unit.
-        int4 r_next = ni > 1 ? interval(1) : r_cur;
+        int2 r_next = ni > 1 ? interval(1) : r_cur;
         __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
         __syncthreads();
         auto step = [&](auto own, int i) {
             constexpr bool OWN = decltype(own)::value;
-            const int j0 = __builtin_amdgcn_readfirstlane(r_cur.x);
-            const uint32_t mk0 = __builtin_amdgcn_readfirstlane(r_cur.y);
-            const uint32_t mk1 = SLOTS == 2 ? __builtin_amdgcn_readfirstlane(r_cur.w) : 0u;
+            const int j0 = __builtin_amdgcn_readfirstlane(r_cur.x) & 0xffff;
+            const uint32_t mks = (uint32_t)__builtin_amdgcn_readfirstlane(r_cur.y);
+            const uint32_t mk0 = mks & 0xffffu, mk1 = SLOTS == 2 ? mks >> 16 : 0u;
             if (i + 1 < ni) issue_interval(r_next, (i + 1) & 1);
             r_cur = r_next;
             if (i + 2 < ni) r_next = interval(i + 2);
-            const uint16_t *stage = stages + ((i & 1) * SLOTS) * STAGE_ELEMS;
+            const uint32_t stage = lds0 + (uint32_t)(((i & 1) * SLOTS) * STAGE_ELEMS * 2);
             // (consecutive tests rather than the arms of one branch: the compiler would otherwise merge the
             // identical operand reads of the two units above the branch and run out of registers)
-            if ((mk0 >> w) & 1u) unit<OWN>(st, stage, lo, lane, t0 + w - j0 * kBlock);
-            if (SLOTS == 2 && ((mk1 >> w) & 1u)) unit<false>(st, stage + STAGE_ELEMS, lo, lane, 0);
+            if ((mk0 >> w) & 1u) unit<OWN>(st, stage, kx, vx, lane, t0 + w - j0 * kBlock);
+            if (SLOTS == 2 && ((mk1 >> w) & 1u)) unit<false>(st, stage + STAGE_ELEMS * 2, kx, vx, lane, 0);
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);        // this wave's pieces of the next interval have landed
             __syncthreads();
         };
@@ -298,7 +311,7 @@ struct TileKernel {
             }
             // log-sum-exp in natural units: the reference and the row sum are kept in powers of two
             if (a.lse != nullptr && g == 0)
-                a.lse[(int64_t)(h * G + m16) * a.map.total_rows + row0 + ti] = (__log2f(l) - st.nm[0]) * 0.6931471805599453f;
+                a.lse[(int64_t)(h * G + m16) * a.map.total_rows + row0 + ti] = (__log2f(l) - st.nr) * 0.6931471805599453f;
         }
     }
 };
@@ -361,7 +374,7 @@ int launch_tile(const Launch &L, const AttnArgs &a0, const int32_t *cu_h) {
     // stages, block masks, union list (8 bytes per entry)
     const size_t lds = (size_t)2 * SLOTS * STAGE_ELEMS * sizeof(uint16_t) +
                        (size_t)a.nb_cap * 4 + (size_t)a.list_cap * 8;
-    if (lds > 160 * 1024 - 256) return INFLLMV2_ERR_UNSUPPORTED;     // does not fit: the caller pairs nothing
+    if (lds > 160 * 1024 - 256 || nb_max >= 0xffff) return INFLLMV2_ERR_UNSUPPORTED;     // does not fit: the caller pairs nothing
     auto kern = attn_tile_kernel<NW, SLOTS>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -377,6 +390,12 @@ int launch_tile(const Launch &L, const AttnArgs &a0, const int32_t *cu_h) {
 
 bool attn_mfma_supported(const infllmv2_params *p) {
     return p->dtype == INFLLMV2_BF16 && p->head_dim == D && p->num_q_heads / p->num_kv_heads == G;
+}
+
+// the V^T copy: one [128 dims][64 keys] tile per block and KV head
+size_t attn_fwd_ws_bytes(const infllmv2_params *p, const BatchTotals &t) {
+    if (!attn_mfma_supported(p)) return 0;
+    return align256((size_t)t.blocks * p->num_kv_heads * VT_TILE_ELEMS * sizeof(uint16_t));
 }
 
 int launch_attn_mfma(const Launch &L, const void *q, const void *k, const void *v, const int32_t *idx,
@@ -398,14 +417,13 @@ int launch_attn_mfma(const Launch &L, const void *q, const void *k, const void *
     a.dense_below = dense_below;
     a.scale = L.p->softmax_scale;
     a.nb_cap = a.list_cap = 0;
-    // V^T copy for the tile kernel: stream-ordered scratch, returned to the device's pool after the launch
+    // V^T copy for the tile kernel, in the caller's workspace
     int64_t nblk_total = 0;
     for (int s = 0; s < L.map.batch; ++s) nblk_total += (cu_h[s + 1] - cu_h[s] + kBlock - 1) / kBlock;
     if (nblk_total == 0) return INFLLMV2_OK;
-    keep_freed_memory_in_pool();
-    void *ws = nullptr;
-    const size_t ws_bytes = (size_t)nblk_total * L.p->num_kv_heads * VT_TILE_ELEMS * sizeof(uint16_t);
-    if (hipMallocAsync(&ws, ws_bytes, L.stream) != hipSuccess) return INFLLMV2_ERR_HIP;
+    void *ws = L.ws;
+    if (ws == nullptr || L.ws_bytes < (size_t)nblk_total * L.p->num_kv_heads * VT_TILE_ELEMS * sizeof(uint16_t))
+        return INFLLMV2_ERR_WORKSPACE_TOO_SMALL;
     a.vt = (const uint16_t *)ws;
     a.nblk_total = (int)nblk_total;
     hipLaunchKernelGGL(vt_transpose_kernel, dim3((unsigned)nblk_total, L.p->num_kv_heads), dim3(256), 0, L.stream,
@@ -418,7 +436,6 @@ int launch_attn_mfma(const Launch &L, const void *q, const void *k, const void *
         if (idx != nullptr) rc = launch_tile<16, 2>(L, a, cu_h);
         if (rc == INFLLMV2_ERR_UNSUPPORTED) rc = launch_tile<16, 1>(L, a, cu_h);
     }
-    if (hipFreeAsync(ws, L.stream) != hipSuccess && rc == INFLLMV2_OK) rc = INFLLMV2_ERR_HIP;
     return rc;
 }
 

@@ -206,21 +206,20 @@ __device__ inline void softmax_pv(TokState &st, f32x4 (&acc)[4], const uint16_t 
 // key tiles through the instruction's immediate offset.
 constexpr int VT_TILE_ELEMS = D * kBlock;            // one V^T block: 128 rows x 128 B
 
-struct LaneOffs2 {
-    int kx[4];         // K operand, k-step s: element offset of (row 8 (m16 / 4) + m16 % 4, logical chunk 4s + g)
-    int vx[2];         // V^T operand, k-step s2: element offset of (row m16, logical chunk 4 s2 + g)
-};
-
-__device__ inline LaneOffs2 lane_offsets2(int lane) {
-    LaneOffs2 o;
+// Operand addresses.  K operand of k-step s: row 8 (m16 / 4) + m16 % 4 (+ a constant per key tile), logical chunk
+// 4s + g, stored at chunk (4s + g) ^ m16 = (g ^ m16) ^ 4s: the byte offset of k-step s is that of k-step 0 with
+// bits 6-7 flipped by s, so one register per lane (plus an exclusive-or when the address is formed) serves all
+// k-steps.  Likewise the V^T operand of k-step s2: row m16 (+ 16 per dim tile), chunk (4 s2 + g) ^ ((m16 >> 1) & 7).
+__device__ inline uint32_t k_lane_bytes(int lane) {
     const int m16 = lane & 15, g = lane >> 4;
-    const int krow = 8 * (m16 >> 2) + (m16 & 3);
-#pragma unroll
-    for (int s = 0; s < 4; ++s) o.kx[s] = krow * D + (((4 * s + g) ^ m16) << 3);
-#pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2) o.vx[s2] = m16 * kBlock + (((4 * s2 + g) ^ ((m16 >> 1) & 7)) << 3);
-    return o;
+    return (uint32_t)((8 * (m16 >> 2) + (m16 & 3)) * D + ((g ^ m16) << 3)) * 2u;
 }
+__device__ inline uint32_t v_lane_bytes(int lane) {
+    const int m16 = lane & 15, g = lane >> 4;
+    return (uint32_t)(m16 * kBlock + ((g ^ ((m16 >> 1) & 7)) << 3)) * 2u;
+}
+typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
+__device__ inline bf16x8 lds_read16(uint32_t byte_addr) { return *(lds_bf16x8 *)(uintptr_t)byte_addr; }
 
 // Per-lane byte offsets of the asynchronous loads that fill the two tiles; piece q is 1 KB of LDS.
 // K piece q (rows 4q .. 4q+3 of the block): lane l fills (row 4q + l / 16, physical chunk l % 16).
@@ -236,129 +235,174 @@ __device__ inline uint32_t vt_piece_src_bytes(int q, int lane) {
 }
 
 struct Tok {
-    bf16x8 qf[4];      // Q_t * softmax_scale * log2(e) as MFMA B operand: head = lane % 16, dims ks*32 + (lane/16)*8 ..
+    bf16x8 qf[4];      // Q_t * 2^ce (exact) as MFMA B operand: head = lane % 16, dims ks*32 + (lane/16)*8 ..
     f32x4 o[8];        // O_t^T: dim tile dt, dims dt*16 + 4*(lane/16) + r, head = lane % 16
-    f32x4 nm;          // minus the reference (log2 units) in all four slots: seed of the S^T accumulator
+    float nr;          // minus the reference of the online softmax, in powers of two
     float l;           // this lane's share of the running sum
-    bool fresh;        // no block consumed yet (wave-uniform)
+    float cm;          // mantissa of softmax_scale * log2(e): probability = 2^(cm * accumulator + nr)
+    float slack;       // a lane's probabilities of a half block may sum to this much before the reference moves;
+                       // negative while no block has been consumed yet, so that the first one always sets it
+                       // (a value rather than a flag: a branch on a flag lets the compiler move the
+                       // exponentials out from between the products)
 };
 
-// a lane's 16 probabilities may sum to this much before the reference moves (each is then < 2^12)
+// a lane's 8 probabilities of a half block may sum to this much before the reference moves (each is then < 2^12)
 constexpr float kSumSlack = 4096.0f;
 
-__device__ inline void tok_init(Tok &t) {
+// softmax_scale * log2(e) = cm * 2^ce with 0.5 <= cm < 1.  The power of two goes into Q (exact in bf16), the
+// mantissa multiplies the fp32 accumulator (in the same fused multiply-add that subtracts the reference), so the
+// logits are those of Q as stored (Alg. 2 computes S from Q itself; rounding Q * scale back to bf16 would move
+// every logit by ~1e-3).
+__device__ inline void split_scale(float c, float &cm, int &ce) { cm = frexpf(c, &ce); }
+
+__device__ inline void tok_init(Tok &t, float cm) {
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) t.o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    t.nm = f32x4{0.f, 0.f, 0.f, 0.f};
+    t.nr = 0.f;
     t.l = 0.f;
-    t.fresh = true;
+    t.cm = cm;
+    t.slack = -1.0f;
 }
 
-// Q fragment scaled by c and rounded to bf16 (round to nearest even)
-__device__ inline bf16x8 scale_q(uint4 raw, float c) {
+// Q fragment times 2^ce: exact unless the result leaves bf16's exponent range
+__device__ inline bf16x8 scale_q(uint4 raw, int ce) {
     const bf16x8 q = __builtin_bit_cast(bf16x8, raw);
     bf16x8 r;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) r[i] = (__bf16)((float)q[i] * c);
+    for (int i = 0; i < 8; ++i) r[i] = (__bf16)ldexpf((float)q[i], ce);
     return r;
 }
 
-__device__ inline bf16x8 k_frag(const uint16_t *ktile, const LaneOffs2 &lo, int i) {     // i -> (s = i / 4, kt = i % 4)
-    const int kt = i & 3;
-    return *reinterpret_cast<const bf16x8 *>(ktile + (32 * (kt >> 1) + 4 * (kt & 1)) * D + lo.kx[i >> 2]);
+// kb / vb: LDS byte address of the stage (a multiple of 1024) plus k_lane_bytes / v_lane_bytes of the lane.  The
+// k-step is applied by exclusive-or after the stage address has been added (the stage address has no low bits, so
+// that is the same thing) -- formed the other way round, the compiler keeps a register per k-step alive for the whole
+// kernel.  Key tile / dim tile offsets are instruction immediates.
+__device__ inline bf16x8 k_frag(uint32_t kb, int kt, int s) {
+    return lds_read16((kb ^ (uint32_t)(64 * s)) + (uint32_t)((32 * (kt >> 1) + 4 * (kt & 1)) * D * 2));
 }
-__device__ inline bf16x8 v_frag(const uint16_t *vtile, const LaneOffs2 &lo, int i) {     // i -> (s2 = i / 8, dt = i % 8)
-    return *reinterpret_cast<const bf16x8 *>(vtile + (i & 7) * 16 * kBlock + lo.vx[i >> 3]);
+__device__ inline bf16x8 v_frag(uint32_t vb, int dt, int s2) {
+    return lds_read16((vb ^ (uint32_t)(64 * s2)) + (uint32_t)(TILE_ELEMS * 2 + dt * 16 * kBlock * 2));
 }
 
-// 2^exponent for the 16 exponents of a lane, packed as the B operand of the two PV k-steps (slot i = key
-// 32 s2 + 8g + i); returns their sum
-__device__ inline float probs(const f32x4 (&acc)[4], bf16x8 (&pb)[2]) {
-    float ls = 0.f;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ inline uint32_t pack_bf16(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo, hi}, bf16x2));
+}
+
+// A lane's share of a half block (32 keys): the 8 exponents a0[0..3], a1[0..3] become the B operand of the PV
+// k-step of that half (slot e = key 32 half + 8g + e).  exponent e -> probability; the causal mask of the token's own
+// block is applied on the way and written back, so that a later move of the reference sees the masked exponents.
+template <bool OWN>
+__device__ inline float prob_step(f32x4 &a0, f32x4 &a1, int e, float (&p)[2], u32x4 &pb, float cm, float nr, int key0,
+                                  int key_limit) {
+    float x = e < 4 ? a0[e & 3] : a1[e & 3];
+    if (OWN && key0 + e > key_limit) {
+        x = -INFINITY;
+        if (e < 4) a0[e & 3] = x; else a1[e & 3] = x;
+    }
+    const float q = fast_exp2(__builtin_fmaf(x, cm, nr));
+    p[e & 1] = q;
+    if (e & 1) {
+        uint32_t w = pack_bf16(p[0], p[1]);
+        asm volatile("" : "+v"(w));        // packed here, not after the branch that follows the half block
+        pb[e >> 1] = w;
+    }
+    return q;
+}
+
+// The lazy reference.  Probabilities are computed with the reference as it is; only if a lane's sum of them says
+// that an exponent was large (or this is the token's first half block) is the reference moved to the half block's
+// maximum, everything accumulated so far rescaled, and the half block's probabilities redone from the exponents,
+// which are still in a0, a1.
+__device__ inline float move_reference(Tok &t, f32x4 &a0, f32x4 &a1, u32x4 &pb) {
+    float mx = fmaxf(fmaxf(a0[0], a0[1]), a0[2]);
+    mx = fmaxf(fmaxf(mx, a0[3]), a1[0]);
+    mx = fmaxf(fmaxf(mx, a1[1]), a1[2]);
+    mx = fmaxf(mx, a1[3]);
+    mx = rows_max(mx);                     // all four lanes of a head agree
+    float delta = __builtin_fmaf(mx, t.cm, t.nr);      // by how much the largest exponent exceeds the reference
+    float alpha = 1.0f;
+    if (t.slack > 0.f) {
+        delta = fmaxf(delta, 0.f);         // never down once there is history
+        alpha = fast_exp2(-delta);
+    }
+    t.slack = kSumSlack;
+    t.nr -= delta;
+    t.l *= alpha;
 #pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2)
+    for (int dt = 0; dt < 8; ++dt) t.o[dt] *= alpha;
+    float ls = 0.f, p[2];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float p0 = fast_exp2(acc[2 * s2][r]), p1 = fast_exp2(acc[2 * s2 + 1][r]);
-            ls += p0 + p1;
-            pb[s2][r] = (__bf16)p0;
-            pb[s2][4 + r] = (__bf16)p1;
-        }
+    for (int e = 0; e < 8; ++e) ls += prob_step<false>(a0, a1, e, p, pb, t.cm, t.nr, 0, 0);
     return ls;
 }
 
-// Exponents of one token -> probabilities, with the causal mask of the token's own block and the lazy reference.
-// The probabilities are computed with the reference as it is; only if a lane's sum of them says that an exponent
-// was large (or this is the token's first block) is the reference moved and the work redone from the exponents,
-// which are still in acc.  The common case then has no maximum to compute at all.
-template <bool OWN>
-__device__ inline void softmax_tok(Tok &t, f32x4 (&acc)[4], bf16x8 (&pb)[2], int g, int key_limit) {
-    if (OWN) {
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (32 * (kt >> 1) + 8 * g + 4 * (kt & 1) + r > key_limit) acc[kt][r] = -INFINITY;
-    }
-    float ls = probs(acc, pb);
-    if (t.fresh || __any(!(ls < kSumSlack))) {
-        float mx = fmaxf(fmaxf(acc[0][0], acc[0][1]), acc[0][2]);
-        mx = fmaxf(fmaxf(mx, acc[0][3]), acc[1][0]);
-        mx = fmaxf(fmaxf(mx, acc[1][1]), acc[1][2]);
-        mx = fmaxf(fmaxf(mx, acc[1][3]), acc[2][0]);
-        mx = fmaxf(fmaxf(mx, acc[2][1]), acc[2][2]);
-        mx = fmaxf(fmaxf(mx, acc[2][3]), acc[3][0]);
-        mx = fmaxf(fmaxf(mx, acc[3][1]), acc[3][2]);
-        mx = fmaxf(mx, acc[3][3]);
-        // move the reference of every head to its current maximum (never down once there is history)
-        float delta = rows_max(mx);
-        float alpha = 1.0f;
-        if (!t.fresh) {
-            delta = fmaxf(delta, 0.f);
-            alpha = fast_exp2(-delta);
-        }
-        t.fresh = false;
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) acc[kt][r] -= delta;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) t.nm[r] -= delta;
-        t.l *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) t.o[dt] *= alpha;
-        ls = probs(acc, pb);
-    }
-    t.l += ls;
-}
-
 // One token against one block.  OWN: the block is the token's own and keys past key_limit are masked.
+//
+// The block is handled as two halves of 32 keys so that the vector work of the softmax always has matrix work
+// of the same wave to hide under: the exponentials of the first half are issued between the S^T products of the
+// second half, those of the second half between the PV products of the first.  (With the whole block's softmax
+// between the two groups of products, the waves of a workgroup, which start every unit together after a barrier,
+// all reach the softmax at the same time and the matrix core idles meanwhile.)  The order below is the issue
+// order: a scheduling fence after every step keeps the compiler from regrouping it.
 template <bool OWN>
-__device__ inline void unit(Tok &t, const uint16_t *stage, const LaneOffs2 &lo, int lane, int key_limit) {
-    const uint16_t *ktile = stage, *vtile = stage + TILE_ELEMS;
-    constexpr int W = 4;               // operand fetches run W MFMAs ahead
+__device__ inline void unit(Tok &t, uint32_t stage, uint32_t kx, uint32_t vx, int lane, int key_limit) {
+    const int key0 = 8 * (lane >> 4);
+    const uint32_t kb = stage + kx, vb = stage + vx;
+    constexpr int W = 4;               // operand fetches run W products ahead, through all four groups of products
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     f32x4 acc[4];
-    bf16x8 pb[2];
+    u32x4 pb[2];
     bf16x8 f[W];
-    // ---- exponents: S^T seeded with minus the reference
+    float p[2];
+    // fragment n of the unit: 0-7 K rows of the first half (key tile n & 1, k-step n >> 1), 8-15 of the second
+    // half, 16-23 V^T k-step 0 (dim tile n & 7), 24-31 V^T k-step 1
+    auto frag = [&](int n) -> bf16x8 {
+        if (n < 16) return k_frag(kb, 2 * (n >> 3) + (n & 1), (n >> 1) & 3);
+        return v_frag(vb, n & 7, (n >> 3) & 1);
+    };
 #pragma unroll
-    for (int i = 0; i < W; ++i) f[i] = k_frag(ktile, lo, i);
+    for (int n = 0; n < W; ++n) f[n] = frag(n);
+    // ---- exponents of the first half (8 products, 2 accumulators)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int kt = i & 3, s = i >> 2;
-        acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[i % W], t.qf[s], s == 0 ? t.nm : acc[kt], 0, 0, 0);
-        if (i + W < 16) f[i % W] = k_frag(ktile, lo, i + W);
+    for (int i = 0; i < 8; ++i) {
+        const int kt = i & 1, s = i >> 1;
+        acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[i % W], t.qf[s], s == 0 ? zero : acc[kt], 0, 0, 0);
+        f[i % W] = frag(i + W);
+        __builtin_amdgcn_sched_barrier(0);
     }
-    // V^T fragments of the first k-step are requested before the softmax so that they arrive under it
+    // ---- second half's exponents || first half's probabilities
+    float ls = 0.f;
 #pragma unroll
-    for (int i = 0; i < W; ++i) f[i] = v_frag(vtile, lo, i);
-    softmax_tok<OWN>(t, acc, pb, lane >> 4, key_limit);
-    // ---- O^T += V^T P^T
+    for (int i = 0; i < 8; ++i) {
+        const int kt = i & 1, s = i >> 1;
+        acc[2 + kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[(8 + i) % W], t.qf[s], s == 0 ? zero : acc[2 + kt], 0, 0, 0);
+        f[(8 + i) % W] = frag(8 + i + W);
+        ls += prob_step<OWN>(acc[0], acc[1], i, p, pb[0], t.cm, t.nr, key0, key_limit);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (__any(!(ls < t.slack))) ls = move_reference(t, acc[0], acc[1], pb[0]);
+    t.l += ls;
+    // ---- O^T += V^T P^T of the first half || second half's probabilities
+    ls = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int dt = i & 7, s2 = i >> 3;
-        t.o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[i % W], pb[s2], t.o[dt], 0, 0, 0);
-        if (i + W < 16) f[i % W] = v_frag(vtile, lo, i + W);
+    for (int i = 0; i < 8; ++i) {
+        t.o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[(16 + i) % W], __builtin_bit_cast(bf16x8, pb[0]), t.o[i], 0, 0, 0);
+        f[(16 + i) % W] = frag(16 + i + W);
+        ls += prob_step<OWN>(acc[2], acc[3], i, p, pb[1], t.cm, t.nr, key0 + 32, key_limit);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (__any(!(ls < t.slack))) ls = move_reference(t, acc[2], acc[3], pb[1]);
+    t.l += ls;
+    // ---- second half
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        t.o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[(24 + i) % W], __builtin_bit_cast(bf16x8, pb[1]), t.o[i], 0, 0, 0);
+        if (i + W < 8) f[(24 + i) % W] = frag(24 + i + W);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 

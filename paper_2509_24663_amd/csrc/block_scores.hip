@@ -668,14 +668,13 @@ int launch_scores_mfma(const Launch &L, ScoreArgs a, const int32_t *cu_h) {
     }
     if (tiles == 0 || kt_fine == 0) return INFLLMV2_OK;      // no token sees a compressed key
     if (kt_fine + kt_coarse > 0x7fffffff) return INFLLMV2_ERR_UNSUPPORTED;
-    // fp16 key tiles + one shift per tile: stream-ordered scratch, returned to the device's pool after the launch
+    // fp16 key tiles + one shift per tile, in the caller's workspace
     const int hkv = L.p->num_kv_heads;
     const size_t tile_bytes = (size_t)kBlock * SD * sizeof(_Float16);
     const size_t data_bytes = (size_t)hkv * (kt_fine + kt_coarse) * tile_bytes;
     const size_t ws_bytes = data_bytes + (size_t)hkv * (kt_fine + kt_coarse) * sizeof(int32_t);
-    keep_freed_memory_in_pool();
-    void *ws = nullptr;
-    if (hipMallocAsync(&ws, ws_bytes, L.stream) != hipSuccess) return INFLLMV2_ERR_HIP;
+    void *ws = L.ws;
+    if (ws == nullptr || L.ws_bytes < ws_bytes) return INFLLMV2_ERR_WORKSPACE_TOO_SMALL;
     _Float16 *fine = (_Float16 *)ws, *coarse = fine + (size_t)hkv * kt_fine * kBlock * SD;
     int32_t *sh_fine = (int32_t *)((char *)ws + data_bytes), *sh_coarse = sh_fine + (size_t)hkv * kt_fine;
     int ce;
@@ -687,21 +686,32 @@ int launch_scores_mfma(const Launch &L, ScoreArgs a, const int32_t *cu_h) {
     const size_t lds = (size_t)2 * S_TILE * sizeof(_Float16);
     dim3 grid((unsigned)tiles, hkv);
     hipLaunchKernelGGL((block_scores_mfma_kernel<NW, TPW, POOL>), grid, dim3(NW * 64), lds, L.stream, a, (int)tiles);
-    const hipError_t e = hipGetLastError();
-    (void)hipFreeAsync(ws, L.stream);
-    return hip_status(e);
+    return hip_status(hipGetLastError());
+}
+
+bool scores_mfma_params(const infllmv2_params *p, bool pooled) {
+    // the tiled kernel pools on chip only for the paper's window (l = 5, s = 4), unshifted or shifted by one, with
+    // four compressed keys per selection block (block j's window then starts at key 4j of its tile row)
+    const bool pool_ok = !pooled || (p->pool_len == 5 && p->pool_stride == 4 && (p->pool_pad == 0 || p->pool_pad == 1) &&
+                                     p->cmp_stride * p->pool_stride == kBlock);
+    return p->dtype == INFLLMV2_BF16 && p->head_dim == SD && p->num_q_heads / p->num_kv_heads == SG && pool_ok;
 }
 
 }  // namespace
+
+// fp16 copies of the fine (and, with the LSE Approximation, coarse) key tiles plus one shift per tile
+size_t scores_ws_bytes(const infllmv2_params *p, const BatchTotals &t, bool pooled) {
+    if (!scores_mfma_params(p, pooled)) return 0;
+    const int64_t tiles = t.kt_fine + (p->lse_mode ? t.kt_coarse : 0);
+    return align256((size_t)p->num_kv_heads * tiles * ((size_t)kBlock * SD * sizeof(_Float16) + sizeof(int32_t)));
+}
 
 int launch_block_scores(const Launch &L, const void *q, const float *kc, float *s_shared, int64_t row_stride,
                         const int32_t *cu_h, bool pooled) {
     const bool bf = L.p->dtype == INFLLMV2_BF16;
     const PoolArgs pool{pooled ? 1 : 0, L.p->pool_len, L.p->pool_stride, L.p->pool_pad};
-    // the tiled kernel pools on chip only for the paper's window (l = 5, s = 4), unshifted or shifted by one
-    const bool pool_ok = !pooled || (pool.len == 5 && pool.stride == 4 && (pool.pad == 0 || pool.pad == 1));
-    if (bf && cu_h != nullptr && L.map.ctx == nullptr && L.p->head_dim == SD &&
-        L.p->num_q_heads / L.p->num_kv_heads == SG && (((uintptr_t)q | (uintptr_t)kc) & 15) == 0 && pool_ok) {
+    if (cu_h != nullptr && L.map.ctx == nullptr && scores_mfma_params(L.p, pooled) &&
+        (((uintptr_t)q | (uintptr_t)kc) & 15) == 0) {
         ScoreArgs a{(const uint16_t *)q, kc, HalfTiles{}, HalfTiles{}, s_shared, L.map, L.p->num_q_heads, L.p->cmp_len, L.p->cmp_stride,
                     L.p->dense_threshold, L.p->lse_mode, L.p->softmax_scale, row_stride};
         if (!pooled) return launch_scores_mfma<8, 4, -1>(L, a, cu_h);

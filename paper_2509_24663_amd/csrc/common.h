@@ -123,6 +123,8 @@ struct Launch {
     RowMap map;
     hipStream_t stream;
     int32_t max_len;          // longest sequence (host knowledge, for grid sizing)
+    void *ws;                 // caller's scratch (device, 256-byte aligned) and its size
+    size_t ws_bytes;
 };
 
 int launch_cu_c(const infllmv2_params *p, const int32_t *cu_d, int batch, int32_t *cu_c_d, hipStream_t s);
@@ -148,19 +150,24 @@ int launch_attn_bwd(const Launch &L, const void *q, const void *k, const void *v
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? INFLLMV2_OK : INFLLMV2_ERR_HIP; }
 
-// Stream-ordered scratch (hipMallocAsync / hipFreeAsync) comes from the current device's default memory pool.  By
-// default the pool hands freed memory back to the driver at every synchronisation; a release threshold of
-// "never" makes the second and later calls allocation-free in effect.  Set once per device.
-inline void keep_freed_memory_in_pool() {
-    static bool pool_set[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && !pool_set[dev]) {
-        hipMemPool_t pool;
-        uint64_t keep = UINT64_MAX;
-        if (hipDeviceGetDefaultMemPool(&pool, dev) == hipSuccess)
-            (void)hipMemPoolSetAttribute(pool, hipMemPoolAttrReleaseThreshold, &keep);
-        pool_set[dev] = true;
-    }
-}
+inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+// ---------------------------------------------------------------- caller-provided scratch
+// What a call needs depends on the batch only through a few totals, so the exact need of a call (from its host
+// cu_seqlens) and the bound the workspace query returns (from batch, total tokens, longest sequence) share one
+// formula each.  All sizes are multiples of 256 bytes; 0 = the path that serves these parameters needs none.
+struct BatchTotals {
+    int64_t rows;         // tokens
+    int64_t blocks;       // sum over sequences of ceil(len / 64)
+    int64_t kt_fine;      // sum of ceil(nc(len) / 64): 64-key tiles of K^{C1}
+    int64_t kt_coarse;    // the same for the coarse keys of the LSE Approximation
+    int64_t sel_words;    // sum of ceil(len / 64) * ceil(len / 32): words of the backward's selection bitmap per KV head
+};
+BatchTotals exact_totals(const infllmv2_params *p, const int32_t *cu_h, int batch);
+BatchTotals bound_totals(const infllmv2_params *p, int batch, int64_t total_tokens, int32_t max_seqlen);
+size_t scores_ws_bytes(const infllmv2_params *p, const BatchTotals &t, bool pooled);
+size_t attn_fwd_ws_bytes(const infllmv2_params *p, const BatchTotals &t);
+// with_bitmap: including the block-major selection bitmap that speeds up dK/dV when block lists are given
+size_t attn_bwd_ws_bytes(const infllmv2_params *p, const BatchTotals &t, bool with_bitmap);
 
 }  // namespace ifv2

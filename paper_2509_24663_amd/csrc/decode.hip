@@ -175,6 +175,7 @@ __global__ void __launch_bounds__(256) dec_scores_kernel(DecArgs a) {
 // Stages 2b-3 for one (sequence, KV head) pair in one workgroup.  Selection rule and tie handling are those of
 // topk_row: keys above the k-th largest, then the first `need` keys equal to it in ascending block order.
 constexpr int SEL_THREADS = 1024;
+constexpr size_t kSelLdsMax = 128 * 1024;     // dynamic LDS of the select kernel: score row + pooled keys
 constexpr int SEL_WAVES = SEL_THREADS / 64;
 
 // exclusive prefix count of `flag` over the workgroup's threads in thread order (+ total); two barriers
@@ -199,7 +200,7 @@ __device__ inline int wg_prefix_count(bool flag, int *wave_tot, int tid, int &to
 __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int sh_cap) {
     extern __shared__ __attribute__((aligned(16))) float sel_smem[];
     float *sh = sel_smem;                                              // [sh_cap] group scores of the row
-    uint32_t *pk = reinterpret_cast<uint32_t *>(sel_smem + sh_cap);    // [(sh_cap + 3) / 4 + 1] pooled keys per block
+    uint32_t *pk = reinterpret_cast<uint32_t *>(sel_smem + sh_cap);    // [blocks of the longest context + 4] pooled keys
     __shared__ float red[64][16][2];
     __shared__ float lse2[16];
     __shared__ int hist[4][256];                 // one histogram per radix pass, all zeroed up front
@@ -627,27 +628,17 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
 
     // group sum + max-pool + top-k run as one workgroup per pair with the score row in LDS
     const int sh_cap = (d.zs + 3) / 4 * 4;
-    const size_t sel_lds = ((size_t)sh_cap + (size_t)sh_cap / 4 + 4) * sizeof(float);
-    if (sel_lds > 128 * 1024) return INFLLMV2_ERR_UNSUPPORTED;     // before anything is launched
-    // Larger-than-default dynamic LDS has to be enabled once per kernel and device; remembered per device (a
-    // repeated or concurrent call sets the same value again, which is harmless).
-    static size_t sel_attr[64] = {};
-    static bool attn_attr[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return INFLLMV2_ERR_HIP;
-    if (sel_lds > 48 * 1024 && sel_lds > sel_attr[dev]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(dec_select_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sel_lds);
-        if (e != hipSuccess) return INFLLMV2_ERR_HIP;
-        sel_attr[dev] = sel_lds;
-    }
+    // (one pooled key per selection block: however many compressed keys a block spans)
+    const size_t sel_lds = ((size_t)sh_cap + (size_t)(max_ctx + kBlock - 1) / kBlock + 4) * sizeof(float);
+    if (sel_lds > kSelLdsMax) return INFLLMV2_ERR_UNSUPPORTED;     // before anything is launched
+    // Larger-than-default dynamic LDS has to be enabled per kernel; the same fixed limits are set on every call, so
+    // nothing has to be remembered between calls.
     const size_t attn_lds = (size_t)AW * TILE_ELEMS * sizeof(uint16_t);
-    if (!attn_attr[dev]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(dec_attn_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds);
-        if (e != hipSuccess) return INFLLMV2_ERR_HIP;
-        attn_attr[dev] = true;
-    }
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(dec_select_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSelLdsMax) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void *>(dec_attn_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds) != hipSuccess)
+        return INFLLMV2_ERR_HIP;
     hipLaunchKernelGGL(dec_scores_kernel, dim3(d.nchunk, pairs), dim3(256), 0, stream, a);
     hipLaunchKernelGGL(dec_select_kernel, dim3(pairs), dim3(SEL_THREADS), sel_lds, stream, a, sh_cap);
     hipLaunchKernelGGL(dec_attn_kernel, dim3(d.nsplit, pairs), dim3(AW * 64), attn_lds, stream, a);

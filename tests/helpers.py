@@ -25,13 +25,17 @@ def out_tolerances(dtype: str):
     return (FP32_MAX_ABS, None) if dtype == "fp32" else (BF16_MAX_ABS, BF16_MEAN_ABS)
 
 
+SCORE_RTOL = 5e-4        # stage-2 scores: K^{C1} enters the MFMA as fp16 (11-bit significand), see below
+TIE_FLIP_RATE_MAX = 0.05  # share of sampled rows whose list may differ from the oracle's by near-ties
+
+
 def prefill_lse_atol(dtype: str) -> float:
-    """Tolerance for the log-sum-exp of the prefill kernels.  The bf16 tile kernel multiplies Q by
-    softmax_scale * log2(e) before the matrix product and rounds the result to bf16 again (relative error at most
-    2^-9 per element, unbiased).  With d_h = 128 and unit-scale data that perturbs a logit by about
-    2^-9 / sqrt(3) * sqrt(128) * scale * |q_i k_i| ~ 1e-3 (one sigma) and the log-sum-exp, a weighted mean of logit
-    errors, by at most a few sigma; the outputs keep their own max-abs / mean-abs bars."""
-    return 1e-2 if dtype == "bf16" else 1e-4
+    """Tolerance for the log-sum-exp of the prefill kernels.  The logits are formed from Q and K as stored (the
+    power-of-two part of softmax_scale * log2(e) goes into Q exactly, the mantissa multiplies the fp32
+    accumulator), accumulated in fp32; what is left is the fast exponential / logarithm (relative 2^-22) and the
+    order of a sum over up to 131072 keys: 2e-3 is the bar the bf16 decode path has always met, 1e-4 for fp32
+    data (whose logits are accumulated by plain fp32 loops)."""
+    return 2e-3 if dtype == "bf16" else 1e-4
 
 
 def assert_out_close(got: np.ndarray, want: np.ndarray, dtype: str, what: str = "out"):
