@@ -296,6 +296,24 @@ int infllmv2_sparse_decode(const infllmv2_params *p, const void *q_d, const void
  * (= infllmv2_workspace_bytes(INFLLMV2_OP_SPARSE_DECODE, p, batch, 0, max_ctx_len)). */
 size_t infllmv2_decode_workspace_bytes(const infllmv2_params *p, int32_t batch, int32_t max_ctx_len);
 
+/*
+ * infllmv2_sparse_decode for callers that cannot allocate or pass device scratch: code under HIP graph capture that
+ * may not call hipMalloc, tight serving loops, harnesses that forbid allocation.  Same arguments, results and
+ * errors as infllmv2_sparse_decode without (workspace_d, workspace_bytes): the scratch is a fixed array of
+ * infllmv2_sparse_decode_static_capacity() bytes (16 MiB: batch 16 with contexts up to 65536 tokens fits) inside the
+ * library's device image, which every GPU the library runs on holds until the process ends.  A step that needs
+ * more (infllmv2_decode_workspace_bytes) returns INFLLMV2_ERR_WORKSPACE_TOO_SMALL before anything is launched.  The
+ * call allocates and frees nothing.  All calls on one GPU share that GPU's array: calls that overlap in time on one
+ * GPU (different streams or threads) race and give undefined results; calls on one stream, or ordered by events,
+ * are fine.  The first call on a GPU looks the array's address up once (a host-side query).
+ */
+int infllmv2_sparse_decode_static(const infllmv2_params *p, const void *q_d, const void *k_cache_d,
+                                  const void *v_cache_d, int64_t kv_batch_stride, int64_t kv_head_stride,
+                                  int64_t kv_tok_stride, const float *kc_cache_d, int64_t kc_head_stride,
+                                  const int32_t *ctx_lens_h, const int32_t *ctx_lens_d, int32_t batch,
+                                  int32_t *block_idx_out_d, void *out_d, float *lse_d, void *stream);
+size_t infllmv2_sparse_decode_static_capacity(void);
+
 #ifdef __cplusplus
 }
 #endif

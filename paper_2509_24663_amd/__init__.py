@@ -25,6 +25,8 @@ from .binding import (  # noqa: F401
     sparse_attn_bwd,
     sparse_attn_fwd,
     sparse_decode,
+    sparse_decode_static,
+    sparse_decode_static_capacity,
     sparse_prefill,
     status_string,
     topk_blocks,

@@ -77,6 +77,9 @@ _SIGNATURES = {
     "infllmv2_sparse_decode": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _I64, _P, _I64, _P, _P, _I32, _P, _P, _P,
                                               _P, _SZ, _P]),
     "infllmv2_decode_workspace_bytes": (_SZ, [_PP, _I32, _I32]),
+    "infllmv2_sparse_decode_static": (ctypes.c_int, [_PP, _P, _P, _P, _I64, _I64, _I64, _P, _I64, _P, _P, _I32, _P, _P, _P,
+                                                     _P]),
+    "infllmv2_sparse_decode_static_capacity": (_SZ, []),
 }
 
 
@@ -361,6 +364,24 @@ def sparse_decode(p: Params, q, k_cache, v_cache, kc_cache, ctx_lens, workspace=
                                       _ptr(di.ctx_h), _ptr(di.ctx_d), B, _ptr(idx), _ptr(out), _ptr(lse),
                                       _ptr(workspace), workspace.numel(), _stream())
     _check(st, "infllmv2_sparse_decode")
+    return out, lse, idx
+
+
+def sparse_decode_static_capacity() -> int:
+    return int(lib().infllmv2_sparse_decode_static_capacity())
+
+
+def sparse_decode_static(p: Params, q, k_cache, v_cache, kc_cache, ctx_lens, out, lse, idx=None):
+    """Decode step through the entry point that allocates nothing: scratch is a fixed array inside the library, and
+    every output buffer is the caller's (out [B, hq, d], lse [B, hq], idx [B, hkv, topk_total] or None)."""
+    di = ctx_lens if isinstance(ctx_lens, DecodeInfo) else DecodeInfo(ctx_lens)
+    assert k_cache.dim() == 4 and k_cache.stride(3) == 1 and k_cache.stride() == v_cache.stride()
+    assert kc_cache.dim() == 4 and kc_cache.is_contiguous() and q.is_contiguous() and out.is_contiguous()
+    st = lib().infllmv2_sparse_decode_static(ctypes.byref(p), _ptr(q), _ptr(k_cache), _ptr(v_cache), k_cache.stride(0),
+                                             k_cache.stride(1), k_cache.stride(2), _ptr(kc_cache), kc_cache.stride(1),
+                                             _ptr(di.ctx_h), _ptr(di.ctx_d), q.shape[0], _ptr(idx), _ptr(out), _ptr(lse),
+                                             _stream())
+    _check(st, "infllmv2_sparse_decode_static")
     return out, lse, idx
 
 
