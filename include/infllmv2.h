@@ -282,7 +282,7 @@ int infllmv2_dense_attn_fwd(const infllmv2_params *p, const void *q_d, const voi
  *   out_d          device out dtype [batch, num_q_heads, head_dim];  lse_d float32 [batch, num_q_heads] or NULL
  *   workspace_d    device scratch of at least infllmv2_decode_workspace_bytes(...) bytes, 256-byte aligned
  * Contexts longer than 262144 tokens are supported only for bf16 data with 16 query heads per KV head and
- * head_dim 128 (up to about 419000 tokens); longer ones return INFLLMV2_ERR_UNSUPPORTED.
+ * head_dim 128 (with the LSE Approximation up to about 419000 tokens; longer ones return INFLLMV2_ERR_UNSUPPORTED).
  * Sequences shorter than dense_threshold attend densely.
  */
 int infllmv2_sparse_decode(const infllmv2_params *p, const void *q_d, const void *k_cache_d, const void *v_cache_d,

@@ -2,24 +2,28 @@
 // t = L-1 of every sequence (the row of Alg. 1 / Eq. 2 / Alg. 2 that a prefill would compute last).
 // The step moves ~100 MB (compressed-key cache once, 64 selected K/V blocks per KV head) and does almost no
 // arithmetic, so the work of one (sequence, KV head) pair is split over many workgroups to fill the chip;
-// the two reductions that need a whole pair are separate small kernels.  A kernel boundary is the cheap way to
-// make one workgroup's results visible to another on a multi-die GPU: letting the last attend workgroup of a pair
-// do the merge (device-wide fence + counter) was measured slower than the extra launch, 58.6 vs 53.3 us, because
-// the fences act on whole caches.
+// reductions that need a whole pair sit behind kernel boundaries.  A kernel boundary is the cheap way to make one
+// workgroup's results visible to another on a multi-die GPU: letting the last attend workgroup of a pair do the
+// merge (device-wide fence + counter) was measured slower than the extra launch, 58.6 vs 53.3 us, because the
+// fences act on whole caches.
+//
+// Two forms.  With the exact normalisation (lse_mode 0) the step is front / pool / attend / merge, described at the
+// kernels ("three-stage form" below): the blocks Eq. 2 always keeps are attended beside the score computation,
+// normalisation and max-pooling are spread over many workgroups, and the selection itself is repeated by each
+// attend workgroup, so no kernel of the chain works through a pair alone.  With the LSE Approximation (Sec. 3.4) it
+// is the older chain
 //   scores  : grid (key chunks, pairs)  logits of 128 compressed keys x 16 heads per workgroup, written once
 //             as log2-domain logits, plus per-chunk (max, sum) partials of the softmax normaliser
-//   select  : grid (pairs)              one 1024-thread workgroup per pair merges the partials into the normaliser
-//             (with the LSE Approximation: forms it from means of four logits, the coarse keys' logits),
-//             sums the normalised scores of the 16 heads (Eq. 5) into LDS, max-pools them to blocks (Eq. 6) and
-//             selects (Eq. 2) with a workgroup-wide radix select: a single wavefront per row, as in prefill, would
-//             leave the chip empty and spend ~16 us on latency here.  The score row of a pair must fit in LDS
-//             (contexts up to ~419K tokens).
+//   select  : grid (pairs)              one 1024-thread workgroup per pair forms the normaliser from means of four
+//             logits (the coarse keys' logits), sums the normalised scores of the 16 heads (Eq. 5) into LDS,
+//             max-pools them to blocks (Eq. 6) and selects (Eq. 2) with a workgroup-wide radix select.  The score
+//             row of a pair must fit in LDS (contexts up to ~419K tokens).
 //   attend  : grid (splits, pairs)      one wavefront per selected block: K fragments straight from global
 //             memory into MFMA operands, V through a 16 KB LDS tile (MFMA unit shared with prefill); the
 //             eight partial results of a workgroup are merged in LDS
 //   merge   : grid (pairs)              log-sum-exp merge of the per-split partial outputs, writes O and lse
 // K^{C1} is float32; it is split into a bf16 high part and a bf16 residual in registers and both products
-// are accumulated, so the logits carry ~16 mantissa bits of K^{C1} (as in the prefill score kernel).
+// are accumulated, so the logits carry ~16 mantissa bits of K^{C1}.
 #include "attn_unit.h"
 #include "topk_row.h"
 
@@ -51,6 +55,30 @@ struct DecArgs {
     float *lse;        // [batch][hq] or nullptr
     int zs, nchunk, nsplit;
     int lse_mode;      // 1: normalise with the log-sum-exp over the four times coarser keys (LSE Approximation, Sec. 3.4)
+    // three-stage form (front / pool / attend + merge):
+    uint32_t *pk;      // [pairs][pk_cap] pooled score of every block (bit pattern of a float >= 0; 0 for forced blocks)
+    int pk_cap;
+    int fsplit;        // partial-output slots taken by the forced blocks (attended beside the scores)
+    int nslot;         // fsplit + nsplit
+};
+
+// Which blocks the newest token of an L-token sequence always keeps (Eq. 2: the first n_init and the last n_local
+// blocks), and how many of the others the top-k adds.
+struct Forced {
+    int bt, nblk, f_init, f_lo, n_forced, n_rest, kr;
+    __host__ __device__ Forced(const TopkArgs &tk, int L) {
+        bt = (L - 1) / kBlock;
+        nblk = bt + 1;
+        f_init = tk.n_init < nblk ? tk.n_init : nblk;
+        f_lo = bt - tk.n_local + 1 > 0 ? bt - tk.n_local + 1 : 0;
+        n_forced = f_init + (bt - f_lo + 1) - (f_init > f_lo ? f_init - f_lo : 0);
+        n_rest = nblk - n_forced;
+        const int want = tk.topk_total - tk.n_init - tk.n_local;
+        kr = want < n_rest ? want : n_rest;
+    }
+    // e-th forced block in ascending order, e < n_forced
+    __host__ __device__ int forced_block(int e) const { return e < f_init ? e : (f_lo > f_init ? f_lo : f_init) + (e - f_init); }
+    __host__ __device__ bool is_forced(int j) const { return j < f_init || j >= f_lo; }
 };
 
 // reductions over the 16 lanes of a row (lanes with equal lane / 16), result in every lane, without LDS: swaps inside
@@ -83,8 +111,7 @@ __device__ inline float rows_sum(float x) {
 }
 
 // ------------------------------------------------------------------------------------------ scores
-__global__ void __launch_bounds__(256) dec_scores_kernel(DecArgs a) {
-    const int chunk = blockIdx.x, pair = blockIdx.y;
+__device__ inline void score_chunk(const DecArgs &a, int chunk, int pair) {
     const int b = pair / a.hkv, h = pair - b * a.hkv;
     const int L = a.ctx[b];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -170,6 +197,8 @@ __global__ void __launch_bounds__(256) dec_scores_kernel(DecArgs a) {
         }
     }
 }
+
+__global__ void __launch_bounds__(256) dec_scores_kernel(DecArgs a) { score_chunk(a, blockIdx.x, blockIdx.y); }
 
 // ------------------------------------------------------------------------------------------ select
 // Stages 2b-3 for one (sequence, KV head) pair in one workgroup.  Selection rule and tie handling are those of
@@ -390,22 +419,17 @@ __global__ void __launch_bounds__(SEL_THREADS) dec_select_kernel(DecArgs a, int 
 // ------------------------------------------------------------------------------------------ attend + merge
 constexpr int AW = 8;              // waves (= selected blocks) per attend workgroup
 
-__global__ void __launch_bounds__(AW * 64) dec_attn_kernel(DecArgs a) {
-    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];     // AW V tiles of 16 KB, one per wave
-    __shared__ float wm[AW][16], wl[AW][16];
-    const int split = blockIdx.x, pair = blockIdx.y;
+// Up to NWV waves of a workgroup attend to one block each (j < 0: none) for the newest token of (sequence b, KV head
+// h); the partial results are merged in LDS and written as partial `slot` of the pair.  Every thread of the
+// workgroup calls this (barriers inside); waves past NWV only help with the final sum.  smem: NWV tiles of 16 KB.
+template <int NWV>
+__device__ inline void attend_partial(const DecArgs &a, int pair, int slot, int j, uint16_t *smem, float (*wm)[16],
+                                      float (*wl)[16]) {
     const int b = pair / a.hkv, h = pair - b * a.hkv;
     const int L = a.ctx[b];
     const int t = L - 1, bt = t / kBlock;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m16 = lane & 15, g = lane >> 4;
-    const bool dense = L < a.tk.dense_below;
-    const int e = split * AW + w;                                         // entry of the block list
-    int j = -1;
-    if (dense) j = e <= bt ? e : -1;
-    else if (e < a.tk.topk_total) j = a.idx[(int64_t)pair * a.tk.topk_total + e];
-    if (j > bt) j = -1;
-    uint16_t *vtile = smem + w * TILE_ELEMS;
     const uint16_t *kb = a.k + (int64_t)b * a.kv_batch_stride + (int64_t)h * a.kv_head_stride;
     const uint16_t *vb = a.v + (int64_t)b * a.kv_batch_stride + (int64_t)h * a.kv_head_stride;
     const float c = a.scale * LOG2E;
@@ -414,7 +438,8 @@ __global__ void __launch_bounds__(AW * 64) dec_attn_kernel(DecArgs a) {
     for (int dt = 0; dt < 8; ++dt) st.o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     st.m = -INFINITY;
     st.l = 0.f;
-    if (j >= 0) {
+    if (w < NWV && j >= 0) {
+        uint16_t *vtile = smem + w * TILE_ELEMS;
 #pragma unroll
         for (int qi = 0; qi < 16; ++qi) load_piece(vb, a.kv_tok_stride, j, L, vtile, qi, lane);
         // K fragments as MFMA A operands, straight from global memory: row 16*kt + m16, dims 32*s + 8*g ..
@@ -447,18 +472,17 @@ __global__ void __launch_bounds__(AW * 64) dec_attn_kernel(DecArgs a) {
         st.l += __shfl_xor(st.l, 16);
         st.l += __shfl_xor(st.l, 32);
     }
-    if (g == 0) { wm[w][m16] = st.m; wl[w][m16] = st.l; }
+    if (w < NWV && g == 0) { wm[w][m16] = st.m; wl[w][m16] = st.l; }
     __syncthreads();                                  // every wave is done with its V tile: reuse as scratch
     // Each wave scales its partial to the workgroup's reference of its lane's head and lays it down as it sits in
-    // registers (slot dt * 64 + lane holds dims 16 dt + 4 (lane / 16) .. + 3 of head lane % 16); one thread per slot
-    // then adds the AW partials: 16-byte LDS traffic only, no exponentials in the sum.
-    static_assert(AW * 64 * 4 == OPART, "one 16-byte slot of the partial output per thread");
-    {
+    // registers (slot dt * 64 + lane holds dims 16 dt + 4 (lane / 16) .. + 3 of head lane % 16); the threads then
+    // add the NWV partials slot by slot: 16-byte LDS traffic only, no exponentials in the sum.
+    if (w < NWV) {
         float mm = wm[0][m16];
 #pragma unroll
-        for (int k = 1; k < AW; ++k) mm = fmaxf(mm, wm[k][m16]);
+        for (int k = 1; k < NWV; ++k) mm = fmaxf(mm, wm[k][m16]);
         const float wgt = st.m == -INFINITY ? 0.f : fast_exp2((st.m - mm) * c);
-        float4 *scr4 = reinterpret_cast<float4 *>(smem);           // [AW waves][512 slots]
+        float4 *scr4 = reinterpret_cast<float4 *>(smem);           // [NWV waves][512 slots]
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt)
             scr4[w * (OPART / 4) + dt * 64 + lane] = make_float4(st.o[dt][0] * wgt, st.o[dt][1] * wgt, st.o[dt][2] * wgt, st.o[dt][3] * wgt);
@@ -466,25 +490,305 @@ __global__ void __launch_bounds__(AW * 64) dec_attn_kernel(DecArgs a) {
     __syncthreads();
     {
         const float4 *scr4 = reinterpret_cast<const float4 *>(smem);
-        float4 acc = scr4[tid];
+        float4 *dst = reinterpret_cast<float4 *>(a.opart + ((int64_t)pair * a.nslot + slot) * OPART);
+        for (int i = tid; i < OPART / 4; i += (int)blockDim.x) {
+            float4 acc = scr4[i];
 #pragma unroll
-        for (int k = 1; k < AW; ++k) {
-            const float4 x = scr4[k * (OPART / 4) + tid];
-            acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+            for (int k = 1; k < NWV; ++k) {
+                const float4 x = scr4[k * (OPART / 4) + i];
+                acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+            }
+            dst[i] = acc;
         }
-        reinterpret_cast<float4 *>(a.opart + ((int64_t)pair * a.nsplit + split) * OPART)[tid] = acc;
     }
     if (tid < 16) {
         float mm = -INFINITY;
-        for (int k = 0; k < AW; ++k) mm = fmaxf(mm, wm[k][tid]);
+        for (int k = 0; k < NWV; ++k) mm = fmaxf(mm, wm[k][tid]);
         float ll = 0.f;
-        for (int k = 0; k < AW; ++k)
+        for (int k = 0; k < NWV; ++k)
             if (wm[k][tid] != -INFINITY) ll += wl[k][tid] * fast_exp2((wm[k][tid] - mm) * c);
-        float *ml = a.mlpart + ((int64_t)pair * a.nsplit + split) * 32;
+        float *ml = a.mlpart + ((int64_t)pair * a.nslot + slot) * 32;
         ml[tid * 2] = mm;
         ml[tid * 2 + 1] = ll;
     }
+}
 
+__global__ void __launch_bounds__(AW * 64) dec_attn_kernel(DecArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];     // AW V tiles of 16 KB, one per wave
+    __shared__ float wm[AW][16], wl[AW][16];
+    const int split = blockIdx.x, pair = blockIdx.y;
+    const int b = pair / a.hkv;
+    const int L = a.ctx[b];
+    const int bt = (L - 1) / kBlock;
+    const int e = split * AW + (int)(threadIdx.x >> 6);                    // entry of the block list
+    int j = -1;
+    if (L < a.tk.dense_below) j = e <= bt ? e : -1;
+    else if (e < a.tk.topk_total) j = a.idx[(int64_t)pair * a.tk.topk_total + e];
+    if (j > bt) j = -1;
+    attend_partial<AW>(a, pair, split, j, smem, wm, wl);
+}
+
+// =========================================================================================== three-stage form
+// The four kernels above are a chain of two memory bursts (compressed keys, then selected K/V blocks) separated by a
+// selection that one workgroup per pair works through alone.  For the exact normalisation (lse_mode 0) the same
+// step runs as
+//   front  : grid (key chunks + forced splits, pairs)  the scores workgroups of above, and beside them -- independent
+//            data, same launch -- workgroups that already attend to the blocks Eq. 2 keeps whatever the scores say
+//            (initial and local blocks: known from the context length alone), two blocks per workgroup
+//   pool   : grid (64-block groups, pairs)   every workgroup merges the pair's chunk partials into the normaliser
+//            (a few KB, redundantly), normalises and group-sums its own keys, max-pools them to its 64 blocks
+//   attend : grid (splits, pairs)  every workgroup first selects (radix select over the pair's <= a few thousand
+//            pooled keys: no trip through memory between selection and attention), then attends to its eight
+//            blocks of the top-k list
+//   merge  : as above, over forced + top-k partials.
+// The serial selection kernel is gone from the chain; what it did is spread over many workgroups (pool) or repeated
+// by each of the few workgroups that need the result (attend).
+constexpr int FW = 2;                       // forced blocks per front workgroup (2 V tiles = the 32 KB of LDS every
+                                            // workgroup of that launch gets, scores workgroups included)
+constexpr int PB = 64;                      // blocks per pool workgroup
+constexpr int kPoolKeysMax = 2048;          // compressed keys a pool workgroup may have to hold (pool_stride * 64 + pool_len)
+
+__global__ void __launch_bounds__(256) dec_front_kernel(DecArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];     // FW V tiles of 16 KB
+    __shared__ float wm[FW][16], wl[FW][16];
+    const int pair = blockIdx.y;
+    if ((int)blockIdx.x < a.nchunk) {
+        score_chunk(a, blockIdx.x, pair);
+        return;
+    }
+    const int f = (int)blockIdx.x - a.nchunk;             // forced split
+    const int L = a.ctx[pair / a.hkv];
+    const Forced fo(a.tk, L);
+    const int e = f * FW + (int)(threadIdx.x >> 6);
+    // (dense sequences attend to every block in the attend kernel; their forced slots stay empty)
+    const int j = (L >= a.tk.dense_below && (int)(threadIdx.x >> 6) < FW && e < fo.n_forced) ? fo.forced_block(e) : -1;
+    attend_partial<FW>(a, pair, f, j, smem, wm, wl);
+}
+
+__global__ void __launch_bounds__(256) dec_pool_kernel(DecArgs a) {
+    __shared__ float red[16][16][2];
+    __shared__ float lse2[16];
+    __shared__ float sh[kPoolKeysMax];
+    const int pair = blockIdx.y;
+    const int L = a.ctx[pair / a.hkv];
+    if (L < a.tk.dense_below) return;
+    const Forced fo(a.tk, L);
+    if (fo.kr == fo.n_rest) return;                       // everything is kept: no scores needed
+    const int j0 = (int)blockIdx.x * PB;
+    if (j0 >= fo.nblk) return;
+    const int j1 = min(j0 + PB, fo.nblk);
+    const int tid = threadIdx.x;
+    const int v = visible_cmp(L - 1, a.tk.lc, a.tk.sc);
+    // keys this workgroup pools: the union of its blocks' windows, clipped to the visible keys
+    const int k0 = max(a.tk.pool_stride * j0 - a.tk.pool_pad, 0);
+    const int k1 = min(a.tk.pool_stride * (j1 - 1) - a.tk.pool_pad + a.tk.pool_len, v);
+    // their logits are requested first, so that the trip overlaps the merge of the normaliser
+    constexpr int KPT = kPoolKeysMax / 256;
+    const float *zb = a.z + (int64_t)pair * a.zs * G;
+    float4 zr[2][4];                                      // the first two keys of this thread, 16 heads each
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int i = min(k0 + tid + u * 256, max(v - 1, 0));
+        const float4 *zk = reinterpret_cast<const float4 *>(zb + (int64_t)i * G);
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) zr[u][q4] = zk[q4];
+    }
+    {   // log2 of sum_i 2^z per head from the chunk partials: 16 thread groups per head, then 16 -> 1
+        const int head = tid & 15, pg = tid >> 4;
+        const float *pp = a.part + (int64_t)pair * a.nchunk * 32 + head * 2;
+        float mm = -INFINITY, ll = 0.f;
+        for (int ch = pg; ch < a.nchunk; ch += 16) {
+            const float mo = pp[ch * 32], lo = pp[ch * 32 + 1];
+            const float mn = fmaxf(mm, mo);
+            const float ms = mn == -INFINITY ? 0.f : mn;
+            ll = ll * fast_exp2(mm - ms) + lo * fast_exp2(mo - ms);
+            mm = mn;
+        }
+        red[pg][head][0] = mm;
+        red[pg][head][1] = ll;
+        __syncthreads();
+        if (tid < 16) {
+            float m2 = -INFINITY;
+            for (int k = 0; k < 16; ++k) m2 = fmaxf(m2, red[k][tid][0]);
+            float l2 = 0.f;
+            for (int k = 0; k < 16; ++k)
+                if (red[k][tid][0] != -INFINITY) l2 += red[k][tid][1] * fast_exp2(red[k][tid][0] - m2);
+            lse2[tid] = l2 > 0.f ? m2 + __log2f(l2) : INFINITY;
+        }
+        __syncthreads();
+    }
+    // S^shared[i] = sum over the 16 heads of 2^(z[g][i] - lse2[g]) for this workgroup's keys
+    float nl[G];
+#pragma unroll
+    for (int gq = 0; gq < G; ++gq) nl[gq] = lse2[gq];
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) {
+        const int i = k0 + tid + u * 256;
+        if (i < k1) {
+            float4 z4[4];
+            if (u < 2) {
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) z4[q4] = zr[u][q4];
+            } else {
+                const float4 *zk = reinterpret_cast<const float4 *>(zb + (int64_t)i * G);
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) z4[q4] = zk[q4];
+            }
+            float sum = 0.f;
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                sum += (fast_exp2(z4[q4].x - nl[4 * q4]) + fast_exp2(z4[q4].y - nl[4 * q4 + 1])) +
+                       (fast_exp2(z4[q4].z - nl[4 * q4 + 2]) + fast_exp2(z4[q4].w - nl[4 * q4 + 3]));
+            sh[i - k0] = sum;
+        }
+    }
+    __syncthreads();
+    // pooled key of every block of the group (0 for forced blocks: they take no part in the top-k)
+    if (tid < j1 - j0) {
+        const int j = j0 + tid;
+        float m = 0.f;
+        if (!fo.is_forced(j)) {
+            const int lo = a.tk.pool_stride * j - a.tk.pool_pad;
+            for (int u = 0; u < a.tk.pool_len; ++u) {
+                const int i = lo + u;
+                if (i >= 0 && i < v) m = fmaxf(m, sh[i - k0]);
+            }
+        }
+        a.pk[(int64_t)pair * a.pk_cap + j] = __float_as_uint(m);
+    }
+}
+
+// exclusive prefix count of `flag` over the workgroup's threads in thread order (+ total); two barriers
+template <int NWAVES>
+__device__ inline int wg_prefix_count_n(bool flag, int *wave_tot, int tid, int &total) {
+    const int lane = tid & 63, w = tid >> 6;
+    const uint64_t b = __ballot(flag);
+    const int within = __popcll(b & ((1ull << lane) - 1ull));
+    __syncthreads();                                   // previous readers of wave_tot are done
+    if (lane == 0) wave_tot[w] = __popcll(b);
+    __syncthreads();
+    int before = 0, tot = 0;
+#pragma unroll
+    for (int k = 0; k < NWAVES; ++k) {
+        const int t = wave_tot[k];
+        before += k < w ? t : 0;
+        tot += t;
+    }
+    total = tot;
+    return before + within;
+}
+
+constexpr int kSelMax = 1024;               // top-k entries (topk_total <= 1024)
+constexpr int kPkLds = 4096;                // pooled keys kept in LDS (contexts up to 262144 tokens; longer: re-read)
+
+__global__ void __launch_bounds__(AW * 64) dec_attn2_kernel(DecArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];     // AW V tiles of 16 KB, one per wave
+    __shared__ float wm[AW][16], wl[AW][16];
+    __shared__ int hist[4][256];
+    __shared__ int wave_tot[AW];
+    __shared__ int sel[kSelMax];            // the top-k blocks (without the forced ones), ascending
+    __shared__ uint32_t spk[kPkLds];        // the pair's pooled keys (read five times: four radix passes, one emission)
+    __shared__ uint32_t s_prefix;
+    __shared__ int s_k;
+    constexpr int NT = AW * 64;
+    const int split = blockIdx.x, pair = blockIdx.y;
+    const int b = pair / a.hkv;
+    const int L = a.ctx[b];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const Forced fo(a.tk, L);
+    const bool dense = L < a.tk.dense_below;
+    int32_t *out = a.idx != nullptr ? a.idx + (int64_t)pair * a.tk.topk_total : nullptr;
+    int j = -1;
+    const int e = split * AW + w;
+    if (dense) {
+        j = e <= fo.bt ? e : -1;
+        if (out != nullptr && split == 0)
+            for (int i = tid; i < a.tk.topk_total; i += NT) out[i] = -1;
+    } else if (fo.kr == fo.n_rest) {
+        // everything up to the query's block is kept: the blocks between the initial and the local ones
+        j = e < fo.kr ? fo.f_init + e : -1;
+        if (out != nullptr && split == 0)
+            for (int i = tid; i < a.tk.topk_total; i += NT) out[i] = i < fo.nblk ? i : -1;
+    } else {
+        if (split * AW >= fo.kr && !(out != nullptr && split == 0)) {
+            j = -1;                                        // nothing for this workgroup: an empty partial
+        } else {
+            // ---- radix select (4 x 8 bits) of the kr-th largest pooled key among the live blocks; selection rule
+            // and tie order as in the prefill: keys above it, then the first `need` keys equal to it by block number
+            const uint32_t *pk = a.pk + (int64_t)pair * a.pk_cap;
+            if (fo.nblk <= kPkLds) {
+                for (int i = tid; i < fo.nblk; i += NT) spk[i] = pk[i];
+                pk = spk;
+            }
+            for (int i = tid; i < 4 * 256; i += NT) (&hist[0][0])[i] = 0;
+            if (tid == 0) { s_prefix = 0u; s_k = fo.kr; }
+            __syncthreads();
+            for (int pass = 3; pass >= 0; --pass) {
+                const uint32_t prefix = s_prefix;
+                const int hi_shift = 8 * (pass + 1);
+                for (int jb = tid; jb < fo.nblk; jb += NT) {
+                    if (fo.is_forced(jb)) continue;
+                    const uint32_t key = pk[jb];
+                    if (pass == 3 || (key >> hi_shift) == prefix) atomicAdd(&hist[pass][(key >> (8 * pass)) & 255u], 1);
+                }
+                __syncthreads();
+                if (w == 0) {
+                    // lane l owns digits 4l .. 4l+3; above = number of keys with a larger digit
+                    const int k = s_k;
+                    int c[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) c[u] = hist[pass][4 * lane + u];
+                    const int mine = c[0] + c[1] + c[2] + c[3];
+                    int run = mine;                          // inclusive suffix sum over lanes
+#pragma unroll
+                    for (int o = 1; o < 64; o <<= 1) {
+                        const int other = __shfl_down(run, o);
+                        if (lane + o < 64) run += other;
+                    }
+                    int above = run - mine;
+#pragma unroll
+                    for (int u = 3; u >= 0; --u) {
+                        if (above < k && k <= above + c[u]) {
+                            s_prefix = (prefix << 8) | (uint32_t)(4 * lane + u);
+                            s_k = k - above;
+                        }
+                        above += c[u];
+                    }
+                }
+                __syncthreads();
+            }
+            const uint32_t thr = s_prefix;               // the kr-th largest key; `need` of the keys equal to it are taken
+            const int need = s_k;
+            int written = 0, eq_seen = 0;
+            for (int base = 0; base < fo.nblk; base += NT) {
+                const int jb = base + tid;
+                const bool lv = jb < fo.nblk && !fo.is_forced(jb);
+                const uint32_t key = lv ? pk[jb] : 0u;
+                int eq_tot, sel_tot;
+                const int eq_rank = eq_seen + wg_prefix_count_n<AW>(lv && key == thr, wave_tot, tid, eq_tot);
+                const bool take = lv && (key > thr || (key == thr && eq_rank < need));
+                const int pos = written + wg_prefix_count_n<AW>(take, wave_tot, tid, sel_tot);
+                if (take) sel[pos] = jb;
+                written += sel_tot;
+                eq_seen += eq_tot;
+            }
+            __syncthreads();
+            j = e < fo.kr ? sel[e] : -1;
+            if (out != nullptr && split == 0) {
+                // the whole list, ascending: initial blocks, the top-k, the local blocks, then -1
+                const int n_loc = fo.n_forced - fo.f_init;
+                for (int i = tid; i < a.tk.topk_total; i += NT) {
+                    int val = -1;
+                    if (i < fo.f_init) val = i;
+                    else if (i < fo.f_init + fo.kr) val = sel[i - fo.f_init];
+                    else if (i < fo.f_init + fo.kr + n_loc) val = fo.forced_block(i - fo.kr);
+                    out[i] = val;
+                }
+            }
+        }
+    }
+    if (j > fo.bt) j = -1;
+    attend_partial<AW>(a, pair, a.fsplit + split, j, smem, wm, wl);
 }
 
 // ------------------------------------------------------------------------------------------ merge
@@ -496,18 +800,18 @@ __global__ void __launch_bounds__(256) dec_merge_kernel(DecArgs a) {
     const int tid = threadIdx.x;
     const int head = tid & 15, dg = tid >> 4;          // 16 heads x 16 groups of 8 dims
     const float c = a.scale * LOG2E;
-    const float *ml = a.mlpart + (int64_t)pair * a.nsplit * 32 + head * 2;
+    const float *ml = a.mlpart + (int64_t)pair * a.nslot * 32 + head * 2;
     // dims 8 dg .. + 7 of this head are two 16-byte slots of a partial (see DecArgs::opart)
-    const float4 *opb = reinterpret_cast<const float4 *>(a.opart + (int64_t)pair * a.nsplit * OPART) +
+    const float4 *opb = reinterpret_cast<const float4 *>(a.opart + (int64_t)pair * a.nslot * OPART) +
                         (dg >> 1) * 64 + (dg & 1) * 32 + head;
     float mm = -INFINITY, ll = 0.f, o[8];
 #pragma unroll
     for (int e2 = 0; e2 < 8; ++e2) o[e2] = 0.f;
-    for (int s0 = 0; s0 < a.nsplit; s0 += 8) {
+    for (int s0 = 0; s0 < a.nslot; s0 += 8) {
         float ms[8], ls[8], ov[8][8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int s = min(s0 + u, a.nsplit - 1);        // past the end: re-read the last split, weight 0 below
+            const int s = min(s0 + u, a.nslot - 1);        // past the end: re-read the last split, weight 0 below
             ms[u] = ml[s * 32];
             ls[u] = ml[s * 32 + 1];
             const float4 lo4 = opb[(int64_t)s * (OPART / 4)], hi4 = opb[(int64_t)s * (OPART / 4) + 16];
@@ -517,7 +821,7 @@ __global__ void __launch_bounds__(256) dec_merge_kernel(DecArgs a) {
         float cm = mm;
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            if (s0 + u < a.nsplit) cm = fmaxf(cm, ms[u]);
+            if (s0 + u < a.nslot) cm = fmaxf(cm, ms[u]);
         if (cm == -INFINITY) continue;                      // nothing attended to in these splits
         const float resc = mm == -INFINITY ? 0.f : fast_exp2((mm - cm) * c);
         ll *= resc;
@@ -525,7 +829,7 @@ __global__ void __launch_bounds__(256) dec_merge_kernel(DecArgs a) {
         for (int e2 = 0; e2 < 8; ++e2) o[e2] *= resc;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const float wg = s0 + u < a.nsplit && ms[u] != -INFINITY ? fast_exp2((ms[u] - cm) * c) : 0.f;
+            const float wg = s0 + u < a.nslot && ms[u] != -INFINITY ? fast_exp2((ms[u] - cm) * c) : 0.f;
             ll += ls[u] * wg;
 #pragma unroll
             for (int e2 = 0; e2 < 8; ++e2) o[e2] += ov[u][e2] * wg;
@@ -547,7 +851,16 @@ inline size_t align_up(size_t x, size_t al) { return (x + al - 1) / al * al; }
 struct DecLayout {
     int zs, nchunk, nsplit;
     size_t off_part, off_idx, off_opart, off_ml, total;
+    // three-stage form
+    bool staged;
+    int fsplit, nslot, pk_cap;
+    size_t off_pk;
 };
+
+// the three-stage form covers the exact normalisation and pooling windows whose keys fit a pool workgroup
+bool staged_params(const infllmv2_params *p) {
+    return p->lse_mode == 0 && (int64_t)p->pool_stride * PB + p->pool_len <= kPoolKeysMax;
+}
 
 DecLayout dec_layout(const infllmv2_params *p, int batch, int max_ctx, int dense_blocks) {
     DecLayout d;
@@ -556,17 +869,27 @@ DecLayout dec_layout(const infllmv2_params *p, int batch, int max_ctx, int dense
     d.zs = (int)align_up((size_t)max_nc + 4, 4);
     d.nchunk = (max_nc + CK - 1) / CK;
     if (d.nchunk < 1) d.nchunk = 1;
-    const int entries = p->topk_total > dense_blocks ? p->topk_total : dense_blocks;
+    d.staged = staged_params(p);
+    // entries of the attend launch: the whole list (forced blocks too) in the four-kernel form, the top-k part in
+    // the three-stage form; a dense sequence attends to all its blocks there either way
+    const int listed = d.staged ? p->topk_total - p->n_init - p->n_local : p->topk_total;
+    const int entries = listed > dense_blocks ? listed : dense_blocks;
     d.nsplit = (entries + AW - 1) / AW;
+    if (d.nsplit < 1) d.nsplit = 1;
+    d.fsplit = d.staged ? (p->n_init + p->n_local + FW - 1) / FW : 0;
+    d.nslot = d.fsplit + d.nsplit;
+    d.pk_cap = (int)align_up((size_t)(max_ctx + kBlock - 1) / kBlock + 4, 4);
     size_t off = align_up(pairs * G * d.zs * sizeof(float), 256);
     d.off_part = off;
     off += align_up(pairs * d.nchunk * 32 * sizeof(float), 256);
     d.off_idx = off;
     off += align_up(pairs * p->topk_total * sizeof(int32_t), 256);
+    d.off_pk = off;
+    off += d.staged ? align_up(pairs * d.pk_cap * sizeof(uint32_t), 256) : 0;
     d.off_opart = off;
-    off += align_up(pairs * d.nsplit * OPART * sizeof(float), 256);
+    off += align_up(pairs * d.nslot * OPART * sizeof(float), 256);
     d.off_ml = off;
-    off += align_up(pairs * d.nsplit * 32 * sizeof(float), 256);
+    off += align_up(pairs * d.nslot * 32 * sizeof(float), 256);
     d.total = off;
     return d;
 }
@@ -625,6 +948,26 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     a.nchunk = d.nchunk;
     a.nsplit = d.nsplit;
     a.lse_mode = p->lse_mode;
+    a.pk = (uint32_t *)(base + d.off_pk);
+    a.pk_cap = d.pk_cap;
+    a.fsplit = d.fsplit;
+    a.nslot = d.nslot;
+    const size_t attn_lds = (size_t)AW * TILE_ELEMS * sizeof(uint16_t);
+    if (d.staged) {
+        // Larger-than-default dynamic LDS has to be enabled per kernel; the same fixed limit is set on every call,
+        // so nothing has to be remembered between calls.
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(dec_attn2_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds) != hipSuccess)
+            return INFLLMV2_ERR_HIP;
+        a.idx = idx_out;                     // written by the attend kernel only when the caller wants the list
+        const int groups = ((max_ctx + kBlock - 1) / kBlock + PB - 1) / PB;
+        hipLaunchKernelGGL(dec_front_kernel, dim3(d.nchunk + d.fsplit, pairs), dim3(256),
+                           (size_t)FW * TILE_ELEMS * sizeof(uint16_t), stream, a);
+        hipLaunchKernelGGL(dec_pool_kernel, dim3(groups, pairs), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(dec_attn2_kernel, dim3(d.nsplit, pairs), dim3(AW * 64), attn_lds, stream, a);
+        hipLaunchKernelGGL(dec_merge_kernel, dim3(pairs), dim3(256), 0, stream, a);
+        return hip_status(hipGetLastError());
+    }
 
     // group sum + max-pool + top-k run as one workgroup per pair with the score row in LDS
     const int sh_cap = (d.zs + 3) / 4 * 4;
@@ -633,7 +976,6 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     if (sel_lds > kSelLdsMax) return INFLLMV2_ERR_UNSUPPORTED;     // before anything is launched
     // Larger-than-default dynamic LDS has to be enabled per kernel; the same fixed limits are set on every call, so
     // nothing has to be remembered between calls.
-    const size_t attn_lds = (size_t)AW * TILE_ELEMS * sizeof(uint16_t);
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(dec_select_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSelLdsMax) != hipSuccess ||
         hipFuncSetAttribute(reinterpret_cast<const void *>(dec_attn_kernel),
