@@ -54,11 +54,18 @@ def main() -> int:
     ap.add_argument("--dense-steps", type=int, default=1, help="timed runs of the dense path at the same shape (0 = skip)")
     ap.add_argument("--backward-steps", type=int, default=1, help="timed runs of the backward of stage 4 (0 = skip)")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-budgets", action="store_true", help="skip the paper's own selection budgets on the same inputs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=6144, help="query rows per KV head the oracle is timed on")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="instead of the default line: the paper's own benchmark shapes (Sec. 4.3: 16 selected blocks "
                          "at 32k..128k, and |I| = 96 at 128k), one JSON object")
+    ap.add_argument("--lib", default=None,
+                    help="time libinfllmv2_<NAME>.so (python paper_2509_24663_amd/build.py --variant NAME DEFINE ...) "
+                         "instead of the library: timing experiments only, nothing is checked")
+    ap.add_argument("--probe-spread", action="store_true",
+                    help="instead of the default line: the attention kernel on synthetic block lists whose entries have "
+                         "four consumers each, spread over the SIMDs in three ways (timing only)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, to scale PMC byte counters)")
     args = ap.parse_args()
@@ -68,6 +75,9 @@ def main() -> int:
 
     import torch
 
+    if args.lib:
+        import paper_2509_24663_amd.binding as _binding
+        _binding._LIB_PATH = os.path.join(ROOT, "paper_2509_24663_amd", f"libinfllmv2_{args.lib}.so")
     import paper_2509_24663_amd as m
     import synth
 
@@ -76,6 +86,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.paper_sweep:
         print(json.dumps(paper_sweep(torch, m, synth, args.steps)))
+        return 0
+    if args.probe_spread:
+        print(json.dumps(probe_spread(torch, m, args.steps)))
         return 0
     cfg = synth.CONFIGS[args.workload]
     gp = m.Params.from_config(cfg)
@@ -127,6 +140,12 @@ def main() -> int:
         for i, s in enumerate(stage_names):
             acc[s] += ev[i].elapsed_time(ev[i + 1])
     stage_ms = {s: acc[s] / args.steps for s in stage_names}
+
+    if args.lib:        # a timing variant: stage times only, nothing compared or derived
+        print(json.dumps({"lib": args.lib, "ms_per_layer": {**{s: round(stage_ms[s], 4) for s in stage_names},
+                                                              "total": round(step_ms, 4)},
+                          "dense_attn_ms": dense_ms_only(torch, m, gp, q, k, v, si, bufs) if args.dense_steps else None}))
+        return 0
 
     # the same two stages with S^shared written per compressed key (identical block lists)
     s_shared = m.block_scores(gp, q, bufs["kc"], si, bufs["cu_seqlens_c"], workspace=bufs["ws_scores"])
@@ -256,7 +275,7 @@ def main() -> int:
     # (Sec. 4.3: 16 selected blocks; Sec. 4.1: |I| = 96 = 1 + 32 + 63), exact and with the LSE Approximation, on the
     # same inputs; the full sweep over lengths is bench.py --paper-sweep
     budgets = None
-    if args.workload == "C3":
+    if args.workload == "C3" and not args.no_budgets:
         budgets = {"what": "ms per layer on the same 128K inputs with the paper's block budgets (block selection = "
                            "stages 1-3); the paper's figures are for other hardware and are context only",
                    "paper_context": {"block_selection_ms_128k_16_blocks": {"A100": {"exact": 75.36, "lse_approx": 56.59},
@@ -326,6 +345,66 @@ def main() -> int:
     }
     print(json.dumps(line))
     return 0
+
+
+def dense_ms_only(torch, m, gp, q, k, v, si, bufs):
+    od, ld = torch.empty_like(q), torch.empty_like(bufs["lse"])
+    m.dense_attn_fwd(gp, q, k, v, si, out=od, lse=ld, workspace=bufs["ws_attn"])
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch, 2)
+    e0.record()
+    m.dense_attn_fwd(gp, q, k, v, si, out=od, lse=ld, workspace=bufs["ws_attn"])
+    e1.record()
+    torch.cuda.synchronize()
+    return round(e0.elapsed_time(e1), 3)
+
+
+def probe_spread(torch, m, steps: int):
+    """How much the attention tile kernel cares where an entry's consumers sit.  64K tokens, 64 blocks per token: per
+    16-token tile 14 entries shared by all tokens and 196 entries with four consumers each -- one per SIMD ("spread"),
+    four neighbouring tokens ("adjacent"), or four tokens of one SIMD ("same_simd").  Same union size, same number of
+    (token, block) units, same loads in all three."""
+    n, hq, hkv, d, K = 65536, 32, 2, 128, 64
+    gp = m.Params.make("bf16", hq, hkv, d, n_init=1, n_local=8, topk_total=K)
+    g = torch.Generator(device="cuda").manual_seed(1)
+    q = torch.randn((n, hq, d), generator=g, device="cuda").to(torch.bfloat16)
+    k = torch.randn((hkv, n, d), generator=g, device="cuda").to(torch.bfloat16)
+    v = torch.randn((hkv, n, d), generator=g, device="cuda").to(torch.bfloat16)
+    si = m.SeqInfo([0, n])
+
+    def build(mode):
+        t = np.arange(n)
+        bt, w = t // 64, t % 16
+        cols = [np.zeros(n, np.int64)] + [np.maximum(bt - i, 0) for i in range(8)] + [np.maximum(bt - 9 - i, 0) for i in range(5)]
+        base = np.maximum(bt - 214, 1)
+        for c in range(49):
+            r, a = w % 4, w // 4
+            e = 4 * c + {"spread": (a - r) % 4, "same_simd": r, "adjacent": a}[mode]
+            cols.append(np.minimum(base + e, np.maximum(bt - 15, 0)))
+        cols.append(np.full(n, np.iinfo(np.int64).max))
+        arr = np.sort(np.stack(cols[:K], axis=1), axis=1)
+        dup = np.zeros_like(arr, bool)
+        dup[:, 1:] = arr[:, 1:] == arr[:, :-1]
+        arr = np.sort(np.where(dup, np.iinfo(np.int64).max, arr), axis=1)
+        arr = np.where(arr == np.iinfo(np.int64).max, -1, arr).astype(np.int32)
+        return torch.from_numpy(np.broadcast_to(arr, (hkv, n, K)).copy()).cuda()
+
+    out, lse = torch.empty_like(q), torch.empty((hq, n), device="cuda")
+    ws = torch.empty(m.workspace_bytes(m.OP_SPARSE_ATTN_FWD, gp, 1, n, n), dtype=torch.uint8, device="cuda")
+    res = {"what": "sparse_attn_fwd, 65536 tokens, synthetic block lists (timing only)"}
+    for mode in ("spread", "adjacent", "same_simd"):
+        idx = build(mode)
+        units = int((idx >= 0).sum())
+        m.sparse_attn_fwd(gp, q, k, v, idx, si, out=out, lse=lse, workspace=ws)
+        torch.cuda.synchronize()
+        e0, e1 = _events(torch, 2)
+        e0.record()
+        for _ in range(steps):
+            m.sparse_attn_fwd(gp, q, k, v, idx, si, out=out, lse=lse, workspace=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        res[mode] = {"ms": round(e0.elapsed_time(e1) / steps, 3), "token_block_units": units}
+    return res
 
 
 def budget_row(torch, m, q, k, v, si, n_init, n_local, total, steps, dense_ms):

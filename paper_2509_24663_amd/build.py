@@ -113,5 +113,41 @@ def build(force: bool = True, jobs: int = 8) -> str:
     return LIB
 
 
+def build_probes() -> str:
+    """The measurement program behind the roofline model (probes/unit_limits.hip): a stand-alone executable."""
+    src = os.path.join(HERE, "probes", "unit_limits.hip")
+    exe = os.path.join(HERE, "probes", "unit_limits")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-inline-asm", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", exe, src]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on unit_limits.hip:\n{r.stdout}")
+    return exe
+
+
+def build_variant(name: str, defines) -> str:
+    """libinfllmv2_<name>.so: the library with extra -D flags, for timing experiments (bench.py --lib <name>).  The
+    timing switches of attn_mfma.hip (ATTN_TIMING_NO_LOADS, ATTN_TIMING_NO_BARRIER) give wrong results by design."""
+    out_dir = os.path.join(OBJ, "variant_" + name)
+    os.makedirs(out_dir, exist_ok=True)
+    objs = []
+    for src in sources():
+        obj = os.path.join(out_dir, src[:-4] + ".o")
+        cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), *[f"-D{d}" for d in defines], "-c", os.path.join(CSRC, src), "-o", obj]
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}")
+        objs.append(obj)
+    lib = os.path.join(HERE, f"libinfllmv2_{name}.so")
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs])
+    return lib
+
+
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv))
+    if "--probes" in sys.argv:
+        print(build_probes())
+    elif "--variant" in sys.argv:          # build.py --variant NAME DEFINE [DEFINE ...]
+        i = sys.argv.index("--variant")
+        print(build_variant(sys.argv[i + 1], sys.argv[i + 2:]))
+    else:
+        print(build(force="--force" in sys.argv))

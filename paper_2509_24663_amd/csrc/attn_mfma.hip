@@ -23,6 +23,10 @@
 //
 // Schedule: the waves of a tile walk the union in lock step, one barrier per interval of two entries, the
 // next interval's blocks landing in the other half of a four-stage LDS buffer meanwhile.
+//
+// Two compile-time switches exist for timing experiments only (a build with either gives wrong results; they are
+// never defined in the library build): ATTN_TIMING_NO_LOADS leaves out the global -> LDS copies, and
+// ATTN_TIMING_NO_BARRIER the barrier that ends an interval.  What the kernel's time is made of is measured with them.
 #include <type_traits>
 
 #include "attn_unit.h"
@@ -179,7 +183,7 @@ struct TileKernel {
                 __syncthreads();
             }
         } else {
-            ni = nblk;
+            ni = SLOTS == 2 ? nblk / 2 + 1 : nblk;     // pairs of blocks, the tile's own block alone at the end
         }
         // Interval i -> its blocks and consumer masks (unused slot: block NONE, mask 0).  With SLOTS == 2 an
         // interval covers two consecutive entries of the union, so that a SIMD usually has two or more units to
@@ -191,7 +195,12 @@ struct TileKernel {
             return make_int2((j0 & 0xffff) | (j1 << 16), (mk0 & 0xffff) | (mk1 << 16));
         };
         auto interval = [&](int i) -> int2 {
-            if (dense) return pack(i, (int)full, NONE, 0);
+            if (dense) {
+                if (SLOTS == 1) return pack(i, (int)full, NONE, 0);
+                if (i == ni - 1) return pack(ne - 1, (int)full, NONE, 0);
+                const int j1 = 2 * i + 1 < ne - 1 ? 2 * i + 1 : NONE;
+                return pack(2 * i, (int)full, j1, j1 != NONE ? (int)full : 0);
+            }
             if (SLOTS == 1) {
                 const int2 r = rec[i];
                 return pack(r.x, r.y, NONE, 0);
@@ -238,7 +247,11 @@ struct TileKernel {
                     k_piece_src(qi, lane, row, chunk);
                     off = (uint32_t)(min(row, own_rows - 1) * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
                 }
+#ifndef ATTN_TIMING_NO_LOADS
                 async_copy16(base, off, dst);
+#else
+                (void)base; (void)off; (void)dst;       // timing experiment only (results are garbage)
+#endif
             }
         };
         auto issue_interval = [&](int2 r, int buf) {
@@ -290,7 +303,9 @@ struct TileKernel {
             if ((mk0 >> w) & 1u) unit<OWN>(st, stage, kx, vx, lane, t0 + w - j0 * kBlock);
             if (SLOTS == 2 && ((mk1 >> w) & 1u)) unit<false>(st, stage + STAGE_ELEMS * 2, kx, vx, lane, 0);
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);        // this wave's pieces of the next interval have landed
+#ifndef ATTN_TIMING_NO_BARRIER
             __syncthreads();
+#endif
         };
         for (int i = 0; i < ni - 1; ++i) step(std::false_type{}, i);
         if (ni > 0) step(std::true_type{}, ni - 1);
@@ -430,10 +445,10 @@ int launch_attn_mfma(const Launch &L, const void *q, const void *k, const void *
                        a.v, (uint16_t *)ws, L.map, (int)nblk_total);
     int rc = hip_status(hipGetLastError());
     if (rc == INFLLMV2_OK) {
-        // Two entries per interval only when block lists exist; the four stages that needs may not fit next to
-        // the block masks of very long sequences.
+        // Two entries per interval when the four LDS stages that needs fit next to the block masks (with block lists:
+        // sequences up to about 384K tokens; dense calls keep no masks), else one.
         rc = INFLLMV2_ERR_UNSUPPORTED;
-        if (idx != nullptr) rc = launch_tile<16, 2>(L, a, cu_h);
+        rc = launch_tile<16, 2>(L, a, cu_h);
         if (rc == INFLLMV2_ERR_UNSUPPORTED) rc = launch_tile<16, 1>(L, a, cu_h);
     }
     return rc;
