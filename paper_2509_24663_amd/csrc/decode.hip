@@ -681,16 +681,23 @@ __device__ inline int wg_prefix_count_n(bool flag, int *wave_tot, int tid, int &
 constexpr int kSelMax = 1024;               // top-k entries (topk_total <= 1024)
 constexpr int kPkLds = 4096;                // pooled keys kept in LDS (contexts up to 262144 tokens; longer: re-read)
 
-__global__ void __launch_bounds__(AW * 64) dec_attn2_kernel(DecArgs a) {
-    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];     // AW V tiles of 16 KB, one per wave
-    __shared__ float wm[AW][16], wl[AW][16];
-    __shared__ int hist[4][256];
-    __shared__ int wave_tot[AW];
-    __shared__ int sel[kSelMax];            // the top-k blocks (without the forced ones), ascending
-    __shared__ uint32_t spk[kPkLds];        // the pair's pooled keys (read five times: four radix passes, one emission)
+// NW waves (= blocks) per workgroup: 8 when the launch has at most one workgroup per CU anyway, 4 when it has more
+// (64 KB of V tiles instead of 128: two workgroups share a CU and one's selection overlaps the other's loads).
+template <int NW>
+__global__ void __launch_bounds__(NW * 64) dec_attn2_kernel(DecArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];     // NW V tiles of 16 KB, one per wave
+    __shared__ float wm[NW][16], wl[NW][16];
+    __shared__ int wave_tot[NW];
     __shared__ uint32_t s_prefix;
     __shared__ int s_k;
-    constexpr int NT = AW * 64;
+    // the selection's state lives in the V tiles' memory: it is dead before the first tile is requested
+    uint32_t *spk = reinterpret_cast<uint32_t *>(smem);      // [kPkLds] the pair's pooled keys (read five times: four
+                                                             // radix passes, one emission)
+    int *sel = reinterpret_cast<int *>(spk + kPkLds);        // [kSelMax] the top-k blocks (without the forced ones), ascending
+    int(*hist)[256] = reinterpret_cast<int(*)[256]>(sel + kSelMax);     // [4][256]
+    static_assert((kPkLds + kSelMax + 4 * 256) * 4 <= NW * TILE_ELEMS * 2, "selection state must fit in the V tiles");
+    constexpr int AW = NW;                                   // (shadows the four-kernel form's constant below)
+    constexpr int NT = NW * 64;
     const int split = blockIdx.x, pair = blockIdx.y;
     const int b = pair / a.hkv;
     const int L = a.ctx[b];
@@ -785,10 +792,11 @@ __global__ void __launch_bounds__(AW * 64) dec_attn2_kernel(DecArgs a) {
                     out[i] = val;
                 }
             }
+            __syncthreads();                             // the V tiles may overwrite the selection's state now
         }
     }
     if (j > fo.bt) j = -1;
-    attend_partial<AW>(a, pair, a.fsplit + split, j, smem, wm, wl);
+    attend_partial<NW>(a, pair, a.fsplit + split, j, smem, wm, wl);
 }
 
 // ------------------------------------------------------------------------------------------ merge
@@ -853,6 +861,7 @@ struct DecLayout {
     size_t off_part, off_idx, off_opart, off_ml, total;
     // three-stage form
     bool staged;
+    int aw;                     // blocks per attend workgroup
     int fsplit, nslot, pk_cap;
     size_t off_pk;
 };
@@ -874,7 +883,9 @@ DecLayout dec_layout(const infllmv2_params *p, int batch, int max_ctx, int dense
     // the three-stage form; a dense sequence attends to all its blocks there either way
     const int listed = d.staged ? p->topk_total - p->n_init - p->n_local : p->topk_total;
     const int entries = listed > dense_blocks ? listed : dense_blocks;
-    d.nsplit = (entries + AW - 1) / AW;
+    // three-stage form: four blocks per workgroup once eight would give more than one workgroup per CU
+    d.aw = d.staged && pairs * (size_t)((entries + AW - 1) / AW) > 256 ? AW / 2 : AW;
+    d.nsplit = (entries + d.aw - 1) / d.aw;
     if (d.nsplit < 1) d.nsplit = 1;
     d.fsplit = d.staged ? (p->n_init + p->n_local + FW - 1) / FW : 0;
     d.nslot = d.fsplit + d.nsplit;
@@ -956,15 +967,20 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     if (d.staged) {
         // Larger-than-default dynamic LDS has to be enabled per kernel; the same fixed limit is set on every call,
         // so nothing has to be remembered between calls.
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(dec_attn2_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(dec_attn2_kernel<AW>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(dec_attn2_kernel<AW / 2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds / 2) != hipSuccess)
             return INFLLMV2_ERR_HIP;
         a.idx = idx_out;                     // written by the attend kernel only when the caller wants the list
         const int groups = ((max_ctx + kBlock - 1) / kBlock + PB - 1) / PB;
         hipLaunchKernelGGL(dec_front_kernel, dim3(d.nchunk + d.fsplit, pairs), dim3(256),
                            (size_t)FW * TILE_ELEMS * sizeof(uint16_t), stream, a);
         hipLaunchKernelGGL(dec_pool_kernel, dim3(groups, pairs), dim3(256), 0, stream, a);
-        hipLaunchKernelGGL(dec_attn2_kernel, dim3(d.nsplit, pairs), dim3(AW * 64), attn_lds, stream, a);
+        if (d.aw == AW)
+            hipLaunchKernelGGL(dec_attn2_kernel<AW>, dim3(d.nsplit, pairs), dim3(AW * 64), attn_lds, stream, a);
+        else
+            hipLaunchKernelGGL(dec_attn2_kernel<AW / 2>, dim3(d.nsplit, pairs), dim3(AW * 32), attn_lds / 2, stream, a);
         hipLaunchKernelGGL(dec_merge_kernel, dim3(pairs), dim3(256), 0, stream, a);
         return hip_status(hipGetLastError());
     }

@@ -383,6 +383,17 @@ def test_decode_dense_switch_and_ragged(m, oracle):
         assert _check_decode(m, oracle, w, ctx, gp, op, dtype) == 3 * hkv
 
 
+def test_decode_many_pairs_launch_shape(m, oracle):
+    """With more (sequence, KV head) pairs than one workgroup per CU the attend kernel of the three-stage form runs
+    four blocks per workgroup instead of eight (another split count, another partial layout): 40 sequences x 2 KV
+    heads x 7 splits.  Mixed lengths, two of them below the dense threshold."""
+    rng = np.random.default_rng(404)
+    ctx = [int(x) for x in rng.integers(1100, 6000, size=38)] + [700, 64]
+    w = synth.make_decode(ctx, 32, 2, 128, seed=92, dtype="bf16", max_len=6016)
+    gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=8, topk_total=64, dense_threshold=1024)
+    assert _check_decode(m, oracle, w, ctx, gp, op, "bf16") == 38 * 2
+
+
 def test_decode_c4_full_shape(m, oracle):
     """BASELINE config 4 at full size: batch 16, context lengths uniform in [16384, 65536], top-k 64."""
     cfg = synth.CONFIGS["C4"]
