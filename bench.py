@@ -4,8 +4,8 @@
 A "step" is one pass of the whole sparse prefill path -- compress_k, block_scores_pooled, topk_pooled,
 sparse_attn_fwd (stages 2 and 3 in the form with the max-pooling fused into the score kernel; the block lists are
 identical to those of block_scores + topk_blocks, which are timed beside it) -- over one synthetic batch that is
-already resident in HBM.  The default workload is
-BASELINE config 3 (bf16, 131072 tokens, 32 query heads / 2 KV heads, d 128, 64 selected blocks), the one
+already resident in HBM.  The default is
+workload C3 of synth.CONFIGS (bf16, 131072 tokens, 32 query heads / 2 KV heads, d 128, 64 selected blocks), the one
 the headline metric is quoted on.  One JSON line is printed with the whole-step throughput, the per-stage
 times, the roofline of the dominant kernel (HIP-event timed on the launch stream), the library's own dense
 path at the same shape, the decode workload (config 4) and the CPU oracle timed on a bounded sample of rows.

@@ -4,7 +4,7 @@
 // Alg. 2 gives every token a private pass over its selected K/V blocks.  Here a workgroup owns a tile of
 // T consecutive tokens of one KV head instead: it forms the union of the tile's block lists, brings each
 // K/V block of the union into LDS once, and every token that selected the block consumes it from there.
-// Neighbouring tokens share most of their blocks (all init/local blocks, and most top-k blocks), so the
+// Neighbouring tokens share blocks (all init/local blocks, and whichever top-k blocks they agree on), so the
 // gather traffic from L2 / HBM drops by the sharing factor while the arithmetic stays exactly the
 // per-token softmax attention of Alg. 2.
 //
@@ -21,8 +21,8 @@
 // (8 dim tiles x 2 k-steps), whose A operand comes from the V^T tile.  Dense attention is the same kernel
 // with "every block, every token".
 //
-// Schedule: the waves of a tile walk the union in lock step, one barrier per interval of two entries, the
-// next interval's blocks landing in the other half of a four-stage LDS buffer meanwhile.
+// Schedule: the waves of a tile walk the union in lock step, one barrier per interval of two entries (dense: two
+// consecutive blocks), the next interval's blocks landing in the other half of a four-stage LDS buffer meanwhile.
 //
 // Two compile-time switches exist for timing experiments only (a build with either gives wrong results; they are
 // never defined in the library build): ATTN_TIMING_NO_LOADS leaves out the global -> LDS copies, and

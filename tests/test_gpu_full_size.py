@@ -1,4 +1,4 @@
-"""Parity at the full BASELINE sizes, through the same entry points and launch configuration bench.py times.
+"""Parity at the full sizes of the workloads in synth.CONFIGS, through the same entry points and launch configuration bench.py times.
 The oracle cannot afford every row at these sizes, so it is run on a stratified sample of query rows (rows are
 independent: parity on a sampled row is exact for that row): whole query blocks (first, last, random) plus
 random single tokens, per sequence."""

@@ -126,7 +126,7 @@ def _run_prefill_case(m, oracle, w, gp, op, dtype, rows=None, check_stages=True,
 
 # ----------------------------------------------------------------------------------------------- configs
 def test_c1_tiny_fp32_full(m, oracle):
-    """BASELINE config 1 in full: fp32, n 2048, 4 q heads / 1 kv head, d 64, top-k 8 (1 init + 2 local)."""
+    """Workload C1 of synth.CONFIGS in full: fp32, n 2048, 4 q heads / 1 kv head, d 64, top-k 8 (1 init + 2 local)."""
     cfg = synth.CONFIGS["C1"]
     w = synth.make_config(cfg)
     gp, op = m.Params.from_config(cfg), oracle.Params.from_config(cfg)
@@ -249,7 +249,7 @@ def test_sparse_equals_dense_when_all_blocks_kept(m, oracle):
 
 
 def test_varlen_switch(m, oracle):
-    """Packed sequences on both sides of the dense/sparse threshold (the shape of BASELINE config 5, smaller)."""
+    """Packed sequences on both sides of the dense/sparse threshold (the shape of workload C5, smaller)."""
     lens = [100, 1024, 64, 2500, 1023, 1]
     w = synth.make_varlen(lens, 32, 2, 128, seed=77, dtype="bf16")
     gp, op = _params(m, oracle, "bf16", 32, 2, 128, n_init=1, n_local=4, topk_total=10, dense_threshold=1024)
@@ -395,7 +395,7 @@ def test_decode_many_pairs_launch_shape(m, oracle):
 
 
 def test_decode_c4_full_shape(m, oracle):
-    """BASELINE config 4 at full size: batch 16, context lengths uniform in [16384, 65536], top-k 64."""
+    """Workload C4 at full size: batch 16, context lengths uniform in [16384, 65536], top-k 64."""
     cfg = synth.CONFIGS["C4"]
     ctx = synth.draw_ctx_lens(cfg.batch, cfg.ctx_lo, cfg.ctx_hi, cfg.seed)
     w = synth.make_config(cfg, ctx_lens=ctx)
