@@ -66,6 +66,10 @@ def main() -> int:
     ap.add_argument("--probe-spread", action="store_true",
                     help="instead of the default line: the attention kernel on synthetic block lists whose entries have "
                          "four consumers each, spread over the SIMDs in three ways (timing only)")
+    ap.add_argument("--probe-regroup", action="store_true",
+                    help="instead of the default line: on the default workload's own selections, the size of a 16-token "
+                         "tile's block union for consecutive tokens and for tokens regrouped by overlap inside their "
+                         "64-token block (runs the selection on the GPU, the statistics on the host)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, to scale PMC byte counters)")
     args = ap.parse_args()
@@ -89,6 +93,9 @@ def main() -> int:
         return 0
     if args.probe_spread:
         print(json.dumps(probe_spread(torch, m, args.steps)))
+        return 0
+    if args.probe_regroup:
+        print(json.dumps(probe_regroup(torch, m, synth, args.workload)))
         return 0
     cfg = synth.CONFIGS[args.workload]
     gp = m.Params.from_config(cfg)
@@ -405,6 +412,51 @@ def probe_spread(torch, m, steps: int):
         torch.cuda.synchronize()
         res[mode] = {"ms": round(e0.elapsed_time(e1) / steps, 3), "token_block_units": units}
     return res
+
+
+def probe_regroup(torch, m, synth, workload: str, windows: int = 128):
+    """Would tiles made of the most-overlapping tokens be smaller than tiles of consecutive tokens?  Runs stages 1-3
+    on the workload, takes `windows` random 64-token query blocks per KV head (all their tokens share the causal
+    block and the forced blocks) and compares the mean block union of a 16-token tile for (a) consecutive tokens,
+    (b) tiles grown greedily -- start from the first free token, keep adding the free token that shares most blocks
+    with the tile so far.  The attention kernel's loads and lock-step both scale with that union."""
+    cfg = synth.CONFIGS[workload]
+    gp = m.Params.from_config(cfg)
+    w = synth.make_config(cfg)
+    q, k, v = (torch.from_numpy(w[x]).to(torch.bfloat16).cuda() for x in ("q", "k", "v"))
+    r = m.sparse_prefill(gp, q, k, v, m.SeqInfo(w["cu_seqlens"]), fused_pool=True)
+    torch.cuda.synchronize()
+    n = cfg.seq_len
+    rng = np.random.default_rng(1)
+    wins = np.sort(rng.choice(np.arange(32, n // 64), size=windows, replace=False))     # past the first 2048 tokens
+    rows = torch.from_numpy((wins[:, None] * 64 + np.arange(64)[None, :]).reshape(-1)).cuda()
+    idx = r["block_idx"][:, rows].cpu().numpy().reshape(cfg.num_kv_heads, windows, 64, -1)
+
+    def union(sets, group):
+        return len(frozenset().union(*[sets[t] for t in group]))
+
+    cons, greedy = [], []
+    for h in range(idx.shape[0]):
+        for wi in range(windows):
+            sets = [frozenset(int(j) for j in row if j >= 0) for row in idx[h, wi]]
+            cons += [union(sets, range(i, i + 16)) for i in range(0, 64, 16)]
+            left = set(range(64))
+            while left:
+                seed = min(left)
+                left.remove(seed)
+                grp, u = [seed], set(sets[seed])
+                while len(grp) < 16:
+                    best = max(left, key=lambda t: (len(u & sets[t]), -t))
+                    left.remove(best)
+                    grp.append(best)
+                    u |= sets[best]
+                greedy.append(len(u))
+    units = float((idx >= 0).sum()) / (idx.shape[0] * windows * 4)
+    return {"what": f"{workload}: block union of a 16-token tile, {windows} random 64-token query blocks per KV head",
+            "token_block_units_per_tile": round(units, 1),
+            "consecutive": {"union": round(float(np.mean(cons)), 1), "consumers_per_entry": round(units / float(np.mean(cons)), 2)},
+            "regrouped_by_overlap": {"union": round(float(np.mean(greedy)), 1),
+                                     "consumers_per_entry": round(units / float(np.mean(greedy)), 2)}}
 
 
 def budget_row(torch, m, q, k, v, si, n_init, n_local, total, steps, dense_ms):
