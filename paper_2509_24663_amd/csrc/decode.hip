@@ -696,7 +696,6 @@ __global__ void __launch_bounds__(NW * 64) dec_attn2_kernel(DecArgs a) {
     int *sel = reinterpret_cast<int *>(spk + kPkLds);        // [kSelMax] the top-k blocks (without the forced ones), ascending
     int(*hist)[256] = reinterpret_cast<int(*)[256]>(sel + kSelMax);     // [4][256]
     static_assert((kPkLds + kSelMax + 4 * 256) * 4 <= NW * TILE_ELEMS * 2, "selection state must fit in the V tiles");
-    constexpr int AW = NW;                                   // (shadows the four-kernel form's constant below)
     constexpr int NT = NW * 64;
     const int split = blockIdx.x, pair = blockIdx.y;
     const int b = pair / a.hkv;
@@ -706,7 +705,7 @@ __global__ void __launch_bounds__(NW * 64) dec_attn2_kernel(DecArgs a) {
     const bool dense = L < a.tk.dense_below;
     int32_t *out = a.idx != nullptr ? a.idx + (int64_t)pair * a.tk.topk_total : nullptr;
     int j = -1;
-    const int e = split * AW + w;
+    const int e = split * NW + w;
     if (dense) {
         j = e <= fo.bt ? e : -1;
         if (out != nullptr && split == 0)
@@ -717,7 +716,7 @@ __global__ void __launch_bounds__(NW * 64) dec_attn2_kernel(DecArgs a) {
         if (out != nullptr && split == 0)
             for (int i = tid; i < a.tk.topk_total; i += NT) out[i] = i < fo.nblk ? i : -1;
     } else {
-        if (split * AW >= fo.kr && !(out != nullptr && split == 0)) {
+        if (split * NW >= fo.kr && !(out != nullptr && split == 0)) {
             j = -1;                                        // nothing for this workgroup: an empty partial
         } else {
             // ---- radix select (4 x 8 bits) of the kr-th largest pooled key among the live blocks; selection rule
@@ -772,9 +771,9 @@ __global__ void __launch_bounds__(NW * 64) dec_attn2_kernel(DecArgs a) {
                 const bool lv = jb < fo.nblk && !fo.is_forced(jb);
                 const uint32_t key = lv ? pk[jb] : 0u;
                 int eq_tot, sel_tot;
-                const int eq_rank = eq_seen + wg_prefix_count_n<AW>(lv && key == thr, wave_tot, tid, eq_tot);
+                const int eq_rank = eq_seen + wg_prefix_count_n<NW>(lv && key == thr, wave_tot, tid, eq_tot);
                 const bool take = lv && (key > thr || (key == thr && eq_rank < need));
-                const int pos = written + wg_prefix_count_n<AW>(take, wave_tot, tid, sel_tot);
+                const int pos = written + wg_prefix_count_n<NW>(take, wave_tot, tid, sel_tot);
                 if (take) sel[pos] = jb;
                 written += sel_tot;
                 eq_seen += eq_tot;
