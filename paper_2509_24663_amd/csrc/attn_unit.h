@@ -366,22 +366,30 @@ __device__ inline void unit(Tok &t, uint32_t stage, uint32_t kx, uint32_t vx, in
     };
 #pragma unroll
     for (int n = 0; n < W; ++n) f[n] = frag(n);
+    // Products are issued in pairs, the later-fetched fragment first: LDS reads return in order, so the one wait
+    // for that fragment covers the pair (16 waits per unit instead of 32; a lone wave on a SIMD is bound by the
+    // number of instructions it has to issue).  The two products of a pair write different accumulators.
     // ---- exponents of the first half (8 products, 2 accumulators)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int kt = i & 1, s = i >> 1;
-        acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[i % W], t.qf[s], s == 0 ? zero : acc[kt], 0, 0, 0);
+    for (int i = 0; i < 8; i += 2) {
+        const int s = i >> 1;
+        acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[(i + 1) % W], t.qf[s], s == 0 ? zero : acc[1], 0, 0, 0);
+        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[i % W], t.qf[s], s == 0 ? zero : acc[0], 0, 0, 0);
         f[i % W] = frag(i + W);
+        f[(i + 1) % W] = frag(i + 1 + W);
         __builtin_amdgcn_sched_barrier(0);
     }
     // ---- second half's exponents || first half's probabilities
     float ls = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int kt = i & 1, s = i >> 1;
-        acc[2 + kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[(8 + i) % W], t.qf[s], s == 0 ? zero : acc[2 + kt], 0, 0, 0);
+    for (int i = 0; i < 8; i += 2) {
+        const int s = i >> 1;
+        acc[3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[(8 + i + 1) % W], t.qf[s], s == 0 ? zero : acc[3], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[(8 + i) % W], t.qf[s], s == 0 ? zero : acc[2], 0, 0, 0);
         f[(8 + i) % W] = frag(8 + i + W);
+        f[(8 + i + 1) % W] = frag(8 + i + 1 + W);
         ls += prob_step<OWN>(acc[0], acc[1], i, p, pb[0], t.cm, t.nr, key0, key_limit);
+        ls += prob_step<OWN>(acc[0], acc[1], i + 1, p, pb[0], t.cm, t.nr, key0, key_limit);
         __builtin_amdgcn_sched_barrier(0);
     }
     if (__any(!(ls < t.slack))) ls = move_reference(t, acc[0], acc[1], pb[0]);
@@ -389,19 +397,26 @@ __device__ inline void unit(Tok &t, uint32_t stage, uint32_t kx, uint32_t vx, in
     // ---- O^T += V^T P^T of the first half || second half's probabilities
     ls = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 8; i += 2) {
+        t.o[i + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[(16 + i + 1) % W], __builtin_bit_cast(bf16x8, pb[0]), t.o[i + 1], 0, 0, 0);
         t.o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[(16 + i) % W], __builtin_bit_cast(bf16x8, pb[0]), t.o[i], 0, 0, 0);
         f[(16 + i) % W] = frag(16 + i + W);
+        f[(16 + i + 1) % W] = frag(16 + i + 1 + W);
         ls += prob_step<OWN>(acc[2], acc[3], i, p, pb[1], t.cm, t.nr, key0 + 32, key_limit);
+        ls += prob_step<OWN>(acc[2], acc[3], i + 1, p, pb[1], t.cm, t.nr, key0 + 32, key_limit);
         __builtin_amdgcn_sched_barrier(0);
     }
     if (__any(!(ls < t.slack))) ls = move_reference(t, acc[2], acc[3], pb[1]);
     t.l += ls;
     // ---- second half
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 8; i += 2) {
+        t.o[i + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[(24 + i + 1) % W], __builtin_bit_cast(bf16x8, pb[1]), t.o[i + 1], 0, 0, 0);
         t.o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[(24 + i) % W], __builtin_bit_cast(bf16x8, pb[1]), t.o[i], 0, 0, 0);
-        if (i + W < 8) f[(24 + i) % W] = frag(24 + i + W);
+        if (i + W < 8) {
+            f[(24 + i) % W] = frag(24 + i + W);
+            f[(24 + i + 1) % W] = frag(24 + i + 1 + W);
+        }
         __builtin_amdgcn_sched_barrier(0);
     }
 }
