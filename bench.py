@@ -70,6 +70,10 @@ def main() -> int:
                     help="instead of the default line: on the default workload's own selections, the size of a 16-token "
                          "tile's block union for consecutive tokens and for tokens regrouped by overlap inside their "
                          "64-token block (runs the selection on the GPU, the statistics on the host)")
+    ap.add_argument("--probe-shared", action="store_true",
+                    help="instead of the default line: the attention kernel on the default workload as it is and with "
+                         "the query of a tile's first token repeated for the whole 16-token tile (the tile's tokens "
+                         "then select the same blocks): how much of the kernel's time is the workload's low sharing")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, to scale PMC byte counters)")
     args = ap.parse_args()
@@ -96,6 +100,9 @@ def main() -> int:
         return 0
     if args.probe_regroup:
         print(json.dumps(probe_regroup(torch, m, synth, args.workload)))
+        return 0
+    if args.probe_shared:
+        print(json.dumps(probe_shared(torch, m, synth, args.workload, args.steps)))
         return 0
     cfg = synth.CONFIGS[args.workload]
     gp = m.Params.from_config(cfg)
@@ -457,6 +464,43 @@ def probe_regroup(torch, m, synth, workload: str, windows: int = 128):
             "consecutive": {"union": round(float(np.mean(cons)), 1), "consumers_per_entry": round(units / float(np.mean(cons)), 2)},
             "regrouped_by_overlap": {"union": round(float(np.mean(greedy)), 1),
                                      "consumers_per_entry": round(units / float(np.mean(greedy)), 2)}}
+
+
+def probe_shared(torch, m, synth, workload: str, steps: int):
+    """The attention kernel on the workload's own inputs, and on the same K/V with queries that are shared inside
+    each group of 16 (one tile) or 64 (one query block) consecutive tokens, selections recomputed by stages 1-3:
+    same shape, same number of (token, block) units, smaller unions.  Timing only."""
+    cfg = synth.CONFIGS[workload]
+    gp = m.Params.from_config(cfg)
+    w = synth.make_config(cfg)
+    q, k, v = (torch.from_numpy(w[x]).to(torch.bfloat16).cuda() for x in ("q", "k", "v"))
+    n, hq, d = q.shape
+    si = m.SeqInfo(w["cu_seqlens"])
+    G = hq // cfg.num_kv_heads
+    res = {"what": f"{workload}: sparse_attn_fwd with the recipe's queries and with queries shared inside groups of tokens"}
+    for name, grp in (("recipe", 1), ("same_query_within_16_tokens", 16), ("same_query_within_64_tokens", 64)):
+        qq = q if grp == 1 else q.view(n // grp, grp, hq, d)[:, :1].expand(-1, grp, -1, -1).reshape(n, hq, d).contiguous()
+        b = m.sparse_prefill(gp, qq, k, v, si, fused_pool=True)
+        torch.cuda.synchronize()
+        e0, e1 = _events(torch, 2)
+        e0.record()
+        for _ in range(steps):
+            m.sparse_attn_fwd(gp, qq, k, v, b["block_idx"], si, out=b["out"], lse=b["lse"], workspace=b["ws_attn"])
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        idx = b["block_idx"]
+        nsel = (idx >= 0).sum(-1).to(torch.int64)
+        tpos = torch.arange(n, device="cuda")[None, :]
+        keys = int(((nsel - 1) * 64 + tpos % 64 + 1).sum())
+        flops = 4.0 * d * G * keys
+        i16 = idx[0].view(n // 16, -1)[:: 64]
+        union = float(np.mean([int((torch.unique(r[r >= 0])).numel()) for r in i16]))
+        res[name] = {"ms": round(ms, 3), "tflops": round(flops / ms / 1e9, 1),
+                     "frac_mfma_peak": round(flops / ms / 1e9 / PEAK_BF16_MFMA_TFLOPS, 4),
+                     "mean_union_of_a_tile": round(union, 1)}
+        del b
+    return res
 
 
 def budget_row(torch, m, q, k, v, si, n_init, n_local, total, steps, dense_ms):
