@@ -74,6 +74,10 @@ def main() -> int:
                     help="instead of the default line: the attention kernel on the default workload as it is and with "
                          "the query of a tile's first token repeated for the whole 16-token tile (the tile's tokens "
                          "then select the same blocks): how much of the kernel's time is the workload's low sharing")
+    ap.add_argument("--probe-clock", action="store_true",
+                    help="instead of the default line: where the waves of the attention kernel spend their time on the "
+                         "default workload; needs libinfllmv2_clock.so (python -m paper_2509_24663_amd.build --variant "
+                         "clock ATTN_TIMING_CLOCK), which writes clock readings in place of lse")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, to scale PMC byte counters)")
     args = ap.parse_args()
@@ -83,6 +87,8 @@ def main() -> int:
 
     import torch
 
+    if args.probe_clock:
+        args.lib = "clock"
     if args.lib:
         import paper_2509_24663_amd.binding as _binding
         _binding._LIB_PATH = os.path.join(ROOT, "paper_2509_24663_amd", f"libinfllmv2_{args.lib}.so")
@@ -103,6 +109,9 @@ def main() -> int:
         return 0
     if args.probe_shared:
         print(json.dumps(probe_shared(torch, m, synth, args.workload, args.steps)))
+        return 0
+    if args.probe_clock:
+        print(json.dumps(probe_clock(torch, m, synth, args.workload)))
         return 0
     cfg = synth.CONFIGS[args.workload]
     gp = m.Params.from_config(cfg)
@@ -464,6 +473,26 @@ def probe_regroup(torch, m, synth, workload: str, windows: int = 128):
             "consecutive": {"union": round(float(np.mean(cons)), 1), "consumers_per_entry": round(units / float(np.mean(cons)), 2)},
             "regrouped_by_overlap": {"union": round(float(np.mean(greedy)), 1),
                                      "consumers_per_entry": round(units / float(np.mean(greedy)), 2)}}
+
+
+def probe_clock(torch, m, synth, workload: str):
+    """Per-wave time in the attention kernel's main loop, from the library variant built with ATTN_TIMING_CLOCK (it
+    stores 100 MHz clock readings where lse would go): microseconds per 16-token tile, averaged over all waves."""
+    cfg = synth.CONFIGS[workload]
+    gp = m.Params.from_config(cfg)
+    w = synth.make_config(cfg)
+    q, k, v = (torch.from_numpy(w[x]).to(torch.bfloat16).cuda() for x in ("q", "k", "v"))
+    r = m.sparse_prefill(gp, q, k, v, m.SeqInfo(w["cu_seqlens"]), fused_pool=True)
+    torch.cuda.synchronize()
+    G = cfg.num_q_heads // cfg.num_kv_heads
+    lse = r["lse"].float()
+    names = ("issuing_copies", "in_units", "waiting_for_own_copies", "at_the_barrier", "main_loop")
+    res = {"what": f"{workload}: attn_tile_kernel main loop, us per tile and wave (mean over all waves)"}
+    for h in range(cfg.num_kv_heads):
+        row = {n: round(float(lse[h * G + i].mean()) * 1e-2, 1) for i, n in enumerate(names)}
+        row["intervals_per_tile"] = round(float(lse[h * G + 5].mean()), 1)
+        res[f"kv_head_{h}"] = row
+    return res
 
 
 def probe_shared(torch, m, synth, workload: str, steps: int):

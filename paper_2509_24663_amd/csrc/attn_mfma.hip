@@ -28,6 +28,9 @@
 // never defined in the library build): ATTN_TIMING_NO_LOADS leaves out the global -> LDS copies (every stage holds the
 // sequence's first block instead: real data, so the softmax takes its usual path and the operands toggle as usual), and
 // ATTN_TIMING_NO_BARRIER the barrier that ends an interval.  What the kernel's time is made of is measured with them.
+// A third one, ATTN_TIMING_CLOCK, keeps the outputs correct but writes, instead of lse, where each wave's time in the
+// main loop went (constant 100 MHz clock: issuing copies, units, waiting for its own copies, waiting at the barrier).
+// ATTN_TIMING_NEAR=N takes every copy from the sequence's first N blocks (are the copies bound by where they come from?).
 #include <type_traits>
 
 #include "attn_unit.h"
@@ -239,6 +242,9 @@ struct TileKernel {
         bool timing_fill = false;
 #endif
         auto issue_block = [&](int j, int stage_idx) {
+#ifdef ATTN_TIMING_NEAR
+            j = j == bt ? j : j % ATTN_TIMING_NEAR;       // timing experiment only: all copies come from a few blocks
+#endif
 #pragma unroll
             for (int p = 0; p < PPW; ++p) {
                 const int qi = w + p * NW;
@@ -297,6 +303,10 @@ struct TileKernel {
         // (every wave left that buffer before the barrier that ended interval i - 1).  The interval records are
         // read one iteration ahead, so their LDS latency hides behind the unit.
         int2 r_next = ni > 1 ? interval(1) : r_cur;
+#ifdef ATTN_TIMING_CLOCK
+        uint64_t ck_issue = 0, ck_units = 0, ck_wait = 0, ck_barrier = 0;
+        const uint64_t ck_start = wall_clock64();
+#endif
         __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
         __syncthreads();
         auto step = [&](auto own, int i) {
@@ -304,7 +314,14 @@ struct TileKernel {
             const int j0 = __builtin_amdgcn_readfirstlane(r_cur.x) & 0xffff;
             const uint32_t mks = (uint32_t)__builtin_amdgcn_readfirstlane(r_cur.y);
             const uint32_t mk0 = mks & 0xffffu, mk1 = SLOTS == 2 ? mks >> 16 : 0u;
+#ifdef ATTN_TIMING_CLOCK
+            const uint64_t ck0 = wall_clock64();
+#endif
             if (i + 1 < ni) issue_interval(r_next, (i + 1) & 1);
+#ifdef ATTN_TIMING_CLOCK
+            const uint64_t ck1 = wall_clock64();
+            ck_issue += ck1 - ck0;
+#endif
             r_cur = r_next;
             if (i + 2 < ni) r_next = interval(i + 2);
             const uint32_t stage = lds0 + (uint32_t)(((i & 1) * SLOTS) * STAGE_ELEMS * 2);
@@ -312,9 +329,20 @@ struct TileKernel {
             // identical operand reads of the two units above the branch and run out of registers)
             if ((mk0 >> w) & 1u) unit<OWN>(st, stage, kx, vx, lane, t0 + w - j0 * kBlock);
             if (SLOTS == 2 && ((mk1 >> w) & 1u)) unit<false>(st, stage + STAGE_ELEMS * 2, kx, vx, lane, 0);
+#ifdef ATTN_TIMING_CLOCK
+            const uint64_t ck2 = wall_clock64();
+            ck_units += ck2 - ck1;
+#endif
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);        // this wave's pieces of the next interval have landed
+#ifdef ATTN_TIMING_CLOCK
+            const uint64_t ck3 = wall_clock64();
+            ck_wait += ck3 - ck2;
+#endif
 #ifndef ATTN_TIMING_NO_BARRIER
             __syncthreads();
+#endif
+#ifdef ATTN_TIMING_CLOCK
+            ck_barrier += wall_clock64() - ck3;
 #endif
         };
         for (int i = 0; i < ni - 1; ++i) step(std::false_type{}, i);
@@ -335,8 +363,18 @@ struct TileKernel {
                 *reinterpret_cast<uint2 *>(op + dt * 16) = pk;
             }
             // log-sum-exp in natural units: the reference and the row sum are kept in powers of two
+#ifdef ATTN_TIMING_CLOCK
+            // timing experiment: instead of lse, heads 0-5 of the group get this wave's 100 MHz ticks spent issuing
+            // copies, in units, waiting for its own copies, at the barrier, in the whole main loop, and the
+            // number of intervals
+            if (a.lse != nullptr && g == 0 && m16 < 6) {
+                const uint64_t vals[6] = {ck_issue, ck_units, ck_wait, ck_barrier, wall_clock64() - ck_start, (uint64_t)ni};
+                a.lse[(int64_t)(h * G + m16) * a.map.total_rows + row0 + ti] = (float)vals[m16];
+            }
+#else
             if (a.lse != nullptr && g == 0)
                 a.lse[(int64_t)(h * G + m16) * a.map.total_rows + row0 + ti] = (__log2f(l) - st.nr) * 0.6931471805599453f;
+#endif
         }
     }
 };

@@ -4,7 +4,10 @@
 //   2. the attention unit of the library itself (attn_unit.h) run back to back on a resident LDS stage: time per unit
 //      of one wave (its latency) and per SIMD (throughput) for 1, 2 and 4 waves per SIMD;
 //   3. how fast a burst of N bytes streams from HBM, cold (rotating buffers) and warm, and what an empty dependent
-//      launch costs.
+//      launch costs;
+//   4. batches of global -> LDS copies as the attention kernel issues them (one workgroup of 16 waves per CU, B KB
+//      requested at once as 1 KB pieces from scattered 16 KB blocks, then waited for): time per batch against the
+//      bytes in flight, from a span that misses the caches, one that fits the memory-side cache and one that stays in L2.
 // Build: hipcc --offload-arch=gfx950 -O3 -std=c++17 -I include -I paper_2509_24663_amd/csrc
 //        -o paper_2509_24663_amd/probes/unit_limits paper_2509_24663_amd/probes/unit_limits.hip
 // (python paper_2509_24663_amd/build.py --probes does it).  Clocks are counted at the nominal 2.4 GHz.
@@ -187,6 +190,116 @@ int run_stream(std::vector<float4 *> &bufs, size_t bytes, float *out, bool cold)
     return 0;
 }
 
+
+// ---------------------------------------------------------------------------------------------- 4. LDS fills
+// PPW one-KB pieces per wave and batch (16 waves: 16 PPW KB per batch), each batch from 16-KB blocks chosen by a hash of
+// (workgroup, batch, block in batch) inside `span` bytes.
+template <int PPW>
+__global__ void __launch_bounds__(1024) fill_kernel(const char *src, uint32_t span_blocks, int batches, float *out) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+    for (int b = 0; b < batches; ++b) {
+#pragma unroll
+        for (int p = 0; p < PPW; ++p) {
+            const int q = w * PPW + p;                          // piece of the batch
+            const uint32_t blk = ((uint32_t)blockIdx.x * 2654435761u + (uint32_t)b * 40503u + (uint32_t)(q >> 4) * 2246822519u) % span_blocks;
+            const char *base = src + (size_t)blk * 16384 + (size_t)(q & 15) * 1024;
+            async_copy16(base, (uint32_t)lane * 16u, lds0 + (uint32_t)q * 1024u);
+        }
+        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+        __syncthreads();
+    }
+    if (out != nullptr && threadIdx.x == 0) out[blockIdx.x] = (float)smem[lane];
+}
+
+template <int PPW>
+int run_fill(const char *src, size_t span_bytes, float *out, const char *what) {
+    const int batches = 400, lds = 16 * PPW * 1024;
+    CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(fill_kernel<PPW>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0));
+    CHECK(hipEventCreate(&e1));
+    const uint32_t span_blocks = (uint32_t)(span_bytes / 16384);
+    hipLaunchKernelGGL(fill_kernel<PPW>, dim3(256), dim3(1024), lds, 0, src, span_blocks, batches, out);
+    CHECK(hipEventRecord(e0));
+    hipLaunchKernelGGL(fill_kernel<PPW>, dim3(256), dim3(1024), lds, 0, src, span_blocks, batches, out);
+    CHECK(hipEventRecord(e1));
+    CHECK(hipEventSynchronize(e1));
+    float ms;
+    CHECK(hipEventElapsedTime(&ms, e0, e1));
+    const double us = ms * 1e3 / batches, kb = 16.0 * PPW;
+    printf("fills %-22s %4.0f KB per batch and CU: %6.2f us per batch, %5.1f GB/s per CU, %5.2f TB/s over 256 CUs\n", what, kb, us,
+           kb * 1024 / us * 1e-3, kb * 1024 * 256 / us * 1e-6);
+    fflush(stdout);
+    return 0;
+}
+
+// The same 64 KB batches (into the upper half of a 128 KB buffer) while NU of the 16 waves run one attention unit per
+// batch on the lower half, as in the attention kernel: do the copies and the units' LDS reads get in each other's way?
+template <int NU, int UPB = 1, bool BARRIER = true>
+__global__ void __launch_bounds__(1024) fill_unit_kernel(const char *src, uint32_t span_blocks, int batches, int copies, float *out) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
+    for (int i = threadIdx.x; i < 2 * STAGE_ELEMS; i += blockDim.x) smem[i] = (uint16_t)(0x3c00 + ((i * 7) & 127));
+    __syncthreads();
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+    Tok st;
+    float cm;
+    int ce;
+    split_scale(0.0883883f * LOG2E, cm, ce);
+    for (int s = 0; s < 4; ++s) st.qf[s] = scale_q(make_uint4(0x3c003c00u + lane, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u), ce);
+    tok_init(st, cm);
+    const uint32_t kx = k_lane_bytes(lane), vx = v_lane_bytes(lane);
+    // the NU busy waves are spread over the four SIMDs (wave w sits on SIMD w % 4 of a 16-wave workgroup)
+    const bool busy = w < NU;
+    for (int b = 0; b < batches; ++b) {
+        if (copies) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int q = w * 4 + p;
+                const uint32_t blk = ((uint32_t)blockIdx.x * 2654435761u + (uint32_t)b * 40503u + (uint32_t)(q >> 4) * 2246822519u) % span_blocks;
+                const char *base = src + (size_t)blk * 16384 + (size_t)(q & 15) * 1024;
+                async_copy16(base, (uint32_t)lane * 16u, lds0 + (uint32_t)(2 * STAGE_ELEMS * 2) + (uint32_t)q * 1024u);
+            }
+        }
+        if (busy) {
+#pragma unroll 1
+            for (int u = 0; u < UPB; ++u) unit<false>(st, lds0 + (uint32_t)((b & 1) * STAGE_ELEMS * 2), kx, vx, lane, 0);
+        }
+        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+        if (BARRIER) __syncthreads();
+    }
+    float s = st.l;
+    for (int dt = 0; dt < 8; ++dt) s += st.o[dt][0] + st.o[dt][3];
+    if (out != nullptr) out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+template <int NU, int UPB = 1, bool BARRIER = true>
+int run_fill_unit(const char *src, size_t span_bytes, float *out, const char *what) {
+    const int batches = 400, lds = 128 * 1024;
+    CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_unit_kernel<NU, UPB, BARRIER>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0));
+    CHECK(hipEventCreate(&e1));
+    const uint32_t span_blocks = (uint32_t)(span_bytes / 16384);
+    double us[2];
+    for (int copies = 0; copies < 2; ++copies) {
+        hipLaunchKernelGGL((fill_unit_kernel<NU, UPB, BARRIER>), dim3(256), dim3(1024), lds, 0, src, span_blocks, batches, copies, out);
+        CHECK(hipEventRecord(e0));
+        hipLaunchKernelGGL((fill_unit_kernel<NU, UPB, BARRIER>), dim3(256), dim3(1024), lds, 0, src, span_blocks, batches, copies, out);
+        CHECK(hipEventRecord(e1));
+        CHECK(hipEventSynchronize(e1));
+        float ms;
+        CHECK(hipEventElapsedTime(&ms, e0, e1));
+        us[copies] = ms * 1e3 / batches;
+    }
+    printf("64 KB batch %-22s beside %2d waves with %d unit(s) each%s: %5.2f us per interval (units alone %5.2f us)\n", what, NU, UPB,
+           BARRIER ? "" : ", no barrier", us[1], us[0]);
+    fflush(stdout);
+    return 0;
+}
+
 int main() {
     float *d;
     CHECK(hipMalloc(&d, 512 * 1024 * 4));
@@ -215,6 +328,30 @@ int main() {
         for (size_t mb : {1, 36, 58, 67, 104, 290, 560})
             for (int cold = 1; cold >= 0; --cold)
                 if (run_stream(bufs, mb << 20, out, cold)) return 1;
+        printf("== 4. batches of global -> LDS copies (one 16-wave workgroup per CU, 1 KB pieces of scattered 16 KB blocks)\n");
+        const char *big0 = reinterpret_cast<const char *>(bufs[0]);
+        if (run_fill<1>(big0, big, d, "from 600 MB (misses)")) return 1;
+        if (run_fill<2>(big0, big, d, "from 600 MB (misses)")) return 1;
+        if (run_fill<4>(big0, big, d, "from 600 MB (misses)")) return 1;
+        if (run_fill<6>(big0, big, d, "from 600 MB (misses)")) return 1;
+        if (run_fill<8>(big0, big, d, "from 600 MB (misses)")) return 1;
+        if (run_fill<2>(big0, (size_t)64 << 20, d, "from 64 MB (MALL hits)")) return 1;
+        if (run_fill<4>(big0, (size_t)64 << 20, d, "from 64 MB (MALL hits)")) return 1;
+        if (run_fill<8>(big0, (size_t)64 << 20, d, "from 64 MB (MALL hits)")) return 1;
+        if (run_fill<2>(big0, (size_t)2 << 20, d, "from 2 MB (L2 hits)")) return 1;
+        if (run_fill<4>(big0, (size_t)2 << 20, d, "from 2 MB (L2 hits)")) return 1;
+        if (run_fill<8>(big0, (size_t)2 << 20, d, "from 2 MB (L2 hits)")) return 1;
+        for (size_t span : {(size_t)600 << 20, (size_t)64 << 20, (size_t)2 << 20}) {
+            const char *what = span > ((size_t)100 << 20) ? "from 600 MB (misses)" : span > ((size_t)4 << 20) ? "from 64 MB (MALL hits)" : "from 2 MB (L2 hits)";
+            if (run_fill_unit<0>(big0, span, d, what)) return 1;
+            if (run_fill_unit<4>(big0, span, d, what)) return 1;
+            if (run_fill_unit<8>(big0, span, d, what)) return 1;
+            if (run_fill_unit<16>(big0, span, d, what)) return 1;
+        }
+        if (run_fill_unit<4, 2>(big0, (size_t)64 << 20, d, "from 64 MB (MALL hits)")) return 1;
+        if (run_fill_unit<4, 4>(big0, (size_t)64 << 20, d, "from 64 MB (MALL hits)")) return 1;
+        if (run_fill_unit<4, 1, false>(big0, (size_t)64 << 20, d, "from 64 MB (MALL hits)")) return 1;
+        if (run_fill_unit<16, 2>(big0, (size_t)64 << 20, d, "from 64 MB (MALL hits)")) return 1;
     }
     return 0;
 }
