@@ -317,7 +317,17 @@ struct TileKernel {
 #ifdef ATTN_TIMING_CLOCK
             const uint64_t ck0 = wall_clock64();
 #endif
-            if (i + 1 < ni) issue_interval(r_next, (i + 1) & 1);
+            // A CU accepts the interval's 64 copies at ~64 bytes per clock and a wave's instructions issue in order, so
+            // a wave that issued its copies first would start its unit ~0.3 us late.  Waves without a unit in this
+            // interval issue at once; the others after the first products of their first unit.
+            const bool u0 = ((mk0 >> w) & 1u) != 0u, u1 = SLOTS == 2 && ((mk1 >> w) & 1u) != 0u;
+            bool to_issue = i + 1 < ni;
+            const int2 r_next_issue = r_next;
+            auto issue_now = [&]() {
+                if (to_issue) issue_interval(r_next_issue, (i + 1) & 1);
+                to_issue = false;
+            };
+            if (!(u0 || u1)) issue_now();
 #ifdef ATTN_TIMING_CLOCK
             const uint64_t ck1 = wall_clock64();
             ck_issue += ck1 - ck0;
@@ -327,8 +337,8 @@ struct TileKernel {
             const uint32_t stage = lds0 + (uint32_t)(((i & 1) * SLOTS) * STAGE_ELEMS * 2);
             // (consecutive tests rather than the arms of one branch: the compiler would otherwise merge the
             // identical operand reads of the two units above the branch and run out of registers)
-            if ((mk0 >> w) & 1u) unit<OWN>(st, stage, kx, vx, lane, t0 + w - j0 * kBlock);
-            if (SLOTS == 2 && ((mk1 >> w) & 1u)) unit<false>(st, stage + STAGE_ELEMS * 2, kx, vx, lane, 0);
+            if (u0) unit<OWN>(st, stage, kx, vx, lane, t0 + w - j0 * kBlock, issue_now);
+            if (u1) unit<false>(st, stage + STAGE_ELEMS * 2, kx, vx, lane, 0, issue_now);
 #ifdef ATTN_TIMING_CLOCK
             const uint64_t ck2 = wall_clock64();
             ck_units += ck2 - ck1;

@@ -348,8 +348,14 @@ __device__ inline float move_reference(Tok &t, f32x4 &a0, f32x4 &a1, u32x4 &pb) 
 // between the two groups of products, the waves of a workgroup, which start every unit together after a barrier,
 // all reach the softmax at the same time and the matrix core idles meanwhile.)  The order below is the issue
 // order: a scheduling fence after every step keeps the compiler from regrouping it.
-template <bool OWN>
-__device__ inline void unit(Tok &t, uint32_t stage, uint32_t kx, uint32_t vx, int lane, int key_limit) {
+struct NoMid {
+    __device__ inline void operator()() const {}
+};
+
+// `mid` is called once, after the first group of products has been issued: work of the caller that must not delay
+// the start of the unit but should be under way long before its end (the tile kernel issues its copies there).
+template <bool OWN, class Mid = NoMid>
+__device__ inline void unit(Tok &t, uint32_t stage, uint32_t kx, uint32_t vx, int lane, int key_limit, Mid mid = Mid()) {
     const int key0 = 8 * (lane >> 4);
     const uint32_t kb = stage + kx, vb = stage + vx;
     constexpr int W = 4;               // operand fetches run W products ahead, through all four groups of products
@@ -379,6 +385,7 @@ __device__ inline void unit(Tok &t, uint32_t stage, uint32_t kx, uint32_t vx, in
         f[(i + 1) % W] = frag(i + 1 + W);
         __builtin_amdgcn_sched_barrier(0);
     }
+    mid();
     // ---- second half's exponents || first half's probabilities
     float ls = 0.f;
 #pragma unroll
