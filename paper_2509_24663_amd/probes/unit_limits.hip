@@ -300,6 +300,47 @@ int run_fill_unit(const char *src, size_t span_bytes, float *out, const char *wh
     return 0;
 }
 
+// One LDS base (M0) per wave and batch, the four pieces told apart by the instruction's offset field (it advances the
+// global and the LDS address alike): does rewriting M0 between a wave's copies slow their issue?
+__global__ void __launch_bounds__(1024) fill_imm_kernel(const char *src, uint32_t span_blocks, int batches, float *out) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+    for (int b = 0; b < batches; ++b) {
+        // wave w copies 4 KB: quarter (w & 3) of the 16 KB block number (w >> 2) of the batch
+        const uint32_t blk = ((uint32_t)blockIdx.x * 2654435761u + (uint32_t)b * 40503u + (uint32_t)(w >> 2) * 2246822519u) % span_blocks;
+        const char *base = src + (size_t)blk * 16384 + (size_t)(w & 3) * 4096;
+        const uint32_t lds = lds0 + (uint32_t)w * 4096u, voff = (uint32_t)lane * 16u;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                     "global_load_lds_dwordx4 %1, %2\n\t"
+                     "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
+                     "global_load_lds_dwordx4 %1, %2 offset:2048\n\t"
+                     "global_load_lds_dwordx4 %1, %2 offset:3072" ::"s"(lds), "v"(voff), "s"(base) : "memory", "m0");
+        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+        __syncthreads();
+    }
+    if (out != nullptr && threadIdx.x == 0) out[blockIdx.x] = (float)smem[lane];
+}
+
+int run_fill_imm(const char *src, size_t span_bytes, float *out, const char *what) {
+    const int batches = 400, lds = 64 * 1024;
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0));
+    CHECK(hipEventCreate(&e1));
+    const uint32_t span_blocks = (uint32_t)(span_bytes / 16384);
+    hipLaunchKernelGGL(fill_imm_kernel, dim3(256), dim3(1024), lds, 0, src, span_blocks, batches, out);
+    CHECK(hipEventRecord(e0));
+    hipLaunchKernelGGL(fill_imm_kernel, dim3(256), dim3(1024), lds, 0, src, span_blocks, batches, out);
+    CHECK(hipEventRecord(e1));
+    CHECK(hipEventSynchronize(e1));
+    float ms;
+    CHECK(hipEventElapsedTime(&ms, e0, e1));
+    const double us = ms * 1e3 / batches;
+    printf("fills %-22s   64 KB per batch and CU, one M0 per wave: %6.2f us per batch, %5.1f GB/s per CU\n", what, us, 65536 / us * 1e-3);
+    fflush(stdout);
+    return 0;
+}
+
 int main() {
     float *d;
     CHECK(hipMalloc(&d, 512 * 1024 * 4));
@@ -341,6 +382,8 @@ int main() {
         if (run_fill<2>(big0, (size_t)2 << 20, d, "from 2 MB (L2 hits)")) return 1;
         if (run_fill<4>(big0, (size_t)2 << 20, d, "from 2 MB (L2 hits)")) return 1;
         if (run_fill<8>(big0, (size_t)2 << 20, d, "from 2 MB (L2 hits)")) return 1;
+        if (run_fill_imm(big0, (size_t)2 << 20, d, "from 2 MB (L2 hits)")) return 1;
+        if (run_fill_imm(big0, (size_t)64 << 20, d, "from 64 MB (MALL hits)")) return 1;
         for (size_t span : {(size_t)600 << 20, (size_t)64 << 20, (size_t)2 << 20}) {
             const char *what = span > ((size_t)100 << 20) ? "from 600 MB (misses)" : span > ((size_t)4 << 20) ? "from 64 MB (MALL hits)" : "from 2 MB (L2 hits)";
             if (run_fill_unit<0>(big0, span, d, what)) return 1;
