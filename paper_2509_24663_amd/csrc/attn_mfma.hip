@@ -319,7 +319,7 @@ struct TileKernel {
 #endif
             // A CU accepts the interval's 64 copies at ~64 bytes per clock and a wave's instructions issue in order, so
             // a wave that issued its copies first would start its unit ~0.3 us late.  Waves without a unit in this
-            // interval issue at once; the others after the first products of their first unit.
+            // interval issue at once; the others from inside their first unit, once its S^T products are out.
             const bool u0 = ((mk0 >> w) & 1u) != 0u, u1 = SLOTS == 2 && ((mk1 >> w) & 1u) != 0u;
             bool to_issue = i + 1 < ni;
             const int2 r_next_issue = r_next;

@@ -352,8 +352,9 @@ struct NoMid {
     __device__ inline void operator()() const {}
 };
 
-// `mid` is called once, after the first group of products has been issued: work of the caller that must not delay
-// the start of the unit but should be under way long before its end (the tile kernel issues its copies there).
+// `mid` is called once, after the second group of products (the S^T half of the unit) has been issued: work of the
+// caller that must not delay the start of the unit but should be under way well before its end (the tile kernel
+// issues its copies there).
 template <bool OWN, class Mid = NoMid>
 __device__ inline void unit(Tok &t, uint32_t stage, uint32_t kx, uint32_t vx, int lane, int key_limit, Mid mid = Mid()) {
     const int key0 = 8 * (lane >> 4);
@@ -385,7 +386,6 @@ __device__ inline void unit(Tok &t, uint32_t stage, uint32_t kx, uint32_t vx, in
         f[(i + 1) % W] = frag(i + 1 + W);
         __builtin_amdgcn_sched_barrier(0);
     }
-    mid();
     // ---- second half's exponents || first half's probabilities
     float ls = 0.f;
 #pragma unroll
@@ -401,6 +401,7 @@ __device__ inline void unit(Tok &t, uint32_t stage, uint32_t kx, uint32_t vx, in
     }
     if (__any(!(ls < t.slack))) ls = move_reference(t, acc[0], acc[1], pb[0]);
     t.l += ls;
+    mid();
     // ---- O^T += V^T P^T of the first half || second half's probabilities
     ls = 0.f;
 #pragma unroll
