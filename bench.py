@@ -491,6 +491,7 @@ def probe_clock(torch, m, synth, workload: str):
     for h in range(cfg.num_kv_heads):
         row = {n: round(float(lse[h * G + i].mean()) * 1e-2, 1) for i, n in enumerate(names)}
         row["intervals_per_tile"] = round(float(lse[h * G + 5].mean()), 1)
+        row["last_arriving_wave_barrier_to_barrier"] = round(float(lse[h * G + 6].mean()) * 1e-2, 1)
         res[f"kv_head_{h}"] = row
     return res
 

@@ -112,6 +112,10 @@ struct TileKernel {
         int2 *rec = reinterpret_cast<int2 *>(masks + a.nb_cap);          // union list: (block, token mask) per entry
         __shared__ int s_seq, s_tile, s_blk0, s_ne, s_ni;
         __shared__ uint32_t s_simd_waves[4];                             // waves (= tokens) resident on each SIMD
+#ifdef ATTN_TIMING_CLOCK
+        __shared__ uint32_t s_busy_ticks[2][NW];                         // per interval parity: each wave's ticks from the
+                                                                         // barrier to its arrival at the next one
+#endif
 
         const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
         const int h = blockIdx.y;
@@ -304,7 +308,7 @@ struct TileKernel {
         // read one iteration ahead, so their LDS latency hides behind the unit.
         int2 r_next = ni > 1 ? interval(1) : r_cur;
 #ifdef ATTN_TIMING_CLOCK
-        uint64_t ck_issue = 0, ck_units = 0, ck_wait = 0, ck_barrier = 0;
+        uint64_t ck_issue = 0, ck_units = 0, ck_wait = 0, ck_barrier = 0, ck_critical = 0;
         const uint64_t ck_start = wall_clock64();
 #endif
         __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
@@ -347,12 +351,18 @@ struct TileKernel {
 #ifdef ATTN_TIMING_CLOCK
             const uint64_t ck3 = wall_clock64();
             ck_wait += ck3 - ck2;
+            if (lane == 0) s_busy_ticks[i & 1][w] = (uint32_t)(ck3 - ck0);
 #endif
 #ifndef ATTN_TIMING_NO_BARRIER
             __syncthreads();
 #endif
 #ifdef ATTN_TIMING_CLOCK
             ck_barrier += wall_clock64() - ck3;
+            {   // the interval's last arrival: how long the wave that everybody waited for was under way
+                uint32_t mx = 0;
+                for (int k = 0; k < NW; ++k) mx = max(mx, s_busy_ticks[i & 1][k]);
+                ck_critical += mx;
+            }
 #endif
         };
         for (int i = 0; i < ni - 1; ++i) step(std::false_type{}, i);
@@ -374,11 +384,11 @@ struct TileKernel {
             }
             // log-sum-exp in natural units: the reference and the row sum are kept in powers of two
 #ifdef ATTN_TIMING_CLOCK
-            // timing experiment: instead of lse, heads 0-5 of the group get this wave's 100 MHz ticks spent issuing
-            // copies, in units, waiting for its own copies, at the barrier, in the whole main loop, and the
-            // number of intervals
-            if (a.lse != nullptr && g == 0 && m16 < 6) {
-                const uint64_t vals[6] = {ck_issue, ck_units, ck_wait, ck_barrier, wall_clock64() - ck_start, (uint64_t)ni};
+            // timing experiment: instead of lse, heads 0-6 of the group get this wave's 100 MHz ticks spent issuing
+            // copies, in units, waiting for its own copies, at the barrier, in the whole main loop, the number of
+            // intervals, and the sum over intervals of the last-arriving wave's ticks from barrier to barrier
+            if (a.lse != nullptr && g == 0 && m16 < 7) {
+                const uint64_t vals[7] = {ck_issue, ck_units, ck_wait, ck_barrier, wall_clock64() - ck_start, (uint64_t)ni, ck_critical};
                 a.lse[(int64_t)(h * G + m16) * a.map.total_rows + row0 + ti] = (float)vals[m16];
             }
 #else
