@@ -75,6 +75,73 @@ __global__ void __launch_bounds__(1024) mix_kernel(float *out, int iters) {
     out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// The same with 32x32x16 products (two tokens' 16 heads as the 32 columns): one 1 KB fragment feeds a product that
+// keeps the matrix core twice as long, and carries two tokens' vector work.  256 registers: 1 or 2 waves per SIMD.
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+template <int R, int M, int V, int X>
+__global__ void __launch_bounds__(512) mix32_kernel(float *out, int iters) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
+    for (int i = threadIdx.x; i < 32768; i += blockDim.x) lds[i] = (uint16_t)(0x3c00 + (i & 63));
+    __syncthreads();
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const uint16_t *base = lds + lane * 8;
+    f32x16 acc[4];
+    for (int i = 0; i < 4; ++i)
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    float x[8];
+    for (int i = 0; i < 8; ++i) x[i] = lane * 1e-3f + i;
+    bf16x8 b;
+    for (int i = 0; i < 8; ++i) b[i] = (__bf16)(1.0f + lane * 0.01f);
+    int off = w * 512;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            bf16x8 a[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) a[r] = *reinterpret_cast<const bf16x8 *>(base + ((off + (g * R + r) * 512) & 32767 & ~511));
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+                acc[(g * M + m) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m % R], b, acc[(g * M + m) & 3], 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < V; ++v) x[(g * V + v) & 7] = x[(g * V + v) & 7] * 0.999f + 0.5f;
+#pragma unroll
+            for (int e = 0; e < X; ++e) x[(g * X + e + 4) & 7] = __builtin_amdgcn_exp2f(x[(g * X + e + 4) & 7]);
+        }
+        off += 8 * R * 512 + 512;
+    }
+    float s = 0;
+    for (int i = 0; i < 4; ++i) s += acc[i][0] + acc[i][15];
+    for (int i = 0; i < 8; ++i) s += x[i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+template <int R, int M, int V, int X>
+int run_mix32(const char *name, float *d) {
+    const int iters = 2048, lds = 96 * 1024;
+    auto kf = mix32_kernel<R, M, V, X>;
+    CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kf), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0));
+    CHECK(hipEventCreate(&e1));
+    printf("%-44s", name);
+    for (int nw : {4, 8}) {
+        hipLaunchKernelGGL(kf, dim3(512), dim3(nw * 64), lds, 0, d, iters);
+        CHECK(hipEventRecord(e0));
+        hipLaunchKernelGGL(kf, dim3(512), dim3(nw * 64), lds, 0, d, iters);
+        CHECK(hipEventRecord(e1));
+        CHECK(hipEventSynchronize(e1));
+        float ms;
+        CHECK(hipEventElapsedTime(&ms, e0, e1));
+        const double clks = ms * 1e-3 * kClockHz / 2.0;
+        const double per_group = clks / (iters * 8.0 * (nw / 4));
+        // a 32x32x16 product is worth two 16x16x32 ones: 32 clocks at peak
+        printf(" | %d w/SIMD %5.1f clk per 32x32x16 product (%4.1f%% of peak)", nw / 4, per_group / M, 100.0 * M * 32.0 / per_group);
+    }
+    printf("\n");
+    fflush(stdout);
+    return 0;
+}
+
 template <int R, int M, int V, int X>
 int run_mix(const char *name, float *d) {
     const int iters = 2048, lds = 96 * 1024;         // 96 KB of LDS: one workgroup per CU
@@ -354,6 +421,9 @@ int main() {
     if (run_mix<2, 2, 3, 1>("2 reads : 2 products + 3 fma + 1 exp", d)) return 1;
     if (run_mix<1, 2, 3, 1>("1 read : 2 products + 3 fma + 1 exp", d)) return 1;
     if (run_mix<1, 4, 6, 2>("1 read : 4 products + 6 fma + 2 exp", d)) return 1;
+    if (run_mix32<1, 1, 0, 0>("32x32x16: 1 read : 1 product", d)) return 1;
+    if (run_mix32<1, 1, 3, 1>("32x32x16: 1 read : 1 product + 3 fma + 1 exp", d)) return 1;
+    if (run_mix32<2, 2, 6, 2>("32x32x16: 2 reads : 2 products + 6 fma + 2 exp", d)) return 1;
     printf("== 2. the library's attention unit on a resident LDS stage (32 products per unit: 512 clocks at peak)\n");
     if (run_unit(d)) return 1;
     printf("== 3. streaming reads (256-thread workgroups, 4 x 16 B per thread), 8 rotating buffers when cold\n");
