@@ -468,7 +468,48 @@ def probe_regroup(torch, m, synth, workload: str, windows: int = 128):
                     u |= sets[best]
                 greedy.append(len(u))
     units = float((idx >= 0).sum()) / (idx.shape[0] * windows * 4)
+
+    # Lock-step model of the tile kernel's main loop on the same lists: an interval of two entries lasts as long as
+    # its slowest wave (one unit of a wave alone on its SIMD 0.55 us, two units one after the other) or its busiest
+    # SIMD (0.33 us per unit when several waves share it; wave w sits on SIMD w % 4), plus 0.25 us per interval for
+    # the barrier, the copies' issue and the start of the unit.  Entries are paired inside ranges of 13 as the kernel
+    # does (first remaining entry + the one that raises the pair's busiest SIMD least).
+    def simd_units(mask):
+        return np.array([bin(mask & (0x1111 << sd)).count("1") for sd in range(4)])
+
+    def interval_us(m0, m1):
+        chain = 1.10 if (m0 & m1) else 0.55
+        return max(chain, float((simd_units(m0) + simd_units(m1)).max()) * 0.33) + 0.25
+
+    model = {"adjacent": [], "as_paired_by_the_kernel": []}
+    for h in range(idx.shape[0]):
+        for wi in range(0, windows, 4):
+            for tile in range(4):
+                masks = {}
+                for ti in range(16):
+                    for j in idx[h, wi, 16 * tile + ti]:
+                        if j >= 0:
+                            masks[int(j)] = masks.get(int(j), 0) | (1 << ti)
+                ms = [masks[k] for k in sorted(masks)]
+                body, own = ms[:-1], ms[-1]
+                t_adj = sum(interval_us(body[i], body[i + 1] if i + 1 < len(body) else 0) for i in range(0, len(body), 2))
+                t_pair = 0.0
+                for lo in range(0, len(body), 13):
+                    left = list(body[lo:lo + 13])
+                    while left:
+                        m0 = left.pop(0)
+                        if not left:
+                            t_pair += interval_us(m0, 0)
+                            break
+                        k = min(range(len(left)), key=lambda q: int((simd_units(m0) + simd_units(left[q])).max()))
+                        t_pair += interval_us(m0, left.pop(k))
+                model["adjacent"].append(t_adj + interval_us(own, 0))
+                model["as_paired_by_the_kernel"].append(t_pair + interval_us(own, 0))
+    tiles_per_cu = cfg.seq_len // 16 * cfg.num_kv_heads / 256.0
+    lock_step = {k: {"us_per_tile": round(float(np.mean(v)), 1), "ms_per_launch": round(float(np.mean(v)) * tiles_per_cu * 1e-3, 2)}
+                 for k, v in model.items()}
     return {"what": f"{workload}: block union of a 16-token tile, {windows} random 64-token query blocks per KV head",
+            "lock_step_model_of_the_main_loop": lock_step,
             "token_block_units_per_tile": round(units, 1),
             "consecutive": {"union": round(float(np.mean(cons)), 1), "consumers_per_entry": round(units / float(np.mean(cons)), 2)},
             "regrouped_by_overlap": {"union": round(float(np.mean(greedy)), 1),
