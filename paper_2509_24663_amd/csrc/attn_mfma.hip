@@ -202,6 +202,23 @@ struct TileKernel {
         auto pack = [](int j0, int mk0, int j1, int mk1) -> int2 {
             return make_int2((j0 & 0xffff) | (j1 << 16), (mk0 & 0xffff) | (mk1 << 16));
         };
+        if (!dense && SLOTS == 2) {
+            // the list becomes the list of packed interval records, in place (one thread per interval: ni <= NTHR
+            // because the list has at most T * topk_total + 1 <= 2 * NTHR entries, which the host checks), so that the
+            // main loop fetches a record with one LDS read and nothing to compute on it
+            int2 r0 = make_int2(NONE, 0), r1 = make_int2(NONE, 0);
+            if (tid < ni) {
+                if (tid == ni - 1) {
+                    r0 = rec[ne - 1];
+                } else {
+                    r0 = rec[2 * tid];
+                    if (2 * tid + 1 < ne - 1) r1 = rec[2 * tid + 1];
+                }
+            }
+            __syncthreads();
+            if (tid < ni) rec[tid] = pack(r0.x, r0.y, r1.x, r1.y);
+            __syncthreads();
+        }
         auto interval = [&](int i) -> int2 {
             if (dense) {
                 if (SLOTS == 1) return pack(i, (int)full, NONE, 0);
@@ -213,77 +230,78 @@ struct TileKernel {
                 const int2 r = rec[i];
                 return pack(r.x, r.y, NONE, 0);
             }
-            if (i == ni - 1) {
-                const int2 r = rec[ne - 1];
-                return pack(r.x, r.y, NONE, 0);
-            }
-            const int2 r0 = rec[2 * i];
-            const int2 r1 = 2 * i + 1 < ne - 1 ? rec[2 * i + 1] : make_int2(NONE, 0);
-            return pack(r0.x, r0.y, r1.x, r1.y);
+            return rec[i];
         };
 
-        // ---- loads: the 32 one-KB pieces of a block (16 of the K tile, 16 of the V^T tile) are dealt round-robin
-        // to the waves.  A piece's source is a wave-uniform base (sequence, head, block: scalar arithmetic) plus a
-        // per-lane byte offset that never changes, except that the sequence's last, partial K block re-reads its
-        // last valid row (finite data, always masked by causality); that block can only be the tile's own.  The
-        // V^T copy is zero-padded instead.
-        const uint64_t blk_bytes = (uint64_t)a.map.kv_tok_stride * (kBlock * sizeof(uint16_t));
+        // ---- loads: a block is 32 one-KB pieces (16 of the K tile: 4 rows each; 16 of the V^T tile: 8 rows each); wave w
+        // copies K piece w and V^T piece w of every block.  A piece's source is a wave-uniform base (sequence, head,
+        // block, piece: scalar arithmetic) plus a per-lane byte offset that never changes, except that the sequence's
+        // last, partial K block re-reads its last valid row (finite data, always masked by causality); that block can
+        // only be the tile's own, which is alone in the last interval.  The V^T copy is zero-padded instead.
+        //
+        // A wave's instructions issue in order, so whatever a wave with a unit in the current interval spends on the
+        // next interval's copies -- address arithmetic included -- delays that unit, and the interval lasts as long as
+        // its slowest wave: the code below is the shortest there is for four copies (every piece offset folded into
+        // per-wave constants, 32-bit block stride, the partial block handled by the last interval's own function).
+        static_assert(NW == 16, "wave w copies piece w of the 16 pieces of a tile");
+        constexpr uint32_t kTileBytes = TILE_ELEMS * 2, kStageBytes = STAGE_ELEMS * 2;
+        const uint32_t blk_bytes = (uint32_t)a.map.kv_tok_stride * (uint32_t)(kBlock * sizeof(uint16_t));   // < 2^31: the stride is < 2^24
         const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(stages));
         const int own_rows = len - bt * kBlock;          // rows of the tile's own block that exist (1..64 counts)
-        uint32_t loff[PPW];
-#pragma unroll
-        for (int p = 0; p < PPW; ++p) {
-            const int qi = w + p * NW;
-            if (qi < 16) {
-                int row, chunk;
-                k_piece_src(qi, lane, row, chunk);
-                loff[p] = (uint32_t)(row * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
-            } else {
-                loff[p] = vt_piece_src_bytes(qi - 16, lane);
-            }
+        uint32_t off_k_w, off_v_w;
+        {
+            int row, chunk;
+            k_piece_src(w, lane, row, chunk);
+            off_k_w = (uint32_t)((row - 4 * w) * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
+            off_v_w = vt_piece_src_bytes(w, lane) - (uint32_t)w * 1024u;
         }
+        const char *kb_w = reinterpret_cast<const char *>(kb) + (uint64_t)w * (blk_bytes / 16u);
+        const char *vtb_w = reinterpret_cast<const char *>(vtb) + (uint32_t)w * 1024u;
+        const uint32_t lds_w = lds0 + (uint32_t)w * 1024u;
 #ifdef ATTN_TIMING_NO_LOADS
         bool timing_fill = false;
 #endif
-        auto issue_block = [&](int j, int stage_idx) {
-#ifdef ATTN_TIMING_NEAR
-            j = j == bt ? j : j % ATTN_TIMING_NEAR;       // timing experiment only: all copies come from a few blocks
-#endif
-#pragma unroll
-            for (int p = 0; p < PPW; ++p) {
-                const int qi = w + p * NW;
-                const char *base = qi < 16 ? reinterpret_cast<const char *>(kb) + (uint64_t)j * blk_bytes
-                                           : reinterpret_cast<const char *>(vtb) + (uint64_t)j * (VT_TILE_ELEMS * sizeof(uint16_t));
-                const uint32_t dst = lds0 + (uint32_t)(stage_idx * STAGE_ELEMS + (qi < 16 ? 0 : TILE_ELEMS) + (qi & 15) * 512) * 2u;
-                uint32_t off = loff[p];
-                if (qi < 16 && j == bt && own_rows < kBlock) {        // the sequence's last, partial block
-                    int row, chunk;
-                    k_piece_src(qi, lane, row, chunk);
-                    off = (uint32_t)(min(row, own_rows - 1) * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
-                }
+        // this wave's sixteenth of the interval whose blocks are jj (two 16-bit block numbers), into buffer buf
+        auto issue = [&](uint32_t jj, int buf) {
 #ifdef ATTN_TIMING_NO_LOADS
-                if (!timing_fill) continue;             // timing experiment only (results are garbage)
+            if (!timing_fill) return;                   // timing experiment only (results are garbage)
 #endif
-                async_copy16(base, off, dst);
+            uint32_t j0 = jj & 0xffffu, j1 = jj >> 16;
+            const bool two = SLOTS == 2 && j1 != (uint32_t)NONE;
+#ifdef ATTN_TIMING_NEAR
+            j0 %= ATTN_TIMING_NEAR;                     // timing experiment only: all copies come from a few blocks
+            j1 %= ATTN_TIMING_NEAR;
+#endif
+            const uint32_t dst = lds_w + (uint32_t)buf * (SLOTS * kStageBytes);
+            async_copy16(kb_w + (uint64_t)j0 * blk_bytes, off_k_w, dst);
+            async_copy16(vtb_w + (j0 << 14), off_v_w, dst + kTileBytes);
+            if (two) {
+                async_copy16(kb_w + (uint64_t)j1 * blk_bytes, off_k_w, dst + kStageBytes);
+                async_copy16(vtb_w + (j1 << 14), off_v_w, dst + kStageBytes + kTileBytes);
             }
         };
-        auto issue_interval = [&](int2 r, int buf) {
-            const uint32_t jj = (uint32_t)__builtin_amdgcn_readfirstlane(r.x);
-            issue_block((int)(jj & 0xffffu), buf * SLOTS);
-            if (SLOTS == 2) {
-                const int j1 = (int)(jj >> 16);
-                if (j1 != NONE) issue_block(j1, buf * SLOTS + 1);
-            }
+        // the last interval: the tile's own block alone, possibly the sequence's partial last block
+        auto issue_last = [&](int buf) {
+#ifdef ATTN_TIMING_NO_LOADS
+            if (!timing_fill) return;
+#endif
+            const uint32_t dst = lds_w + (uint32_t)buf * (SLOTS * kStageBytes);
+            int row, chunk;
+            k_piece_src(w, lane, row, chunk);
+            const uint32_t off = (uint32_t)(min(row, own_rows - 1) * (int)a.map.kv_tok_stride + chunk * 8) * 2u;
+            async_copy16(reinterpret_cast<const char *>(kb) + (uint64_t)bt * blk_bytes, off, dst);
+            async_copy16(vtb_w + ((uint32_t)bt << 14), off_v_w, dst + kTileBytes);
         };
         int2 r_cur = ni > 0 ? interval(0) : make_int2(0, 0);
 #ifdef ATTN_TIMING_NO_LOADS
         // every stage holds the sequence's first block for the whole tile: real data (the softmax takes its usual
         // path, the matrix core sees operands that toggle as usual), but nothing is copied afterwards
         timing_fill = true;
-        for (int sidx = 0; sidx < NSTAGE; ++sidx) issue_block(0, sidx);
+        for (int b2 = 0; b2 < 2; ++b2) issue(0u, b2);
         timing_fill = false;
 #endif
-        if (ni > 0) issue_interval(r_cur, 0);
+        if (ni == 1) issue_last(0);
+        else if (ni > 1) issue((uint32_t)__builtin_amdgcn_readfirstlane(r_cur.x), 0);
 
         // ---- this wave's token
         Tok st;
@@ -325,11 +343,13 @@ struct TileKernel {
             // a wave that issued its copies first would start its unit ~0.3 us late.  Waves without a unit in this
             // interval issue at once; the others from inside their first unit, once its S^T products are out.
             const bool u0 = ((mk0 >> w) & 1u) != 0u, u1 = SLOTS == 2 && ((mk1 >> w) & 1u) != 0u;
-            bool to_issue = i + 1 < ni;
-            const int2 r_next_issue = r_next;
+            // 0: nothing to issue (any more); 1: the last interval; 2: any other
+            int mode = i + 1 >= ni ? 0 : i + 2 == ni ? 1 : 2;
+            const uint32_t jj_next = (uint32_t)__builtin_amdgcn_readfirstlane(r_next.x);
             auto issue_now = [&]() {
-                if (to_issue) issue_interval(r_next_issue, (i + 1) & 1);
-                to_issue = false;
+                if (mode == 1) issue_last((i + 1) & 1);
+                if (mode == 2) issue(jj_next, (i + 1) & 1);
+                mode = 0;
             };
             if (!(u0 || u1)) issue_now();
 #ifdef ATTN_TIMING_CLOCK
@@ -458,6 +478,7 @@ int launch_tile(const Launch &L, const AttnArgs &a0, const int32_t *cu_h) {
     const size_t lds = (size_t)2 * SLOTS * STAGE_ELEMS * sizeof(uint16_t) +
                        (size_t)a.nb_cap * 4 + (size_t)a.list_cap * 8;
     if (lds > 160 * 1024 - 256 || nb_max >= 0xffff) return INFLLMV2_ERR_UNSUPPORTED;     // does not fit: the caller pairs nothing
+    if (SLOTS == 2 && a.list_cap / 2 + 1 > NW * 64) return INFLLMV2_ERR_UNSUPPORTED;      // one thread packs one interval record
     auto kern = attn_tile_kernel<NW, SLOTS>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),

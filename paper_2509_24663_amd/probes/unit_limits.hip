@@ -304,7 +304,8 @@ int run_fill(const char *src, size_t span_bytes, float *out, const char *what) {
 
 // The same 64 KB batches (into the upper half of a 128 KB buffer) while NU of the 16 waves run one attention unit per
 // batch on the lower half, as in the attention kernel: do the copies and the units' LDS reads get in each other's way?
-template <int NU, int UPB = 1, bool BARRIER = true>
+// NCW < 16: the copies are issued by the last NCW waves alone (64 / NCW pieces each), which run no unit.
+template <int NU, int UPB = 1, bool BARRIER = true, int NCW = 16>
 __global__ void __launch_bounds__(1024) fill_unit_kernel(const char *src, uint32_t span_blocks, int batches, int copies, float *out) {
     extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
     for (int i = threadIdx.x; i < 2 * STAGE_ELEMS; i += blockDim.x) smem[i] = (uint16_t)(0x3c00 + ((i * 7) & 127));
@@ -321,10 +322,18 @@ __global__ void __launch_bounds__(1024) fill_unit_kernel(const char *src, uint32
     // the NU busy waves are spread over the four SIMDs (wave w sits on SIMD w % 4 of a 16-wave workgroup)
     const bool busy = w < NU;
     for (int b = 0; b < batches; ++b) {
-        if (copies) {
+        if (copies && NCW == 16) {
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const int q = w * 4 + p;
+                const uint32_t blk = ((uint32_t)blockIdx.x * 2654435761u + (uint32_t)b * 40503u + (uint32_t)(q >> 4) * 2246822519u) % span_blocks;
+                const char *base = src + (size_t)blk * 16384 + (size_t)(q & 15) * 1024;
+                async_copy16(base, (uint32_t)lane * 16u, lds0 + (uint32_t)(2 * STAGE_ELEMS * 2) + (uint32_t)q * 1024u);
+            }
+        }
+        if (copies && NCW < 16 && w >= 16 - NCW) {
+#pragma unroll
+            for (int q = w - (16 - NCW); q < 64; q += NCW) {
                 const uint32_t blk = ((uint32_t)blockIdx.x * 2654435761u + (uint32_t)b * 40503u + (uint32_t)(q >> 4) * 2246822519u) % span_blocks;
                 const char *base = src + (size_t)blk * 16384 + (size_t)(q & 15) * 1024;
                 async_copy16(base, (uint32_t)lane * 16u, lds0 + (uint32_t)(2 * STAGE_ELEMS * 2) + (uint32_t)q * 1024u);
@@ -342,27 +351,29 @@ __global__ void __launch_bounds__(1024) fill_unit_kernel(const char *src, uint32
     if (out != nullptr) out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
-template <int NU, int UPB = 1, bool BARRIER = true>
+template <int NU, int UPB = 1, bool BARRIER = true, int NCW = 16>
 int run_fill_unit(const char *src, size_t span_bytes, float *out, const char *what) {
     const int batches = 400, lds = 128 * 1024;
-    CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_unit_kernel<NU, UPB, BARRIER>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_unit_kernel<NU, UPB, BARRIER, NCW>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     hipEvent_t e0, e1;
     CHECK(hipEventCreate(&e0));
     CHECK(hipEventCreate(&e1));
     const uint32_t span_blocks = (uint32_t)(span_bytes / 16384);
     double us[2];
     for (int copies = 0; copies < 2; ++copies) {
-        hipLaunchKernelGGL((fill_unit_kernel<NU, UPB, BARRIER>), dim3(256), dim3(1024), lds, 0, src, span_blocks, batches, copies, out);
+        hipLaunchKernelGGL((fill_unit_kernel<NU, UPB, BARRIER, NCW>), dim3(256), dim3(1024), lds, 0, src, span_blocks, batches, copies, out);
         CHECK(hipEventRecord(e0));
-        hipLaunchKernelGGL((fill_unit_kernel<NU, UPB, BARRIER>), dim3(256), dim3(1024), lds, 0, src, span_blocks, batches, copies, out);
+        hipLaunchKernelGGL((fill_unit_kernel<NU, UPB, BARRIER, NCW>), dim3(256), dim3(1024), lds, 0, src, span_blocks, batches, copies, out);
         CHECK(hipEventRecord(e1));
         CHECK(hipEventSynchronize(e1));
         float ms;
         CHECK(hipEventElapsedTime(&ms, e0, e1));
         us[copies] = ms * 1e3 / batches;
     }
-    printf("64 KB batch %-22s beside %2d waves with %d unit(s) each%s: %5.2f us per interval (units alone %5.2f us)\n", what, NU, UPB,
-           BARRIER ? "" : ", no barrier", us[1], us[0]);
+    char who[48] = "";
+    if (NCW < 16) snprintf(who, sizeof who, ", copies issued by %d other waves", NCW);
+    printf("64 KB batch %-22s beside %2d waves with %d unit(s) each%s%s: %5.2f us per interval (units alone %5.2f us)\n", what, NU, UPB,
+           BARRIER ? "" : ", no barrier", who, us[1], us[0]);
     fflush(stdout);
     return 0;
 }
@@ -404,6 +415,69 @@ int run_fill_imm(const char *src, size_t span_bytes, float *out, const char *wha
     CHECK(hipEventElapsedTime(&ms, e0, e1));
     const double us = ms * 1e3 / batches;
     printf("fills %-22s   64 KB per batch and CU, one M0 per wave: %6.2f us per batch, %5.1f GB/s per CU\n", what, us, 65536 / us * 1e-3);
+    fflush(stdout);
+    return 0;
+}
+
+// NCW waves issue the batch's 64 one-KB copies alone, G copies per M0 write (G = 1: an M0 write before every copy; 4 and
+// 8: the instruction's offset field tells the copies of a group apart): how fast can one wave issue copies?
+template <int NCW, int G>
+__global__ void __launch_bounds__(1024) fill_group_kernel(const char *src, uint32_t span_blocks, int batches, float *out) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+    const uint32_t voff = (uint32_t)lane * 16u;
+    for (int b = 0; b < batches; ++b) {
+        if (w < NCW) {
+#pragma unroll
+            for (int q = w * (64 / NCW); q < (w + 1) * (64 / NCW); q += G) {     // pieces q .. q + G - 1: same 16 KB block
+                const uint32_t blk = ((uint32_t)blockIdx.x * 2654435761u + (uint32_t)b * 40503u + (uint32_t)(q >> 4) * 2246822519u) % span_blocks;
+                const char *base = src + (size_t)blk * 16384 + (size_t)(q & 15) * 1024;
+                const uint32_t lds = lds0 + (uint32_t)q * 1024u;
+                if (G == 1) {
+                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(base) : "memory", "m0");
+                } else if (G == 4) {
+                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                                 "global_load_lds_dwordx4 %1, %2\n\t"
+                                 "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
+                                 "global_load_lds_dwordx4 %1, %2 offset:2048\n\t"
+                                 "global_load_lds_dwordx4 %1, %2 offset:3072" ::"s"(lds), "v"(voff), "s"(base) : "memory", "m0");
+                } else {
+                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                                 "global_load_lds_dwordx4 %1, %2 offset:-4096\n\t"
+                                 "global_load_lds_dwordx4 %1, %2 offset:-3072\n\t"
+                                 "global_load_lds_dwordx4 %1, %2 offset:-2048\n\t"
+                                 "global_load_lds_dwordx4 %1, %2 offset:-1024\n\t"
+                                 "global_load_lds_dwordx4 %1, %2\n\t"
+                                 "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
+                                 "global_load_lds_dwordx4 %1, %2 offset:2048\n\t"
+                                 "global_load_lds_dwordx4 %1, %2 offset:3072" ::"s"(lds + 4096u), "v"(voff), "s"(base + 4096) : "memory", "m0");
+                }
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+        __syncthreads();
+    }
+    if (out != nullptr && threadIdx.x == 0) out[blockIdx.x] = (float)smem[lane];
+}
+
+template <int NCW, int G>
+int run_fill_group(const char *src, size_t span_bytes, float *out, const char *what) {
+    const int batches = 400, lds = 64 * 1024;
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0));
+    CHECK(hipEventCreate(&e1));
+    const uint32_t span_blocks = (uint32_t)(span_bytes / 16384);
+    hipLaunchKernelGGL((fill_group_kernel<NCW, G>), dim3(256), dim3(1024), lds, 0, src, span_blocks, batches, out);
+    CHECK(hipEventRecord(e0));
+    hipLaunchKernelGGL((fill_group_kernel<NCW, G>), dim3(256), dim3(1024), lds, 0, src, span_blocks, batches, out);
+    CHECK(hipEventRecord(e1));
+    CHECK(hipEventSynchronize(e1));
+    float ms;
+    CHECK(hipEventElapsedTime(&ms, e0, e1));
+    const double us = ms * 1e3 / batches;
+    printf("fills %-22s   64 KB per batch and CU issued by %2d waves, %d copies per M0 write: %6.2f us per batch, %5.1f GB/s per CU\n", what,
+           NCW, G, us, 65536 / us * 1e-3);
     fflush(stdout);
     return 0;
 }
@@ -465,6 +539,25 @@ int main() {
         if (run_fill_unit<4, 4>(big0, (size_t)64 << 20, d, "from 64 MB (MALL hits)")) return 1;
         if (run_fill_unit<4, 1, false>(big0, (size_t)64 << 20, d, "from 64 MB (MALL hits)")) return 1;
         if (run_fill_unit<16, 2>(big0, (size_t)64 << 20, d, "from 64 MB (MALL hits)")) return 1;
+        for (size_t span : {(size_t)64 << 20, (size_t)2 << 20}) {
+            const char *what = span > ((size_t)4 << 20) ? "from 64 MB (MALL hits)" : "from 2 MB (L2 hits)";
+            if (run_fill_group<1, 1>(big0, span, d, what)) return 1;
+            if (run_fill_group<1, 4>(big0, span, d, what)) return 1;
+            if (run_fill_group<1, 8>(big0, span, d, what)) return 1;
+            if (run_fill_group<2, 8>(big0, span, d, what)) return 1;
+            if (run_fill_group<4, 1>(big0, span, d, what)) return 1;
+            if (run_fill_group<4, 4>(big0, span, d, what)) return 1;
+            if (run_fill_group<4, 8>(big0, span, d, what)) return 1;
+            if (run_fill_group<8, 8>(big0, span, d, what)) return 1;
+            if (run_fill_group<16, 4>(big0, span, d, what)) return 1;
+            if (run_fill_unit<0, 1, true, 4>(big0, span, d, what)) return 1;
+            if (run_fill_unit<0, 1, true, 3>(big0, span, d, what)) return 1;
+            if (run_fill_unit<0, 1, true, 2>(big0, span, d, what)) return 1;
+            if (run_fill_unit<0, 1, true, 1>(big0, span, d, what)) return 1;
+            if (run_fill_unit<4, 1, true, 3>(big0, span, d, what)) return 1;
+            if (run_fill_unit<13, 1, true, 3>(big0, span, d, what)) return 1;
+            if (run_fill_unit<12, 1, true, 4>(big0, span, d, what)) return 1;
+        }
     }
     return 0;
 }
