@@ -110,6 +110,18 @@ __device__ inline float rows_sum(float x) {
     return __uint_as_float(q[0]) + __uint_as_float(q[1]);
 }
 
+// inclusive prefix sum over the 64 lanes of a wave in lane order, without LDS: shifts inside the 16-lane rows, then
+// the last lane of a row broadcast into the next row(s)
+__device__ inline int wave_inclusive_sum(int x) {
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, true);      // row_shr:1 (zero shifted in)
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, true);      // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, true);      // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, true);      // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);     // row_bcast:15 into rows 1 and 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);     // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
 // ------------------------------------------------------------------------------------------ scores
 __device__ inline void score_chunk(const DecArgs &a, int chunk, int pair) {
     const int b = pair / a.hkv, h = pair - b * a.hkv;
@@ -423,10 +435,11 @@ constexpr int AW = 8;              // waves (= selected blocks) per attend workg
 // h); the partial results are merged in LDS and written as partial `slot` of the pair.  Every thread of the
 // workgroup calls this (barriers inside); waves past NWV only help with the final sum.  smem: NWV tiles of 16 KB.
 template <int NWV>
-__device__ inline void attend_partial(const DecArgs &a, int pair, int slot, int j, uint16_t *smem, float (*wm)[16],
+__device__ inline void attend_partial(const DecArgs &a, int pair, int L, int slot, int j, uint16_t *smem, float (*wm)[16],
                                       float (*wl)[16]) {
+    // (L = ctx[b] comes from the caller: read again here, after the caller's stores, it would be a second trip to memory
+    // in front of the K/V loads)
     const int b = pair / a.hkv, h = pair - b * a.hkv;
-    const int L = a.ctx[b];
     const int t = L - 1, bt = t / kBlock;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m16 = lane & 15, g = lane >> 4;
@@ -525,7 +538,7 @@ __global__ void __launch_bounds__(AW * 64) dec_attn_kernel(DecArgs a) {
     if (L < a.tk.dense_below) j = e <= bt ? e : -1;
     else if (e < a.tk.topk_total) j = a.idx[(int64_t)pair * a.tk.topk_total + e];
     if (j > bt) j = -1;
-    attend_partial<AW>(a, pair, split, j, smem, wm, wl);
+    attend_partial<AW>(a, pair, L, split, j, smem, wm, wl);
 }
 
 // =========================================================================================== three-stage form
@@ -562,7 +575,7 @@ __global__ void __launch_bounds__(256) dec_front_kernel(DecArgs a) {
     const int e = f * FW + (int)(threadIdx.x >> 6);
     // (dense sequences attend to every block in the attend kernel; their forced slots stay empty)
     const int j = (L >= a.tk.dense_below && (int)(threadIdx.x >> 6) < FW && e < fo.n_forced) ? fo.forced_block(e) : -1;
-    attend_partial<FW>(a, pair, f, j, smem, wm, wl);
+    attend_partial<FW>(a, pair, L, f, j, smem, wm, wl);
 }
 
 __global__ void __launch_bounds__(256) dec_pool_kernel(DecArgs a) {
@@ -596,8 +609,23 @@ __global__ void __launch_bounds__(256) dec_pool_kernel(DecArgs a) {
     {   // log2 of sum_i 2^z per head from the chunk partials: 16 thread groups per head, then 16 -> 1
         const int head = tid & 15, pg = tid >> 4;
         const float *pp = a.part + (int64_t)pair * a.nchunk * 32 + head * 2;
+        // the first 64 chunks' partials (contexts up to 131072 tokens) are requested at once, beside the logits above:
+        // one trip to memory (a loop that loads as it goes makes one trip per iteration)
+        constexpr int PQ = 4;
+        float2 pq[PQ];
+#pragma unroll
+        for (int q = 0; q < PQ; ++q) pq[q] = *reinterpret_cast<const float2 *>(pp + min(pg + 16 * q, a.nchunk - 1) * 32);
         float mm = -INFINITY, ll = 0.f;
-        for (int ch = pg; ch < a.nchunk; ch += 16) {
+#pragma unroll
+        for (int q = 0; q < PQ; ++q)
+            if (pg + 16 * q < a.nchunk) mm = fmaxf(mm, pq[q].x);
+        {
+            const float ms = mm == -INFINITY ? 0.f : mm;
+#pragma unroll
+            for (int q = 0; q < PQ; ++q)
+                if (pg + 16 * q < a.nchunk) ll += pq[q].y * fast_exp2(pq[q].x - ms);
+        }
+        for (int ch = pg + 16 * PQ; ch < a.nchunk; ch += 16) {
             const float mo = pp[ch * 32], lo = pp[ch * 32 + 1];
             const float mn = fmaxf(mm, mo);
             const float ms = mn == -INFINITY ? 0.f : mn;
@@ -679,7 +707,8 @@ __device__ inline int wg_prefix_count_n(bool flag, int *wave_tot, int tid, int &
 }
 
 constexpr int kSelMax = 1024;               // top-k entries (topk_total <= 1024)
-constexpr int kPkLds = 4096;                // pooled keys kept in LDS (contexts up to 262144 tokens; longer: re-read)
+constexpr int kPkLds = 4096;                // pooled keys a workgroup keeps in registers (contexts up to 262144 tokens;
+                                            // longer rows are re-read from memory by every pass)
 
 // NW waves (= blocks) per workgroup: 8 when the launch has at most one workgroup per CU anyway, 4 when it has more
 // (64 KB of V tiles instead of 128: two workgroups share a CU and one's selection overlaps the other's loads).
@@ -691,11 +720,9 @@ __global__ void __launch_bounds__(NW * 64) dec_attn2_kernel(DecArgs a) {
     __shared__ uint32_t s_prefix;
     __shared__ int s_k;
     // the selection's state lives in the V tiles' memory: it is dead before the first tile is requested
-    uint32_t *spk = reinterpret_cast<uint32_t *>(smem);      // [kPkLds] the pair's pooled keys (read five times: four
-                                                             // radix passes, one emission)
-    int *sel = reinterpret_cast<int *>(spk + kPkLds);        // [kSelMax] the top-k blocks (without the forced ones), ascending
+    int *sel = reinterpret_cast<int *>(smem);                // [kSelMax] the top-k blocks (without the forced ones), ascending
     int(*hist)[256] = reinterpret_cast<int(*)[256]>(sel + kSelMax);     // [4][256]
-    static_assert((kPkLds + kSelMax + 4 * 256) * 4 <= NW * TILE_ELEMS * 2, "selection state must fit in the V tiles");
+    static_assert((kSelMax + 4 * 256) * 4 <= NW * TILE_ELEMS * 2, "selection state must fit in the V tiles");
     constexpr int NT = NW * 64;
     const int split = blockIdx.x, pair = blockIdx.y;
     const int b = pair / a.hkv;
@@ -718,14 +745,102 @@ __global__ void __launch_bounds__(NW * 64) dec_attn2_kernel(DecArgs a) {
     } else {
         if (split * NW >= fo.kr && !(out != nullptr && split == 0)) {
             j = -1;                                        // nothing for this workgroup: an empty partial
-        } else {
+        } else if (fo.nblk <= kPkLds) {
             // ---- radix select (4 x 8 bits) of the kr-th largest pooled key among the live blocks; selection rule
-            // and tie order as in the prefill: keys above it, then the first `need` keys equal to it by block number
+            // and tie order as in the prefill: keys above it, then the first `need` keys equal to it by block number.
+            // A thread keeps `per` consecutive blocks' keys in registers (one trip to memory, no copy in LDS); every
+            // wave reduces the histogram of a pass by itself (data-parallel scan, no LDS round trips), so a pass costs
+            // one barrier.
+            constexpr int KPT = kPkLds / NT;
             const uint32_t *pk = a.pk + (int64_t)pair * a.pk_cap;
-            if (fo.nblk <= kPkLds) {
-                for (int i = tid; i < fo.nblk; i += NT) spk[i] = pk[i];
-                pk = spk;
+            const int per = (fo.nblk + NT - 1) / NT, jb0 = tid * per;
+            uint32_t kreg[KPT];
+            uint32_t live = 0u;                              // bit u: block jb0 + u exists and takes part in the top-k
+#pragma unroll
+            for (int u = 0; u < KPT; ++u) {
+                const int jb = jb0 + u;
+                const bool lv = u < per && jb < fo.nblk && !fo.is_forced(jb);
+                kreg[u] = lv ? pk[jb] : 0u;
+                live |= lv ? 1u << u : 0u;
             }
+            for (int i = tid; i < 4 * 256; i += NT) (&hist[0][0])[i] = 0;
+            __syncthreads();
+            uint32_t prefix = 0u;
+            int k = fo.kr;
+            for (int pass = 3; pass >= 0; --pass) {
+                const int hi_shift = 8 * (pass + 1);
+#pragma unroll
+                for (int u = 0; u < KPT; ++u)
+                    if (((live >> u) & 1u) && (pass == 3 || (kreg[u] >> hi_shift) == prefix))
+                        atomicAdd(&hist[pass][(kreg[u] >> (8 * pass)) & 255u], 1);
+                __syncthreads();
+                // lane l owns digits 255 - 4l .. 252 - 4l, largest first; above = number of keys with a larger digit
+                int c[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) c[u] = hist[pass][255 - 4 * lane - u];
+                const int mine = c[0] + c[1] + c[2] + c[3];
+                int above = wave_inclusive_sum(mine) - mine;
+                int digit = 0, knew = 0;
+                bool found = false;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (above < k && k <= above + c[u]) {
+                        found = true;
+                        digit = 255 - 4 * lane - u;
+                        knew = k - above;
+                    }
+                    above += c[u];
+                }
+                const int src = max(__ffsll((long long)__ballot(found)) - 1, 0);     // exactly one lane (kr >= 1 keys exist)
+                prefix = (prefix << 8) | (uint32_t)__builtin_amdgcn_readlane(digit, src);
+                k = __builtin_amdgcn_readlane(knew, src);
+            }
+            const uint32_t thr = prefix;                     // the kr-th largest key; `need` of the keys equal to it are taken
+            const int need = k;
+            // emission in ascending block order: one prefix count over the threads for (keys above, keys equal)
+            int ca = 0, cb = 0;
+#pragma unroll
+            for (int u = 0; u < KPT; ++u) {
+                const bool lv = ((live >> u) & 1u) != 0u;
+                ca += lv && kreg[u] > thr ? 1 : 0;
+                cb += lv && kreg[u] == thr ? 1 : 0;
+            }
+            const int packed = ca | (cb << 16);
+            const int incl = wave_inclusive_sum(packed);
+            if (lane == 63) wave_tot[w] = incl;
+            __syncthreads();
+            int before = incl - packed;
+#pragma unroll
+            for (int q = 0; q < NW; ++q) before += q < w ? wave_tot[q] : 0;
+            int eq_before = before >> 16;
+            int pos = (before & 0xffff) + min(eq_before, need);
+#pragma unroll
+            for (int u = 0; u < KPT; ++u) {
+                if (!((live >> u) & 1u)) continue;
+                bool take = kreg[u] > thr;
+                if (kreg[u] == thr) {
+                    take = eq_before < need;
+                    ++eq_before;
+                }
+                if (take) sel[pos++] = jb0 + u;
+            }
+            __syncthreads();
+            j = e < fo.kr ? sel[e] : -1;
+            if (out != nullptr && split == 0) {
+                // the whole list, ascending: initial blocks, the top-k, the local blocks, then -1
+                const int n_loc = fo.n_forced - fo.f_init;
+                for (int i = tid; i < a.tk.topk_total; i += NT) {
+                    int val = -1;
+                    if (i < fo.f_init) val = i;
+                    else if (i < fo.f_init + fo.kr) val = sel[i - fo.f_init];
+                    else if (i < fo.f_init + fo.kr + n_loc) val = fo.forced_block(i - fo.kr);
+                    out[i] = val;
+                }
+            }
+            __syncthreads();                             // the V tiles may overwrite the selection's state now
+        } else {
+            // the same for rows too long for the registers: every pass re-reads the pooled keys from memory
+            const uint32_t *pk = a.pk + (int64_t)pair * a.pk_cap;
             for (int i = tid; i < 4 * 256; i += NT) (&hist[0][0])[i] = 0;
             if (tid == 0) { s_prefix = 0u; s_k = fo.kr; }
             __syncthreads();
@@ -781,7 +896,6 @@ __global__ void __launch_bounds__(NW * 64) dec_attn2_kernel(DecArgs a) {
             __syncthreads();
             j = e < fo.kr ? sel[e] : -1;
             if (out != nullptr && split == 0) {
-                // the whole list, ascending: initial blocks, the top-k, the local blocks, then -1
                 const int n_loc = fo.n_forced - fo.f_init;
                 for (int i = tid; i < a.tk.topk_total; i += NT) {
                     int val = -1;
@@ -795,62 +909,65 @@ __global__ void __launch_bounds__(NW * 64) dec_attn2_kernel(DecArgs a) {
         }
     }
     if (j > fo.bt) j = -1;
-    attend_partial<NW>(a, pair, a.fsplit + split, j, smem, wm, wl);
+    attend_partial<NW>(a, pair, L, a.fsplit + split, j, smem, wm, wl);
 }
 
 // ------------------------------------------------------------------------------------------ merge
-// Thread (head, group of 8 dims) combines the splits' partial results by itself, eight splits at a time with all of
-// their loads issued before the first use: no LDS, no barrier, one round trip to memory for the usual 8 splits.
-__global__ void __launch_bounds__(256) dec_merge_kernel(DecArgs a) {
+// Thread (head, group of 4 dims) combines the splits' partial results by itself, sixteen splits at a time with all of
+// their loads issued before the first use: no LDS, no barrier, one round trip to memory for up to 16 splits.
+constexpr int kMergeThreads = 512;
+__global__ void __launch_bounds__(kMergeThreads) dec_merge_kernel(DecArgs a) {
+    constexpr int R = 16;                              // splits per round
     const int pair = blockIdx.x;
     const int b = pair / a.hkv, h = pair - b * a.hkv;
     const int tid = threadIdx.x;
-    const int head = tid & 15, dg = tid >> 4;          // 16 heads x 16 groups of 8 dims
+    const int head = tid & 15, dq = tid >> 4;          // 16 heads x 32 groups of 4 dims
     const float c = a.scale * LOG2E;
     const float *ml = a.mlpart + (int64_t)pair * a.nslot * 32 + head * 2;
-    // dims 8 dg .. + 7 of this head are two 16-byte slots of a partial (see DecArgs::opart)
+    // dims 4 dq .. + 3 of this head are one 16-byte slot of a partial (see DecArgs::opart)
     const float4 *opb = reinterpret_cast<const float4 *>(a.opart + (int64_t)pair * a.nslot * OPART) +
-                        (dg >> 1) * 64 + (dg & 1) * 32 + head;
-    float mm = -INFINITY, ll = 0.f, o[8];
+                        (dq >> 2) * 64 + (dq & 3) * 16 + head;
+    float mm = -INFINITY, ll = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < a.nslot; s0 += R) {
+        float ms[R], ls[R];
+        float4 ov[R];
 #pragma unroll
-    for (int e2 = 0; e2 < 8; ++e2) o[e2] = 0.f;
-    for (int s0 = 0; s0 < a.nslot; s0 += 8) {
-        float ms[8], ls[8], ov[8][8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < R; ++u) {
             const int s = min(s0 + u, a.nslot - 1);        // past the end: re-read the last split, weight 0 below
-            ms[u] = ml[s * 32];
-            ls[u] = ml[s * 32 + 1];
-            const float4 lo4 = opb[(int64_t)s * (OPART / 4)], hi4 = opb[(int64_t)s * (OPART / 4) + 16];
-            ov[u][0] = lo4.x; ov[u][1] = lo4.y; ov[u][2] = lo4.z; ov[u][3] = lo4.w;
-            ov[u][4] = hi4.x; ov[u][5] = hi4.y; ov[u][6] = hi4.z; ov[u][7] = hi4.w;
+            const float2 m2 = *reinterpret_cast<const float2 *>(ml + s * 32);
+            ms[u] = m2.x;
+            ls[u] = m2.y;
+            ov[u] = opb[(int64_t)s * (OPART / 4)];
         }
+        // (every load above is requested before anything below is evaluated: with a branch in between the compiler
+        // requests the partial outputs only after the maxima have arrived -- two trips to memory instead of one)
+        __builtin_amdgcn_sched_barrier(0);
         float cm = mm;
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < R; ++u)
             if (s0 + u < a.nslot) cm = fmaxf(cm, ms[u]);
-        if (cm == -INFINITY) continue;                      // nothing attended to in these splits
-        const float resc = mm == -INFINITY ? 0.f : fast_exp2((mm - cm) * c);
+        const float cs = cm == -INFINITY ? 0.f : cm;        // nothing attended to so far: every weight below is 0
+        const float resc = mm == -INFINITY ? 0.f : fast_exp2((mm - cs) * c);
         ll *= resc;
 #pragma unroll
-        for (int e2 = 0; e2 < 8; ++e2) o[e2] *= resc;
+        for (int e2 = 0; e2 < 4; ++e2) o[e2] *= resc;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const float wg = s0 + u < a.nslot && ms[u] != -INFINITY ? fast_exp2((ms[u] - cm) * c) : 0.f;
+        for (int u = 0; u < R; ++u) {
+            const float wg = s0 + u < a.nslot && ms[u] != -INFINITY ? fast_exp2((ms[u] - cs) * c) : 0.f;
             ll += ls[u] * wg;
-#pragma unroll
-            for (int e2 = 0; e2 < 8; ++e2) o[e2] += ov[u][e2] * wg;
+            o[0] += ov[u].x * wg;
+            o[1] += ov[u].y * wg;
+            o[2] += ov[u].z * wg;
+            o[3] += ov[u].w * wg;
         }
         mm = cm;
     }
     const float inv = ll > 0.f ? 1.f / ll : 0.f;
-    uint4 pk;
+    uint2 pk;
     pk.x = (uint32_t)float_to_bf16(o[0] * inv) | ((uint32_t)float_to_bf16(o[1] * inv) << 16);
     pk.y = (uint32_t)float_to_bf16(o[2] * inv) | ((uint32_t)float_to_bf16(o[3] * inv) << 16);
-    pk.z = (uint32_t)float_to_bf16(o[4] * inv) | ((uint32_t)float_to_bf16(o[5] * inv) << 16);
-    pk.w = (uint32_t)float_to_bf16(o[6] * inv) | ((uint32_t)float_to_bf16(o[7] * inv) << 16);
-    *reinterpret_cast<uint4 *>(a.out + ((int64_t)b * a.hq + h * G + head) * D + dg * 8) = pk;
-    if (a.lse != nullptr && dg == 0) a.lse[(int64_t)b * a.hq + h * G + head] = mm * a.scale + __logf(ll);
+    *reinterpret_cast<uint2 *>(a.out + ((int64_t)b * a.hq + h * G + head) * D + dq * 4) = pk;
+    if (a.lse != nullptr && dq == 0) a.lse[(int64_t)b * a.hq + h * G + head] = mm * a.scale + __logf(ll);
 }
 
 inline size_t align_up(size_t x, size_t al) { return (x + al - 1) / al * al; }
@@ -980,7 +1097,7 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
             hipLaunchKernelGGL(dec_attn2_kernel<AW>, dim3(d.nsplit, pairs), dim3(AW * 64), attn_lds, stream, a);
         else
             hipLaunchKernelGGL(dec_attn2_kernel<AW / 2>, dim3(d.nsplit, pairs), dim3(AW * 32), attn_lds / 2, stream, a);
-        hipLaunchKernelGGL(dec_merge_kernel, dim3(pairs), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(dec_merge_kernel, dim3(pairs), dim3(kMergeThreads), 0, stream, a);
         return hip_status(hipGetLastError());
     }
 
@@ -999,7 +1116,7 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     hipLaunchKernelGGL(dec_scores_kernel, dim3(d.nchunk, pairs), dim3(256), 0, stream, a);
     hipLaunchKernelGGL(dec_select_kernel, dim3(pairs), dim3(SEL_THREADS), sel_lds, stream, a, sh_cap);
     hipLaunchKernelGGL(dec_attn_kernel, dim3(d.nsplit, pairs), dim3(AW * 64), attn_lds, stream, a);
-    hipLaunchKernelGGL(dec_merge_kernel, dim3(pairs), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(dec_merge_kernel, dim3(pairs), dim3(kMergeThreads), 0, stream, a);
     return hip_status(hipGetLastError());
 }
 
