@@ -561,7 +561,7 @@ constexpr int FW = 2;                       // forced blocks per front workgroup
 constexpr int PB = 64;                      // blocks per pool workgroup
 constexpr int kPoolKeysMax = 2048;          // compressed keys a pool workgroup may have to hold (pool_stride * 64 + pool_len)
 
-__global__ void __launch_bounds__(256) dec_front_kernel(DecArgs a) {
+__global__ void __launch_bounds__(256, 4) dec_front_kernel(DecArgs a) {
     extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];     // FW V tiles of 16 KB
     __shared__ float wm[FW][16], wl[FW][16];
     const int pair = blockIdx.y;
