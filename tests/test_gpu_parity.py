@@ -394,6 +394,40 @@ def test_decode_many_pairs_launch_shape(m, oracle):
     assert _check_decode(m, oracle, w, ctx, gp, op, "bf16") == 38 * 2
 
 
+def test_decode_selection_with_tied_scores(m, oracle):
+    """Key caches that repeat with a period of one or two blocks: the pooled scores of the blocks of one kind are equal
+    bit for bit (each logit is a dot product of the same numbers in the same order), so the k-th largest score is
+    shared by many blocks and Eq. 2's arg-max takes the lower block numbers among them -- the oracle's repeated arg-max
+    and the decode kernel's radix select + ordered emission must then give the same list, element for element.  With a
+    period of four blocks there are three or four kinds: the best is taken whole and only the first few of the next."""
+    hq, hkv, d = 32, 2, 128
+    ctx = [5000, 2300, 4100]
+    for period, topk_total in ((64, 12), (256, 30)):
+        w = synth.make_decode(ctx, hq, hkv, d, seed=93, dtype="bf16", max_len=5056)
+        kc = w["k_cache"]
+        for b, L in enumerate(ctx):
+            kc[b, :, :L] = np.tile(kc[b, :, :period], (1, (L + period - 1) // period, 1))[:, :L]
+        gp, op = _params(m, oracle, "bf16", hq, hkv, d, n_init=1, n_local=2, topk_total=topk_total)
+        q, kc_, vc_ = to_dev(w["q"], "bf16"), to_dev(kc, "bf16"), to_dev(w["v_cache"], "bf16")
+        kcc = torch.zeros((len(ctx), hkv, oracle.num_cmp(5056, op), d), dtype=torch.float32, device="cuda")
+        for b, L in enumerate(ctx):
+            kcb, _ = m.compress_k(gp, kc_[b, :, :L], [0, L])
+            kcc[b, :, :oracle.num_cmp(L, op)] = kcb[:, :oracle.num_cmp(L, op)]
+        out, lse, idx = m.sparse_decode(gp, q, kc_, vc_, kcc, ctx)
+        torch.cuda.synchronize()
+        ref = oracle.decode(w["q"], kc, w["v_cache"], ctx, op)
+        idx = to_np(idx)
+        # the ties are real: among the blocks the top-k chooses from there are far fewer distinct scores than blocks
+        G = hq // hkv
+        pos = np.array([ctx[0] - 1], np.int32)
+        sh = oracle.block_scores(w["q"][0:1, 0:G], pos, oracle.compress_k(kc[0, 0, :ctx[0]], op), op)
+        _, co = oracle.topk_blocks(sh, pos, op, return_cmp=True)
+        live = np.asarray(co)[0, 1:(ctx[0] - 1) // 64 - 2]
+        assert len(np.unique(live)) <= period // 64
+        np.testing.assert_array_equal(idx, ref["idx"])
+        assert_out_close(to_np(out), ref["out"], "bf16", "decode out, tied scores")
+
+
 def test_decode_c4_full_shape(m, oracle):
     """Workload C4 at full size: batch 16, context lengths uniform in [16384, 65536], top-k 64."""
     cfg = synth.CONFIGS["C4"]
