@@ -124,6 +124,20 @@ def test_sweep_budget_16_blocks_at_128k(m, oracle):
     _report("128K, 16 blocks, fused", _run_prefill_case(m, oracle, w, gp, op, "bf16", rows=rows, fused_pool=True))
 
 
+def test_c3_with_a_budget_of_136_blocks(m, oracle):
+    """At 128K tokens a 16-token tile's union list may then hold more than 2 * 1024 entries, more than one thread per
+    interval record can pack, and the tile kernel walks one entry per barrier interval instead of two (the same path
+    as for sequences whose block masks leave no room for four LDS stages).  Whole sparse path against the oracle on
+    sampled rows."""
+    import dataclasses
+    cfg = synth.CONFIGS["C3"]
+    w = synth.make_config(cfg)
+    gp = m.Params.from_config(cfg, n_init=1, n_local=8, topk_total=136)
+    op = dataclasses.replace(oracle.Params.from_config(cfg), n_init=1, n_local=8, topk_total=136)
+    rows = _sample_rows(w["cu_seqlens"], np.random.default_rng(136), 2, 160)
+    _report("128K, 136 blocks", _run_prefill_case(m, oracle, w, gp, op, "bf16", rows=rows, fused_pool=True))
+
+
 def test_sparse_attention_beyond_384k_tokens(m, oracle):
     """Past about 384K tokens the tile kernel's per-block masks leave no room for four LDS stages, and block lists
     are walked one entry per barrier interval instead of two.  Stage 4 alone on a 400K-token sequence with valid
