@@ -468,6 +468,15 @@ def probe_regroup(torch, m, synth, workload: str, windows: int = 128):
                     u |= sets[best]
                 greedy.append(len(u))
     units = float((idx >= 0).sum()) / (idx.shape[0] * windows * 4)
+    # how many of a consecutive tile's union entries have how many consumers among its 16 tokens
+    by_consumers = np.zeros(17)
+    for h in range(idx.shape[0]):
+        for wi in range(windows):
+            for tile in range(4):
+                blocks = idx[h, wi, 16 * tile:16 * tile + 16]
+                _, cnt = np.unique(blocks[blocks >= 0], return_counts=True)
+                by_consumers += np.bincount(cnt, minlength=17)[:17]
+    by_consumers /= idx.shape[0] * windows * 4
 
     # Lock-step model of the tile kernel's main loop on the same lists: an interval of two entries lasts as long as
     # its slowest wave (one unit of a wave alone on its SIMD 0.55 us, two units one after the other) or its busiest
@@ -511,6 +520,11 @@ def probe_regroup(torch, m, synth, workload: str, windows: int = 128):
     return {"what": f"{workload}: block union of a 16-token tile, {windows} random 64-token query blocks per KV head",
             "lock_step_model_of_the_main_loop": lock_step,
             "token_block_units_per_tile": round(units, 1),
+            "union_entries_per_tile_by_consumers": {"1": round(float(by_consumers[1]), 1), "2": round(float(by_consumers[2]), 1),
+                                                    "3-4": round(float(by_consumers[3:5].sum()), 1),
+                                                    "5-8": round(float(by_consumers[5:9].sum()), 1),
+                                                    "9-15": round(float(by_consumers[9:16].sum()), 1),
+                                                    "16": round(float(by_consumers[16]), 1)},
             "consecutive": {"union": round(float(np.mean(cons)), 1), "consumers_per_entry": round(units / float(np.mean(cons)), 2)},
             "regrouped_by_overlap": {"union": round(float(np.mean(greedy)), 1),
                                      "consumers_per_entry": round(units / float(np.mean(greedy)), 2)}}

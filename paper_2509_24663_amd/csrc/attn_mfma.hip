@@ -24,13 +24,14 @@
 // Schedule: the waves of a tile walk the union in lock step, one barrier per interval of two entries (dense: two
 // consecutive blocks), the next interval's blocks landing in the other half of a four-stage LDS buffer meanwhile.
 //
-// Two compile-time switches exist for timing experiments only (a build with either gives wrong results; they are
+// Compile-time switches exist for timing experiments only (a build with either gives wrong results; they are
 // never defined in the library build): ATTN_TIMING_NO_LOADS leaves out the global -> LDS copies (every stage holds the
 // sequence's first block instead: real data, so the softmax takes its usual path and the operands toggle as usual), and
 // ATTN_TIMING_NO_BARRIER the barrier that ends an interval.  What the kernel's time is made of is measured with them.
 // A third one, ATTN_TIMING_CLOCK, keeps the outputs correct but writes, instead of lse, where each wave's time in the
 // main loop went (constant 100 MHz clock: issuing copies, units, waiting for its own copies, waiting at the barrier).
 // ATTN_TIMING_NEAR=N takes every copy from the sequence's first N blocks (are the copies bound by where they come from?).
+// ATTN_TIMING_DROP_PRIVATE=C leaves the union entries with at most C consumers out of the walk (what do they cost?).
 #include <type_traits>
 
 #include "attn_unit.h"
@@ -177,7 +178,11 @@ struct TileKernel {
                 int base = 0;
                 for (int cbase = 0; cbase < nblk; cbase += 64) {
                     const int j = cbase + lane;
-                    const uint32_t mk = j < nblk ? masks[j] : 0u;
+                    uint32_t mk = j < nblk ? masks[j] : 0u;
+#ifdef ATTN_TIMING_DROP_PRIVATE
+                    // timing experiment only (results are wrong): entries with at most this many consumers are left out
+                    if (j != bt && __popc(mk) <= ATTN_TIMING_DROP_PRIVATE) mk = 0u;
+#endif
                     const uint64_t b = __ballot(mk != 0u);
                     if (mk != 0u) rec[base + __popcll(b & ((1ull << lane) - 1ull))] = make_int2(j, (int)mk);
                     base += __popcll(b);
