@@ -60,6 +60,7 @@ struct DecArgs {
     int pk_cap;
     int fsplit;        // partial-output slots taken by the forced blocks (attended beside the scores)
     int nslot;         // fsplit + nsplit
+    int bpw;           // blocks per attend workgroup (<= its number of waves): list entries split * bpw .. + bpw - 1
 };
 
 // Which blocks the newest token of an L-token sequence always keeps (Eq. 2: the first n_init and the last n_local
@@ -732,7 +733,7 @@ __global__ void __launch_bounds__(NW * 64) dec_attn2_kernel(DecArgs a) {
     const bool dense = L < a.tk.dense_below;
     int32_t *out = a.idx != nullptr ? a.idx + (int64_t)pair * a.tk.topk_total : nullptr;
     int j = -1;
-    const int e = split * NW + w;
+    const int e = w < a.bpw ? split * a.bpw + w : 1 << 30;       // (waves past bpw attend to nothing)
     if (dense) {
         j = e <= fo.bt ? e : -1;
         if (out != nullptr && split == 0)
@@ -743,7 +744,7 @@ __global__ void __launch_bounds__(NW * 64) dec_attn2_kernel(DecArgs a) {
         if (out != nullptr && split == 0)
             for (int i = tid; i < a.tk.topk_total; i += NT) out[i] = i < fo.nblk ? i : -1;
     } else {
-        if (split * NW >= fo.kr && !(out != nullptr && split == 0)) {
+        if (split * a.bpw >= fo.kr && !(out != nullptr && split == 0)) {
             j = -1;                                        // nothing for this workgroup: an empty partial
         } else if (fo.nblk <= kPkLds) {
             // ---- radix select (4 x 8 bits) of the kr-th largest pooled key among the live blocks; selection rule
@@ -977,7 +978,8 @@ struct DecLayout {
     size_t off_part, off_idx, off_opart, off_ml, total;
     // three-stage form
     bool staged;
-    int aw;                     // blocks per attend workgroup
+    int aw;                     // waves per attend workgroup
+    int bpw;                    // blocks per attend workgroup (<= aw)
     int fsplit, nslot, pk_cap;
     size_t off_pk;
 };
@@ -1003,6 +1005,17 @@ DecLayout dec_layout(const infllmv2_params *p, int batch, int max_ctx, int dense
     d.aw = d.staged && pairs * (size_t)((entries + AW - 1) / AW) > 256 ? AW / 2 : AW;
     d.nsplit = (entries + d.aw - 1) / d.aw;
     if (d.nsplit < 1) d.nsplit = 1;
+    d.bpw = d.aw;
+    if (d.staged && d.aw == AW) {
+        // one workgroup per CU at most: as many splits as fill the 256 CUs, each with fewer blocks (C4: 32 pairs x 8
+        // splits of 7 blocks instead of 7 splits of 8 -- every CU then pulls 7/8 of the bytes)
+        const int fit = (int)(256 / (pairs ? pairs : 1));
+        const int ns = fit < entries ? fit : entries;
+        if (ns > d.nsplit && ns <= 16 - ((p->n_init + p->n_local + FW - 1) / FW)) {
+            d.nsplit = ns;
+            d.bpw = (entries + ns - 1) / ns;
+        }
+    }
     d.fsplit = d.staged ? (p->n_init + p->n_local + FW - 1) / FW : 0;
     d.nslot = d.fsplit + d.nsplit;
     d.pk_cap = (int)align_up((size_t)(max_ctx + kBlock - 1) / kBlock + 4, 4);
@@ -1079,6 +1092,7 @@ int launch_decode_mfma(const infllmv2_params *p, const void *q, const void *k, c
     a.pk_cap = d.pk_cap;
     a.fsplit = d.fsplit;
     a.nslot = d.nslot;
+    a.bpw = d.bpw;
     const size_t attn_lds = (size_t)AW * TILE_ELEMS * sizeof(uint16_t);
     if (d.staged) {
         // Larger-than-default dynamic LDS has to be enabled per kernel; the same fixed limit is set on every call,
